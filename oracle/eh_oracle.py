@@ -1,0 +1,277 @@
+"""CPU fp64 oracle for early-exit head evaluation and DSSD greedy verification.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+HIP path is checked against.  It must never be imported by the product package;
+only tests, the smoke check and the benchmark's cpu_baseline leg call it.  It
+shares no code with the HIP path and imports nothing from it.
+
+Everything is computed in numpy float64, two-pass, with the logits of a head
+materialised in full -- the exact opposite of the streamed, fused, low-precision
+formulation the kernels use.
+
+What each function follows (arXiv 2407.21082):
+
+* ``head_logits`` / ``layernorm``: Section 3.2, "Implementation Details": an
+  exit head has the structure of the model's final classification head and is
+  fed the hidden features of a transformer block.  For the Pythia family that
+  is a LayerNorm followed by a bias-free d -> |V| linear map.
+* ``softmax_stats``: Section 3.4.1: the confidence metric is the entropy of the
+  predicted distribution, H(p) = -sum_j p_j log p_j (natural log, 0 log 0 = 0);
+  eq. (2) uses argmax p, taken here with the lowest index on ties.
+* ``exit_rule``: Section 3.4.2 (exit at the first head whose confidence passes
+  its threshold, otherwise the full model's output) in the entropy form of
+  Section 4.3.1, "Drafting phase": first head with H(p_k) < tau_k.
+* ``dssd_verify``: Section 4.3.1, "Verification phase": every drafted token is
+  compared with the full model's greedy prediction for its position; the
+  accepted prefix is committed and the first mismatch is replaced by the
+  full-model token.
+
+Readings taken where the paper is silent (LayerNorm epsilon, biased variance,
+where bf16 rounding happens, strict inequality, alignment of draft and target
+positions) are listed in the repository's design notes; the ones that matter
+here are repeated in the docstrings.
+
+Parity pins: every function in this file is pinned by the CPU tests (closed
+forms, invariants, exhaustive enumeration on tiny cases).  No function is
+"parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "bf16_bits_to_f64",
+    "round_to_bf16",
+    "f64_to_bf16_bits",
+    "layernorm",
+    "head_logits",
+    "softmax_stats",
+    "head_eval",
+    "exit_rule",
+    "cascade",
+    "dssd_verify",
+    "accepted_prefix",
+]
+
+
+# ----------------------------------------------------------------------------
+# bf16 <-> fp64 (storage format only; bf16 = sign, 8 exponent bits, 7 mantissa
+# bits, i.e. the upper half of an IEEE binary32)
+# ----------------------------------------------------------------------------
+def bf16_bits_to_f64(bits) -> np.ndarray:
+    """Exact value of bf16 bit patterns (uint16 array) as float64."""
+    b = np.asarray(bits, dtype=np.uint16)
+    as32 = (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    with np.errstate(invalid="ignore"):      # signalling-NaN patterns
+        return as32.astype(np.float64)
+
+
+def round_to_bf16(x) -> np.ndarray:
+    """Round float64 values to the nearest bf16-representable value, ties to
+    even, returned as float64.
+
+    Written from the definition of the format, not by bit tricks: a finite
+    non-zero x with binary exponent e = floor(log2|x|) lies on a grid of
+    spacing 2**(max(e, -126) - 7) (8 significant bits; below 2**-126 the grid
+    is the subnormal one).  x / spacing is exact in fp64 (power-of-two scale),
+    ``np.rint`` rounds half to even, and multiplying back is exact.  Results of
+    magnitude >= 2**128 overflow to infinity.  NaN and +-inf pass through.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    out = x.copy()
+    fin = np.isfinite(x) & (x != 0.0)
+    if np.any(fin):
+        xf = x[fin]
+        _, ex = np.frexp(xf)              # xf = m * 2**ex with 0.5 <= |m| < 1
+        e = ex.astype(np.int64) - 1        # floor(log2|xf|)
+        q = np.ldexp(1.0, (np.maximum(e, -126) - 7).astype(np.int64))
+        r = np.rint(xf / q) * q
+        r = np.where(np.abs(r) >= np.ldexp(1.0, 128), np.copysign(np.inf, xf), r)
+        out[fin] = r
+    return out
+
+
+def f64_to_bf16_bits(x) -> np.ndarray:
+    """bf16 bit patterns (uint16) of values already representable in bf16."""
+    x32 = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u = x32.view(np.uint32)
+    if np.any((u & np.uint32(0xFFFF)) != 0):
+        raise ValueError("value is not bf16-representable")
+    return (u >> np.uint32(16)).astype(np.uint16)
+
+
+# ----------------------------------------------------------------------------
+# One head
+# ----------------------------------------------------------------------------
+def layernorm(h, gamma, beta, eps=1e-5, bf16_out=False) -> np.ndarray:
+    """LayerNorm over the last axis in fp64, two-pass, biased variance:
+    mu = mean(h); var = mean((h - mu)^2); y = gamma*(h - mu)/sqrt(var+eps)+beta.
+
+    ``bf16_out`` rounds y to bf16 (ties to even): in bf16 mode the normalised
+    activations are the low-precision operand of the projection, and both
+    sides of the parity check agree that this is where the rounding happens.
+    """
+    h = np.asarray(h, dtype=np.float64)
+    gamma = np.asarray(gamma, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    d = h.shape[-1]
+    mu = h.sum(axis=-1, keepdims=True) / d
+    c = h - mu
+    var = (c * c).sum(axis=-1, keepdims=True) / d
+    y = gamma * (c / np.sqrt(var + eps)) + beta
+    if bf16_out:
+        y = round_to_bf16(y)
+    return y
+
+
+def head_logits(y, W, bias=None) -> np.ndarray:
+    """z[r, i] = sum_j W[i, j] * y[r, j] (+ bias[i]); W is [V, d]."""
+    y = np.asarray(y, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    z = y @ W.T
+    if bias is not None:
+        z = z + np.asarray(bias, dtype=np.float64)
+    return z
+
+
+def softmax_stats(z):
+    """Entropy, log-sum-exp, argmax and top-2 gap of each row of logits.
+
+    Two passes over materialised logits, straight from the definitions:
+    m = max z; S = sum exp(z - m); lse = m + log S; p = exp(z - lse);
+    H = -sum_{p>0} p * log p with log p = z - lse; argmax = lowest index
+    attaining m; gap = m - (second largest logit, counting multiplicity).
+    Returns (H, lse, argmax, gap); a NaN anywhere in a row gives NaN H/lse.
+    """
+    z = np.asarray(z, dtype=np.float64)
+    if z.ndim == 1:
+        z = z[None, :]
+    R, V = z.shape
+    H = np.empty(R)
+    lse = np.empty(R)
+    am = np.empty(R, dtype=np.int64)
+    gap = np.empty(R)
+    for r in range(R):
+        zr = z[r]
+        m = zr.max()
+        if not np.isfinite(m):
+            H[r] = lse[r] = gap[r] = np.nan
+            am[r] = -1
+            continue
+        S = np.exp(zr - m).sum()
+        L = m + np.log(S)
+        logp = zr - L
+        p = np.exp(logp)
+        keep = p > 0.0
+        H[r] = -(p[keep] * logp[keep]).sum()
+        lse[r] = L
+        am[r] = np.flatnonzero(zr == m)[0]
+        if V > 1:
+            rest = np.delete(zr, am[r])
+            gap[r] = m - rest.max()
+        else:
+            gap[r] = np.inf
+    return H, lse, am, gap
+
+
+def head_eval(h, gamma, beta, W, eps=1e-5, bf16=False, bias=None):
+    """LayerNorm -> projection -> softmax statistics for rows h [R, d].
+
+    Inputs are the very values the device receives, already widened to fp64
+    (bf16 inputs via ``bf16_bits_to_f64``).  Returns (H, lse, argmax, gap).
+    """
+    y = layernorm(h, gamma, beta, eps, bf16_out=bf16)
+    z = head_logits(y, W, bias)
+    return softmax_stats(z)
+
+
+# ----------------------------------------------------------------------------
+# Exit rule and cascade
+# ----------------------------------------------------------------------------
+def exit_rule(H_by_head, tau) -> int:
+    """Index of the head a token exits at: the first k < n_heads-1 with
+    H_k < tau_k (strict), else the last head, which stands for the full model
+    and always answers.  NaN entropies never pass the test."""
+    n = len(H_by_head)
+    for k in range(n - 1):
+        if H_by_head[k] < tau[k]:
+            return k
+    return n - 1
+
+
+def cascade(h_layers, gammas, betas, Ws, tau, eps=1e-5, bf16=False):
+    """Dynamic-exit inference for R independent rows.
+
+    h_layers[l] is [R, d], the hidden state each head sees.  Heads are visited
+    shallow to deep; head l is evaluated only on the rows that have not yet
+    exited (the increasing list of their indices is the active list after
+    compaction).  Returns dict with exit_layer[R], token[R], H[n_heads, R],
+    lse, argmax, gap (NaN / -1 where a row was no longer active) and
+    active[l] = the index list head l was evaluated on.
+    """
+    n_heads = len(Ws)
+    R = np.asarray(h_layers[0]).shape[0]
+    H = np.full((n_heads, R), np.nan)
+    lse = np.full((n_heads, R), np.nan)
+    am = np.full((n_heads, R), -1, dtype=np.int64)
+    gap = np.full((n_heads, R), np.nan)
+    exit_layer = np.full(R, -1, dtype=np.int64)
+    token = np.full(R, -1, dtype=np.int64)
+    active = np.arange(R)
+    actives = []
+    for l in range(n_heads):
+        actives.append(active.copy())
+        if active.size == 0:
+            continue
+        hl = np.asarray(h_layers[l], dtype=np.float64)[active]
+        Hl, Ll, Al, Gl = head_eval(hl, gammas[l], betas[l], Ws[l], eps, bf16)
+        H[l, active], lse[l, active], am[l, active], gap[l, active] = Hl, Ll, Al, Gl
+        still = []
+        for pos, r in enumerate(active):
+            leaves = (l == n_heads - 1) or (Hl[pos] < tau[l])
+            if leaves:
+                exit_layer[r] = l
+                token[r] = Al[pos]
+            else:
+                still.append(r)
+        active = np.asarray(still, dtype=np.int64)
+    return dict(exit_layer=exit_layer, token=token, H=H, lse=lse, argmax=am,
+                gap=gap, active=actives)
+
+
+# ----------------------------------------------------------------------------
+# DSSD greedy verification
+# ----------------------------------------------------------------------------
+def accepted_prefix(draft_row, target_row, length) -> int:
+    """Largest n <= length with draft[j] == target[j] for every j < n."""
+    n = 0
+    while n < length and int(draft_row[n]) == int(target_row[n]):
+        n += 1
+    return n
+
+
+def dssd_verify(f_final, draft, gamma, beta, W, draft_len=None, eps=1e-5, bf16=False):
+    """Greedy verification of drafted tokens against the full model.
+
+    f_final [B, k+1, d]: the full model's final hidden state at the position
+    preceding each draft token (j = 0..k-1) plus the one after the last draft
+    (j = k); draft [B, k].  target[b, j] is the final head's argmax on
+    f_final[b, j]; accepted[b] is the length of the longest matching prefix
+    (bounded by draft_len[b]); next_token[b] = target[b, accepted[b]] is the
+    token written at the first mismatch, or the bonus token when every draft
+    token is accepted.  Returns (accepted, next_token, target, gap).
+    """
+    f = np.asarray(f_final, dtype=np.float64)
+    B, k1, d = f.shape
+    k = k1 - 1
+    draft = np.asarray(draft)
+    _, _, am, gap = head_eval(f.reshape(B * k1, d), gamma, beta, W, eps, bf16)
+    target = am.reshape(B, k1)
+    gap = gap.reshape(B, k1)
+    accepted = np.zeros(B, dtype=np.int64)
+    nxt = np.zeros(B, dtype=np.int64)
+    for b in range(B):
+        L = k if draft_len is None else int(draft_len[b])
+        accepted[b] = accepted_prefix(draft[b], target[b], L)
+        nxt[b] = target[b, accepted[b]]
+    return accepted, nxt, target, gap

@@ -1,0 +1,349 @@
+"""Pins for the CPU oracle: closed forms, invariants, library cross-checks and
+exhaustive enumeration on tiny cases.  No GPU, no HIP library.
+
+Each test is chosen so that a plausible mistake in the oracle (dropped term,
+wrong sign, transposed operand, off-by-one index, wrong tie rule) fails it.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import eh_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- entropy/lse
+def _golden_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "entropy_closed_form.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            V, n, a, H, lse = line.split()
+            rows.append((int(V), int(n), float(a), float(H), float(lse)))
+    return rows
+
+
+@pytest.mark.parametrize("V,n,a,H_ref,lse_ref", _golden_rows())
+def test_two_level_logits_closed_form(V, n, a, H_ref, lse_ref):
+    # Section 3.4.1: entropy of the predicted distribution; closed form fixture.
+    rng = np.random.default_rng(V + n)
+    z = np.zeros(V)
+    pos = rng.choice(V, size=n, replace=False)
+    z[pos] = a
+    H, lse, am, gap = O.softmax_stats(z)
+    assert H[0] == pytest.approx(H_ref, rel=1e-11, abs=1e-15)
+    assert lse[0] == pytest.approx(lse_ref, rel=1e-13)
+    if a > 0:
+        assert am[0] == pos.min()
+        assert gap[0] == pytest.approx(0.0 if n > 1 else a)
+
+
+def test_uniform_logits_give_log_V():
+    V = 50304
+    for c in (0.0, -3.25, 1e4):
+        H, lse, am, gap = O.softmax_stats(np.full(V, c))
+        # the shift costs |c| * 2**-53 of absolute accuracy in z - lse
+        assert H[0] == pytest.approx(math.log(V), rel=1e-13, abs=max(1.0, abs(c)) * 4e-15)
+        assert lse[0] == pytest.approx(c + math.log(V), rel=1e-13)
+        assert am[0] == 0 and gap[0] == 0.0
+    assert math.log(V) == pytest.approx(10.825839875788878, rel=1e-15)
+
+
+def test_dominant_logit_entropy_goes_to_zero():
+    V = 50304
+    prev = None
+    for a in (20.0, 30.0, 40.0, 80.0, 800.0):
+        z = np.zeros(V)
+        z[V - 1] = a
+        H, lse, am, _ = O.softmax_stats(z)
+        assert 0.0 <= H[0] < 3e-3
+        assert prev is None or H[0] <= prev
+        assert am[0] == V - 1
+        prev = H[0]
+    assert prev == 0.0  # exp underflow gives exactly 0 log 0 = 0
+
+
+def test_shift_permutation_invariance_and_bounds():
+    rng = np.random.default_rng(7)
+    V = 4099
+    for scale in (0.5, 2.0, 8.0):
+        z = rng.normal(size=V) * scale
+        H, lse, am, gap = O.softmax_stats(z)
+        assert 0.0 <= H[0] <= math.log(V)
+        assert z.max() <= lse[0] <= z.max() + math.log(V)
+        for c in (1.0, -1.0, 100.0, -100.0, 1e4, -1e4):
+            H2, lse2, am2, gap2 = O.softmax_stats(z + c)
+            assert H2[0] == pytest.approx(H[0], abs=1e-9)
+            assert lse2[0] == pytest.approx(lse[0] + c, rel=1e-12)
+            assert am2[0] == am[0]
+        perm = rng.permutation(V)
+        H3, lse3, am3, gap3 = O.softmax_stats(z[perm])
+        assert H3[0] == pytest.approx(H[0], rel=1e-12)
+        assert lse3[0] == pytest.approx(lse[0], rel=1e-13)
+        assert perm[am3[0]] == am[0]
+        assert gap3[0] == pytest.approx(gap[0])
+
+
+def test_softmax_stats_against_scipy():
+    # special case reducing to library routines
+    from scipy.special import logsumexp, softmax
+    from scipy.stats import entropy
+    rng = np.random.default_rng(11)
+    z = rng.normal(size=(5, 1000)) * np.array([0.3, 1, 3, 9, 27])[:, None]
+    H, lse, am, gap = O.softmax_stats(z)
+    np.testing.assert_allclose(lse, logsumexp(z, axis=1), rtol=1e-13)
+    np.testing.assert_allclose(H, entropy(softmax(z, axis=1), axis=1), rtol=1e-10, atol=1e-14)
+    np.testing.assert_array_equal(am, z.argmax(axis=1))
+    srt = np.sort(z, axis=1)
+    np.testing.assert_allclose(gap, srt[:, -1] - srt[:, -2])
+
+
+def test_exhaustive_V8_three_level_logits():
+    # brute force: all 3^8 logit vectors over {0,1,2}; naive formulas in pure Python
+    V = 8
+    allz = np.array(list(itertools.product((0.0, 1.0, 2.0), repeat=V)))
+    H, lse, am, gap = O.softmax_stats(allz)
+    for r, z in enumerate(allz):
+        e = [math.exp(v) for v in z]
+        Z = sum(e)
+        p = [v / Z for v in e]
+        Hn = -sum(q * math.log(q) for q in p)
+        assert H[r] == pytest.approx(Hn, rel=1e-12)
+        assert lse[r] == pytest.approx(math.log(Z), rel=1e-13)
+        best = max(z)
+        assert am[r] == list(z).index(best)          # lowest index on ties
+        second = sorted(z)[-2]
+        assert gap[r] == best - second
+
+
+def test_nan_row_gives_nan():
+    z = np.zeros((2, 16))
+    z[1, 3] = np.nan
+    H, lse, am, gap = O.softmax_stats(z)
+    assert np.isfinite(H[0]) and np.isnan(H[1]) and np.isnan(lse[1])
+
+
+# ------------------------------------------------------------------ LayerNorm
+def test_layernorm_constant_row_gives_beta():
+    d = 64
+    rng = np.random.default_rng(0)
+    g, b = rng.normal(size=d), rng.normal(size=d)
+    y = O.layernorm(np.full((3, d), 4.75), g, b)
+    np.testing.assert_array_equal(y, np.broadcast_to(b, (3, d)))
+
+
+def test_layernorm_moments_and_scale_invariance():
+    rng = np.random.default_rng(1)
+    d, eps = 512, 1e-5
+    h = rng.normal(size=(4, d)) * np.array([0.1, 1.0, 7.0, 300.0])[:, None] + 3.0
+    one, zero = np.ones(d), np.zeros(d)
+    xh = O.layernorm(h, one, zero, eps)
+    var = h.var(axis=1)                       # numpy's biased variance
+    np.testing.assert_allclose(xh.mean(axis=1), 0.0, atol=1e-13)
+    np.testing.assert_allclose((xh ** 2).mean(axis=1), var / (var + eps), rtol=1e-12)
+    a = O.layernorm(h, one, zero, 0.0)
+    b = O.layernorm(5.5 * h - 17.0, one, zero, 0.0)
+    np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-11)
+    c = O.layernorm(-2.0 * h, one, zero, 0.0)
+    np.testing.assert_allclose(c, -a, rtol=1e-9, atol=1e-11)  # sign is kept
+
+
+def test_layernorm_d2_closed_form_and_affine():
+    u, v, eps = 3.0, -1.5, 1e-5
+    g = np.array([2.0, -3.0])
+    b = np.array([0.25, 0.5])
+    y = O.layernorm(np.array([[u, v]]), g, b, eps)[0]
+    s = abs(u - v) / math.sqrt((u - v) ** 2 + 4 * eps)
+    assert y[0] == pytest.approx(g[0] * s + b[0], rel=1e-14)
+    assert y[1] == pytest.approx(-g[1] * s + b[1], rel=1e-14)
+
+
+def test_layernorm_against_torch():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(2)
+    d = 160
+    h = rng.normal(size=(6, d)) * 3 + 1
+    g, b = rng.normal(size=d), rng.normal(size=d)
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(h), (d,), torch.from_numpy(g),
+                                         torch.from_numpy(b), eps=1e-5).numpy()
+    np.testing.assert_allclose(O.layernorm(h, g, b, 1e-5), ref, rtol=1e-11, atol=1e-12)
+
+
+# ------------------------------------------------------------------ projection
+def test_projection_selector_rows():
+    # W row i = c_i * e_{j(i)}  ->  z_i = c_i * y_{j(i)}; catches a transposed operand
+    rng = np.random.default_rng(3)
+    d, V = 12, 40
+    y = rng.normal(size=(5, d))
+    j = rng.integers(0, d, size=V)
+    c = rng.normal(size=V)
+    W = np.zeros((V, d))
+    W[np.arange(V), j] = c
+    z = O.head_logits(y, W)
+    np.testing.assert_allclose(z, y[:, j] * c, rtol=1e-15)
+    bias = rng.normal(size=V)
+    np.testing.assert_allclose(O.head_logits(y, W, bias), y[:, j] * c + bias, rtol=1e-15)
+
+
+def test_projection_identity_block():
+    d, V = 8, 20
+    W = np.zeros((V, d))
+    W[:d] = np.eye(d)
+    y = np.arange(1.0, 2 * d + 1).reshape(2, d)
+    z = O.head_logits(y, W)
+    np.testing.assert_array_equal(z[:, :d], y)
+    np.testing.assert_array_equal(z[:, d:], 0.0)
+
+
+def test_head_eval_against_torch_pipeline():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(4)
+    d, V, R = 96, 777, 9
+    h = rng.normal(size=(R, d)) * rng.uniform(0.5, 8, size=(R, 1))
+    g = 1 + 0.02 * rng.normal(size=d)
+    b = 0.02 * rng.normal(size=d)
+    W = rng.normal(size=(V, d)) * 3 / math.sqrt(d)
+    H, lse, am, gap = O.head_eval(h, g, b, W)
+    th = torch.from_numpy
+    y = torch.nn.functional.layer_norm(th(h), (d,), th(g), th(b), eps=1e-5)
+    z = torch.nn.functional.linear(y, th(W))
+    lp = torch.log_softmax(z, dim=-1)
+    ent = torch.distributions.Categorical(logits=z).entropy()
+    np.testing.assert_allclose(H, ent.numpy(), rtol=1e-10)
+    np.testing.assert_allclose(lse, torch.logsumexp(z, -1).numpy(), rtol=1e-12)
+    np.testing.assert_array_equal(am, lp.argmax(-1).numpy())
+
+
+# ------------------------------------------------------------------ bf16
+def test_bf16_roundtrip_all_patterns():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    v = O.bf16_bits_to_f64(bits)
+    fin = np.isfinite(v)
+    r = O.round_to_bf16(v)
+    np.testing.assert_array_equal(r[fin], v[fin])
+    np.testing.assert_array_equal(O.f64_to_bf16_bits(v[fin]), bits[fin])
+
+
+def test_bf16_ties_to_even_and_neighbours():
+    bits = np.arange(0x0001, 0x7F7F, dtype=np.uint32).astype(np.uint16)  # positive finite, incl. subnormals
+    lo = O.bf16_bits_to_f64(bits)
+    hi = O.bf16_bits_to_f64(bits + np.uint16(1))
+    mid = (lo + hi) / 2                      # exact in fp64
+    even = np.where(bits % 2 == 0, lo, hi)
+    np.testing.assert_array_equal(O.round_to_bf16(mid), even)
+    np.testing.assert_array_equal(O.round_to_bf16(-mid), -even)
+    np.testing.assert_array_equal(O.round_to_bf16(np.nextafter(mid, np.inf)), hi)
+    np.testing.assert_array_equal(O.round_to_bf16(np.nextafter(mid, -np.inf)), lo)
+
+
+def test_bf16_hand_picked():
+    f = O.round_to_bf16
+    assert f(np.array([1.0 + 2.0 ** -8]))[0] == 1.0              # tie -> even (1.0)
+    assert f(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6  # tie -> even (up)
+    assert f(np.array([1.00390625 + 1e-9]))[0] == 1.0078125
+    big = O.bf16_bits_to_f64(np.array([0x7F7F], dtype=np.uint16))[0]   # largest finite
+    assert f(np.array([big]))[0] == big
+    assert np.isinf(f(np.array([big * (1 + 2.0 ** -8)]))[0])      # tie at the top rounds to inf
+    assert f(np.array([big * (1 + 2.0 ** -9)]))[0] == big
+    tiny = 2.0 ** -133                                            # smallest subnormal
+    assert f(np.array([tiny * 0.5]))[0] == 0.0                    # tie -> even (0)
+    assert f(np.array([tiny * 0.75]))[0] == tiny
+    z = f(np.array([0.0, -0.0, np.inf, -np.inf, np.nan]))
+    assert z[0] == 0.0 and np.signbit(z[1]) and np.isinf(z[2]) and np.isinf(z[3]) and np.isnan(z[4])
+
+
+def test_bf16_against_torch_rne():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(5)
+    x = (rng.normal(size=200000) * np.exp(rng.uniform(-60, 60, size=200000))).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_to_bf16(x.astype(np.float64)), ref)
+
+
+def test_layernorm_bf16_output_is_rounded_fp64_result():
+    rng = np.random.default_rng(6)
+    d = 256
+    h = rng.normal(size=(3, d))
+    g, b = np.ones(d), np.zeros(d)
+    y = O.layernorm(h, g, b, 1e-5, bf16_out=True)
+    full = O.layernorm(h, g, b, 1e-5)
+    np.testing.assert_array_equal(y, O.round_to_bf16(full))
+    assert np.all(np.abs(y - full) <= np.abs(full) * 2.0 ** -8)
+    O.f64_to_bf16_bits(y)  # raises if not representable
+
+
+# ------------------------------------------------------------------ exit rule
+@pytest.mark.parametrize("n_heads", [1, 2, 3, 4, 5, 6])
+def test_exit_rule_all_patterns(n_heads):
+    tau = np.linspace(0.5, 3.0, n_heads)
+    for pattern in itertools.product((False, True), repeat=n_heads):
+        H = [tau[k] - 0.1 if below else tau[k] + 0.1 for k, below in enumerate(pattern)]
+        early = [k for k in range(n_heads - 1) if pattern[k]]
+        expect = early[0] if early else n_heads - 1
+        assert O.exit_rule(H, tau) == expect
+
+
+def test_exit_rule_strict_and_nan():
+    tau = [1.0, 1.0, 1.0]
+    assert O.exit_rule([1.0, 1.0, 5.0], tau) == 2          # equality does not exit
+    assert O.exit_rule([np.nan, 0.5, 5.0], tau) == 1       # NaN never passes
+    assert O.exit_rule([np.nextafter(1.0, 0), 0.0, 0.0], tau) == 0
+
+
+def test_cascade_equals_masked_full_evaluation():
+    rng = np.random.default_rng(8)
+    d, V, R, n_heads = 32, 200, 40, 5
+    Ws = [rng.normal(size=(V, d)) * (0.5 + 1.2 * l) / math.sqrt(d) for l in range(n_heads)]
+    gs = [1 + 0.02 * rng.normal(size=d) for _ in range(n_heads)]
+    bs = [0.02 * rng.normal(size=d) for _ in range(n_heads)]
+    hs = [rng.normal(size=(R, d)) for _ in range(n_heads)]
+    full_H = np.stack([O.head_eval(hs[l], gs[l], bs[l], Ws[l])[0] for l in range(n_heads)])
+    full_A = np.stack([O.head_eval(hs[l], gs[l], bs[l], Ws[l])[2] for l in range(n_heads)])
+    tau = np.quantile(full_H, 0.3, axis=1)
+    out = O.cascade(hs, gs, bs, Ws, tau)
+    assert len(set(out["exit_layer"])) > 2   # the case exercises several exits
+    for r in range(R):
+        k = O.exit_rule(full_H[:, r], tau)
+        assert out["exit_layer"][r] == k
+        assert out["token"][r] == full_A[k, r]
+        assert np.all(np.isnan(out["H"][k + 1:, r]))
+        np.testing.assert_allclose(out["H"][:k + 1, r], full_H[:k + 1, r], rtol=1e-12)
+    for l in range(n_heads):
+        expect = [r for r in range(R) if out["exit_layer"][r] >= l]
+        assert list(out["active"][l]) == expect      # stable, increasing order
+
+
+# ------------------------------------------------------------------ DSSD verify
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_accepted_prefix_exhaustive(k):
+    for draft in itertools.product((0, 1), repeat=k):
+        for target in itertools.product((0, 1), repeat=k + 1):
+            mism = [j for j in range(k) if draft[j] != target[j]]
+            first = mism[0] if mism else k
+            for L in range(k + 1):
+                assert O.accepted_prefix(draft, target, L) == min(first, L)
+
+
+def test_dssd_verify_planted_targets():
+    rng = np.random.default_rng(9)
+    d, V, B, k = 24, 50, 6, 4
+    W = rng.normal(size=(V, d)) / math.sqrt(d)
+    g, b = np.ones(d), np.zeros(d)
+    tgt = rng.integers(0, V, size=(B, k + 1))
+    f = 6.0 * W[tgt] + 0.05 * rng.normal(size=(B, k + 1, d))   # aligned with row tgt
+    draft = tgt[:, :k].copy()
+    draft[0, 0] = (draft[0, 0] + 1) % V        # reject at once
+    draft[1, 2] = (draft[1, 2] + 1) % V        # accept 2
+    draft[2, 3] = (draft[2, 3] + 1) % V        # accept 3
+    draft_len = np.array([k, k, k, k, 2, 0])   # rows 4, 5 truncated
+    acc, nxt, target, gap = O.dssd_verify(f, draft, g, b, W, draft_len)
+    np.testing.assert_array_equal(target, tgt)
+    np.testing.assert_array_equal(acc, [0, 2, 3, 4, 2, 0])
+    np.testing.assert_array_equal(nxt, [tgt[0, 0], tgt[1, 2], tgt[2, 3], tgt[3, 4], tgt[4, 2], tgt[5, 0]])
+    acc2, _, _, _ = O.dssd_verify(f, draft, g, b, W)
+    np.testing.assert_array_equal(acc2, [0, 2, 3, 4, 4, 4])
