@@ -1,0 +1,177 @@
+/*
+ * eh.h -- C ABI of libeh: early-exit head evaluation and DSSD greedy
+ * verification on one AMD MI355X (gfx950).
+ *
+ * Method: arXiv 2407.21082, "Accelerating Large Language Model Inference with
+ * Dynamic Self-Speculative Decoding".  Section numbers below refer to it.
+ *
+ * General conventions
+ *   - Every entry point returns an eh_status and never throws or aborts.
+ *     Argument errors are detected on the host before anything is launched.
+ *   - "device" pointers are HIP device memory on the context's device; "host"
+ *     pointers are ordinary process memory.  The library never takes ownership
+ *     of a caller buffer.  Inputs and outputs of an asynchronous call must stay
+ *     alive and untouched until the stream has passed the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work of a call is enqueued on it; calls do not synchronise the host.
+ *   - A context serialises its calls: it owns one workspace, so two calls on
+ *     the same context must be ordered on the same stream (or by the caller).
+ *   - Row statistics of rows whose input contains NaN/Inf are NaN; such rows
+ *     never pass the exit test.  This is defined behaviour, not an error.
+ */
+#ifndef EH_H_
+#define EH_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct eh_ctx eh_ctx; /* opaque, owned by the library */
+
+typedef enum {
+  EH_OK = 0,
+  EH_ERR_NULL = 1,      /* a required pointer is NULL                        */
+  EH_ERR_SHAPE = 2,     /* a size is non-positive or inconsistent            */
+  EH_ERR_DTYPE = 3,     /* unsupported dtype combination                     */
+  EH_ERR_RANGE = 4,     /* index (head, n_rows, k ...) outside its range     */
+  EH_ERR_HIP = 5,       /* a HIP runtime call failed (see eh_last_error)     */
+  EH_ERR_WORKSPACE = 6  /* request exceeds the workspace sized at creation   */
+} eh_status;
+
+typedef enum { EH_F32 = 0, EH_BF16 = 1 } eh_dtype;
+
+/*
+ * Description of a stack of exit heads (Section 3.1 "Early exit heads",
+ * Section 3.2: each head has the structure of the model's final classification
+ * head; here LayerNorm(gamma, beta, eps) followed by a d -> V linear map).
+ * Head n_heads-1 stands for the full model's own head: it always answers.
+ *
+ * W[l]      device, [V, d] row-major, dtype w_dtype.  Copied (re-tiled into the
+ *           matrix-core operand order) at creation; the caller may free it
+ *           after eh_create returns.
+ * gamma[l], beta[l]   device, [d] float.  Copied at creation.
+ * bias      NULL, or n_heads device pointers [V] float added to the logits.
+ * tau       host, [n_heads] float, thresholds in nats (Section 3.4.1); the last
+ *           entry is ignored.  Copied.
+ * w_dtype must equal h_dtype.  In EH_BF16 mode the LayerNorm output is rounded
+ * to bf16 (nearest even) before the projection; products are exact and sums
+ * are accumulated in fp32.
+ */
+typedef struct {
+  int32_t d;         /* hidden size, > 0                                       */
+  int32_t V;         /* vocabulary size, > 0                                   */
+  int32_t n_heads;   /* >= 1, includes the final head                          */
+  int32_t max_rows;  /* largest n_rows any call will pass, >= 1                */
+  int32_t w_dtype;   /* eh_dtype of W                                          */
+  int32_t h_dtype;   /* eh_dtype of hidden states                              */
+  float ln_eps;      /* LayerNorm epsilon (> 0; 1e-5 for the Pythia family)    */
+  int32_t device;    /* HIP device ordinal                                     */
+  const void* const* W;
+  const float* const* gamma;
+  const float* const* beta;
+  const float* const* bias;
+  const float* tau;
+} eh_config;
+
+/* Creates a context on cfg->device (made current for the call and restored).
+ * The caller must have finished writing the weight buffers; the copies are
+ * complete when the call returns.  *out is NULL on error. */
+eh_status eh_create(const eh_config* cfg, eh_ctx** out);
+
+/* Frees everything the context owns.  Synchronises the device first. */
+eh_status eh_destroy(eh_ctx* ctx);
+
+/*
+ * One head on a set of rows (Sections 3.2 and 3.4.1): for each row, LayerNorm,
+ * projection to V logits, and the entropy H = -sum p log p (nats), the
+ * log-sum-exp and the argmax (lowest index on ties) of the softmax over the
+ * logits.  The logits are never written to memory.
+ *
+ * head          0 <= head < n_heads
+ * h             device, rows of d elements (h_dtype); row r starts at element
+ *               r * h_row_stride (h_row_stride >= d)
+ * row_idx       device [n_rows] or NULL.  If given, output position p reads
+ *               input row row_idx[p] (gather after compaction); else row p.
+ * n_rows_dev    device int32 or NULL.  If given, the number of live rows is
+ *               read from it on the device (0 <= *n_rows_dev <= n_rows) and
+ *               output positions beyond it are left untouched.
+ * n_rows        host upper bound on rows, 0 <= n_rows <= max_rows (0 = no-op)
+ * H, lse, argmax  device [n_rows] outputs (float, float, int32); any may be
+ *               NULL.  Indexed by output position p.
+ */
+eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride,
+                  const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows,
+                  float* H, float* lse, int32_t* argmax, void* stream);
+
+/*
+ * Exit rule for one head (Section 3.4.2; entropy form of Section 4.3.1,
+ * "Drafting phase") followed by compaction of the rows that go on.
+ *
+ * Position p (p < live rows) describes row r = row_idx ? row_idx[p] : p.
+ * If H[p] < tau[head], or head == n_heads-1, the row exits here:
+ * exit_layer[r] = head, token[r] = argmax[p].  Otherwise r is appended to
+ * active_idx_out, which keeps the input order (stable), and the number of
+ * survivors is written to *n_active_out.
+ *
+ * H, argmax          device [n_rows], outputs of eh_eval for the same positions
+ * exit_layer, token  device, indexed by row r, in-out (caller initialises to -1)
+ * active_idx_out     device [n_rows]; may alias nothing else
+ * n_active_out       device int32
+ * tau_override       if not NaN, used instead of the context's tau[head]
+ */
+eh_status eh_exit_decide(eh_ctx* ctx, int32_t head, const float* H, const int32_t* argmax,
+                         const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows,
+                         int32_t* exit_layer, int32_t* token, int32_t* active_idx_out,
+                         int32_t* n_active_out, float tau_override, void* stream);
+
+/*
+ * Whole dynamic-exit cascade for n_rows independent rows (Section 3.4.2): heads
+ * 0..n_heads-1 in order, each evaluated only on the rows that have not exited,
+ * with no host synchronisation between heads.  Equivalent to calling eh_eval
+ * and eh_exit_decide per head with the active list carried on the device.
+ *
+ * h_layers      device; head l reads row r at element
+ *               l * layer_stride + r * row_stride
+ * exit_layer, token   device [n_rows] outputs (need no initialisation)
+ * H_out         NULL or device [n_heads, n_rows] float: entropy of every
+ *               evaluated (head, row); entries never evaluated are set to NaN
+ * n_evals_out   NULL or device int64: incremented by the number of
+ *               (row, head) evaluations performed
+ */
+eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride,
+                     int64_t row_stride, int32_t n_rows, int32_t* exit_layer,
+                     int32_t* token, float* H_out, int64_t* n_evals_out, void* stream);
+
+/*
+ * DSSD greedy verification (Section 4.3.1, "Verification phase").
+ *
+ * f_final    device [B, k+1, d] (h_dtype, contiguous): the full model's final
+ *            hidden state at the position preceding draft token j (j < k) and
+ *            after the last draft token (j = k)
+ * draft      device [B, k] int32 drafted tokens
+ * draft_len  device [B] int32 (0 <= draft_len[b] <= k) or NULL (= k)
+ * accepted   device [B]: length of the longest prefix with
+ *            draft[b, j] == target[b, j], bounded by draft_len[b]
+ * next_token device [B]: target[b, accepted[b]] -- the full-model token that
+ *            replaces the first mismatch, or the bonus token
+ * target     NULL or device [B, k+1]: the final head's argmax at every position
+ * Requires B * (k+1) <= max_rows.  Uses head n_heads-1.
+ */
+eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft,
+                      const int32_t* draft_len, int32_t B, int32_t k, int32_t* accepted,
+                      int32_t* next_token, int32_t* target, void* stream);
+
+/* Message describing the last error on this context (or, with ctx == NULL, the
+ * last eh_create failure of the calling thread).  Never NULL.  The string is
+ * owned by the library and valid until the next call on the same context. */
+const char* eh_last_error(const eh_ctx* ctx);
+
+/* Library version, e.g. "libeh 0.1 (gfx950)". Static string. */
+const char* eh_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EH_H_ */

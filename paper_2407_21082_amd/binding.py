@@ -1,0 +1,175 @@
+"""ctypes binding of libeh (see include/eh.h).  Argument marshalling only: every
+step of the method runs inside the library's HIP kernels.  PyTorch supplies
+device memory (``tensor.data_ptr()``) and the current stream, nothing else.
+
+There is no CPU or eager fallback: if libeh.so is missing, stale or fails to
+load, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from typing import List, Optional, Sequence
+
+import torch  # noqa: F401  (loaded first so that libeh binds to the same HIP runtime)
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libeh.so")
+
+EH_OK = 0
+EH_F32, EH_BF16 = 0, 1
+STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYPE",
+                4: "EH_ERR_RANGE", 5: "EH_ERR_HIP", 6: "EH_ERR_WORKSPACE"}
+
+# every symbol include/eh.h declares
+EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify",
+           "eh_last_error", "eh_version"]
+
+
+class EhError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {msg}")
+        self.status = status
+
+
+class _Config(C.Structure):
+    _fields_ = [
+        ("d", C.c_int32), ("V", C.c_int32), ("n_heads", C.c_int32), ("max_rows", C.c_int32),
+        ("w_dtype", C.c_int32), ("h_dtype", C.c_int32), ("ln_eps", C.c_float), ("device", C.c_int32),
+        ("W", C.POINTER(C.c_void_p)), ("gamma", C.POINTER(C.c_void_p)), ("beta", C.POINTER(C.c_void_p)),
+        ("bias", C.POINTER(C.c_void_p)), ("tau", C.POINTER(C.c_float)),
+    ]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2407_21082_amd.build` "
+            "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    lib.eh_create.argtypes = [C.POINTER(_Config), C.POINTER(vp)]
+    lib.eh_destroy.argtypes = [vp]
+    lib.eh_eval.argtypes = [vp, i32, vp, i64, vp, vp, i32, vp, vp, vp, vp]
+    lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, f32, vp]
+    lib.eh_cascade.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp]
+    lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.eh_last_error.argtypes = [vp]
+    lib.eh_last_error.restype = C.c_char_p
+    lib.eh_version.argtypes = []
+    lib.eh_version.restype = C.c_char_p
+    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify"):
+        getattr(lib, name).restype = C.c_int
+    return lib
+
+
+lib = _load()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _check(status: int, handle) -> None:
+    if status != EH_OK:
+        raise EhError(status, lib.eh_last_error(handle).decode())
+
+
+def eh_version() -> str:
+    return lib.eh_version().decode()
+
+
+class EhContext:
+    """Owner of an ``eh_ctx*``; freed by ``eh_destroy`` or on garbage collection."""
+
+    def __init__(self, handle: int, d: int, V: int, n_heads: int, max_rows: int, dtype: torch.dtype,
+                 device: torch.device):
+        self.handle = C.c_void_p(handle)
+        self.d, self.V, self.n_heads, self.max_rows = d, V, n_heads, max_rows
+        self.dtype, self.device = dtype, device
+
+    def __del__(self):
+        try:
+            eh_destroy(self)
+        except Exception:
+            pass
+
+
+def eh_create(W: Sequence[torch.Tensor], gamma: Sequence[torch.Tensor], beta: Sequence[torch.Tensor],
+              tau: Sequence[float], max_rows: int, ln_eps: float = 1e-5,
+              bias: Optional[Sequence[torch.Tensor]] = None) -> EhContext:
+    n = len(W)
+    V, d = W[0].shape
+    dt = W[0].dtype
+    code = {torch.float32: EH_F32, torch.bfloat16: EH_BF16}.get(dt)
+    if code is None:
+        raise EhError(3, f"unsupported dtype {dt}")
+    dev = W[0].device
+    for l in range(n):
+        assert W[l].is_cuda and W[l].is_contiguous() and W[l].shape == (V, d) and W[l].dtype == dt
+        assert gamma[l].dtype == torch.float32 and gamma[l].is_contiguous() and gamma[l].numel() == d
+        assert beta[l].dtype == torch.float32 and beta[l].is_contiguous() and beta[l].numel() == d
+    arr = C.c_void_p * n
+    cfg = _Config(d=d, V=V, n_heads=n, max_rows=max_rows, w_dtype=code, h_dtype=code, ln_eps=ln_eps,
+                  device=dev.index or 0,
+                  W=arr(*[w.data_ptr() for w in W]),
+                  gamma=arr(*[g.data_ptr() for g in gamma]),
+                  beta=arr(*[b.data_ptr() for b in beta]),
+                  bias=arr(*[b.data_ptr() for b in bias]) if bias is not None else None,
+                  tau=(C.c_float * n)(*[float(t) if math.isfinite(t) else 3.0e38 for t in tau]))
+    torch.cuda.synchronize(dev)       # the library copies the weights synchronously
+    out = C.c_void_p()
+    st = lib.eh_create(C.byref(cfg), C.byref(out))
+    if st != EH_OK:
+        raise EhError(st, lib.eh_last_error(None).decode())
+    return EhContext(out.value, d, V, n, max_rows, dt, dev)
+
+
+def eh_destroy(ctx: EhContext) -> None:
+    if ctx.handle:
+        lib.eh_destroy(ctx.handle)
+        ctx.handle = C.c_void_p(None)
+
+
+def eh_eval(ctx: EhContext, head: int, h: torch.Tensor, n_rows: int, H: Optional[torch.Tensor],
+            lse: Optional[torch.Tensor], argmax: Optional[torch.Tensor],
+            row_idx: Optional[torch.Tensor] = None, n_rows_dev: Optional[torch.Tensor] = None,
+            row_stride: Optional[int] = None, stream=None) -> None:
+    stride = h.stride(-2) if row_stride is None and h.dim() >= 2 else (row_stride or ctx.d)
+    _check(lib.eh_eval(ctx.handle, head, _ptr(h), stride, _ptr(row_idx), _ptr(n_rows_dev), n_rows,
+                       _ptr(H), _ptr(lse), _ptr(argmax), _stream(stream)), ctx.handle)
+
+
+def eh_exit_decide(ctx: EhContext, head: int, H: torch.Tensor, argmax: torch.Tensor, n_rows: int,
+                   exit_layer: torch.Tensor, token: torch.Tensor, active_idx_out: torch.Tensor,
+                   n_active_out: torch.Tensor, row_idx: Optional[torch.Tensor] = None,
+                   n_rows_dev: Optional[torch.Tensor] = None, tau_override: float = float("nan"),
+                   stream=None) -> None:
+    _check(lib.eh_exit_decide(ctx.handle, head, _ptr(H), _ptr(argmax), _ptr(row_idx), _ptr(n_rows_dev),
+                              n_rows, _ptr(exit_layer), _ptr(token), _ptr(active_idx_out),
+                              _ptr(n_active_out), tau_override, _stream(stream)), ctx.handle)
+
+
+def eh_cascade(ctx: EhContext, h_layers: torch.Tensor, n_rows: int, exit_layer: torch.Tensor,
+               token: torch.Tensor, H_out: Optional[torch.Tensor] = None,
+               n_evals_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """h_layers: [n_heads, n_rows, d] (any strides on the first two axes)."""
+    _check(lib.eh_cascade(ctx.handle, _ptr(h_layers), h_layers.stride(0), h_layers.stride(1), n_rows,
+                          _ptr(exit_layer), _ptr(token), _ptr(H_out), _ptr(n_evals_out),
+                          _stream(stream)), ctx.handle)
+
+
+def dssd_verify(ctx: EhContext, f_final: torch.Tensor, draft: torch.Tensor,
+                draft_len: Optional[torch.Tensor], accepted: torch.Tensor, next_token: torch.Tensor,
+                target: Optional[torch.Tensor] = None, stream=None) -> None:
+    B, k1, _ = f_final.shape
+    assert f_final.is_contiguous()
+    _check(lib.dssd_verify(ctx.handle, _ptr(f_final), _ptr(draft), _ptr(draft_len), B, k1 - 1,
+                           _ptr(accepted), _ptr(next_token), _ptr(target), _stream(stream)), ctx.handle)

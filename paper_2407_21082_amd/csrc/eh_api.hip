@@ -1,0 +1,342 @@
+// libeh: C ABI and host-side dispatch (see include/eh.h for the contract).
+#include "eh.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "eh_kernels.hpp"
+
+using namespace eh;
+
+namespace {
+
+thread_local std::string g_create_error = "";
+
+constexpr int kMaxNB = 10;           // token blocks (of 16) one stream launch covers
+constexpr int kStreamGrid = 512;     // workgroups of the stream kernel (2 per CU)
+
+struct DeviceGuard {
+  int prev = -1;
+  bool changed = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) == hipSuccess && prev != dev) {
+      changed = (hipSetDevice(dev) == hipSuccess);
+    }
+  }
+  ~DeviceGuard() {
+    if (changed) (void)hipSetDevice(prev);
+  }
+};
+
+}  // namespace
+
+struct eh_ctx {
+  int d = 0, V = 0, n_heads = 0, max_rows = 0, dtype = 0, device = 0;
+  float eps = 1e-5f;
+  int KS = 0, VT = 0, R_pad_max = 0;
+  std::vector<frag_t*> Wf;        // per head, fragment-major weights
+  std::vector<float*> gamma, beta, bias;
+  std::vector<float> tau;
+  frag_t* yf = nullptr;           // [R_pad_max/16][KS][64] activations in fragment order
+  Stats* partials = nullptr;      // [kStreamGrid][R_pad_max]
+  float* ws_H = nullptr;          // [max_rows] internal outputs (cascade, verify)
+  float* ws_lse = nullptr;
+  int* ws_argmax = nullptr;
+  int* active[2] = {nullptr, nullptr};
+  int* n_active[2] = {nullptr, nullptr};
+  std::vector<void*> allocs;
+  std::string err = "";
+};
+
+namespace {
+
+eh_status fail(eh_ctx* ctx, eh_status st, const std::string& msg) {
+  if (ctx) ctx->err = msg; else g_create_error = msg;
+  return st;
+}
+
+#define EH_HIP(ctx, call)                                                             \
+  do {                                                                                \
+    hipError_t e_ = (call);                                                           \
+    if (e_ != hipSuccess)                                                             \
+      return fail(ctx, EH_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+template <typename T>
+hipError_t dev_alloc(eh_ctx* ctx, T** p, size_t count) {
+  void* v = nullptr;
+  hipError_t e = hipMalloc(&v, count * sizeof(T) > 0 ? count * sizeof(T) : 16);
+  if (e == hipSuccess) {
+    ctx->allocs.push_back(v);
+    *p = (T*)v;
+  }
+  return e;
+}
+
+void free_all(eh_ctx* ctx) {
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  ctx->allocs.clear();
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+template <typename DT, bool AO>
+void launch_stream(int nbc, const eh_ctx* c, int head, int nb0, const int* n_rows_dev, int n_rows,
+                   int R_pad, hipStream_t s) {
+  const frag_t* Wf = c->Wf[head];
+  const float* bias = c->bias.empty() ? nullptr : c->bias[head];
+  dim3 g(kStreamGrid), b(256);
+#define EH_LAUNCH(NB)                                                                           \
+  hipLaunchKernelGGL((stream_kernel<DT, NB, AO>), g, b, 0, s, Wf, c->yf, bias, c->VT, c->KS, c->V, \
+                     nb0, n_rows_dev, n_rows, R_pad, c->partials)
+  if (nbc <= 1) EH_LAUNCH(1);
+  else if (nbc <= 2) EH_LAUNCH(2);
+  else if (nbc <= 4) EH_LAUNCH(4);
+  else if (nbc <= 6) EH_LAUNCH(6);
+  else if (nbc <= 8) EH_LAUNCH(8);
+  else EH_LAUNCH(10);
+#undef EH_LAUNCH
+}
+
+// LayerNorm + projection + statistics for one head; results to (H, lse, argmax).
+template <bool AO>
+eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const int* row_idx,
+                   const int* n_rows_dev, int n_rows, float* H, float* lse, int* argmax,
+                   hipStream_t s) {
+  const int R_pad = (n_rows + 15) & ~15;
+  const int NBtot = R_pad / 16;
+  const bool bf = c->dtype == EH_BF16;
+  {
+    dim3 g((R_pad + 3) / 4), b(256);
+    if (bf)
+      hipLaunchKernelGGL((ln_pack_kernel<DtBf16>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
+                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
+    else
+      hipLaunchKernelGGL((ln_pack_kernel<DtF32>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
+                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
+  }
+  for (int nb0 = 0; nb0 < NBtot; nb0 += kMaxNB) {
+    const int nbc = std::min(kMaxNB, NBtot - nb0);
+    if (bf) launch_stream<DtBf16, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
+    else launch_stream<DtF32, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
+  }
+  hipLaunchKernelGGL(finalize_kernel, dim3(n_rows), dim3(64), 0, s, c->partials, kStreamGrid, R_pad,
+                     n_rows_dev, n_rows, AO ? nullptr : H, AO ? nullptr : lse, argmax);
+  EH_HIP(c, hipGetLastError());
+  return EH_OK;
+}
+
+eh_status check_rows(eh_ctx* ctx, const void* h, int64_t row_stride, int n_rows) {
+  if (n_rows < 0 || n_rows > ctx->max_rows)
+    return fail(ctx, EH_ERR_WORKSPACE, "n_rows outside [0, max_rows]");
+  if (row_stride < ctx->d) return fail(ctx, EH_ERR_SHAPE, "row stride smaller than d");
+  const int esz = ctx->dtype == EH_BF16 ? 2 : 4;
+  if (!aligned16(h) || (row_stride * esz) % 16 != 0)
+    return fail(ctx, EH_ERR_SHAPE, "hidden rows must be 16-byte aligned");
+  return EH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* eh_version(void) { return "libeh 0.1 (gfx950)"; }
+
+const char* eh_last_error(const eh_ctx* ctx) {
+  return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) return fail(nullptr, EH_ERR_NULL, "cfg or out is NULL");
+  if (!cfg->W || !cfg->gamma || !cfg->beta || !cfg->tau)
+    return fail(nullptr, EH_ERR_NULL, "W, gamma, beta and tau are required");
+  if (cfg->d <= 0 || cfg->V <= 0 || cfg->n_heads <= 0 || cfg->max_rows <= 0)
+    return fail(nullptr, EH_ERR_SHAPE, "d, V, n_heads and max_rows must be positive");
+  if (cfg->w_dtype != EH_F32 && cfg->w_dtype != EH_BF16)
+    return fail(nullptr, EH_ERR_DTYPE, "unknown w_dtype");
+  if (cfg->w_dtype != cfg->h_dtype)
+    return fail(nullptr, EH_ERR_DTYPE, "w_dtype and h_dtype must match");
+  const int epl = cfg->w_dtype == EH_BF16 ? 8 : 4;
+  const int kpf = 4 * epl;
+  if (cfg->d % epl != 0)
+    return fail(nullptr, EH_ERR_SHAPE, "d must be a multiple of 16 bytes worth of elements");
+  if (!(cfg->ln_eps > 0.f) || !std::isfinite(cfg->ln_eps))
+    return fail(nullptr, EH_ERR_RANGE, "ln_eps must be positive and finite");
+  if ((int64_t)cfg->max_rows > (1 << 20)) return fail(nullptr, EH_ERR_RANGE, "max_rows too large");
+  for (int l = 0; l < cfg->n_heads; ++l) {
+    if (!cfg->W[l] || !cfg->gamma[l] || !cfg->beta[l] || (cfg->bias && !cfg->bias[l]))
+      return fail(nullptr, EH_ERR_NULL, "a per-head pointer is NULL");
+    if (!aligned16(cfg->W[l])) return fail(nullptr, EH_ERR_SHAPE, "W must be 16-byte aligned");
+  }
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev)
+    return fail(nullptr, EH_ERR_RANGE, "no such HIP device");
+
+  eh_ctx* c = new (std::nothrow) eh_ctx();
+  if (!c) return fail(nullptr, EH_ERR_HIP, "out of host memory");
+  c->d = cfg->d; c->V = cfg->V; c->n_heads = cfg->n_heads; c->max_rows = cfg->max_rows;
+  c->dtype = cfg->w_dtype; c->device = cfg->device; c->eps = cfg->ln_eps;
+  c->KS = (cfg->d + kpf - 1) / kpf;
+  c->VT = (cfg->V + 15) / 16;
+  c->R_pad_max = (cfg->max_rows + 15) & ~15;
+  c->tau.assign(cfg->tau, cfg->tau + cfg->n_heads);
+
+  DeviceGuard guard(c->device);
+  auto bail = [&](hipError_t e, const char* what) {
+    std::string msg = std::string(what) + ": " + hipGetErrorString(e);
+    free_all(c);
+    delete c;
+    return fail(nullptr, EH_ERR_HIP, msg);
+  };
+  hipError_t e;
+  const size_t wf_frags = (size_t)c->VT * c->KS * kWave;
+  const int Vp = c->VT * 16;
+  c->Wf.resize(c->n_heads); c->gamma.resize(c->n_heads); c->beta.resize(c->n_heads);
+  if (cfg->bias) c->bias.resize(c->n_heads);
+  for (int l = 0; l < c->n_heads; ++l) {
+    if ((e = dev_alloc(c, &c->Wf[l], wf_frags)) != hipSuccess) return bail(e, "hipMalloc(W)");
+    if ((e = dev_alloc(c, &c->gamma[l], (size_t)c->d)) != hipSuccess) return bail(e, "hipMalloc(gamma)");
+    if ((e = dev_alloc(c, &c->beta[l], (size_t)c->d)) != hipSuccess) return bail(e, "hipMalloc(beta)");
+    const unsigned blocks = (unsigned)((wf_frags + 255) / 256);
+    if (c->dtype == EH_BF16)
+      hipLaunchKernelGGL((repack_w_kernel<DtBf16>), dim3(blocks), dim3(256), 0, 0, cfg->W[l], c->V,
+                         c->d, c->VT, c->KS, c->Wf[l]);
+    else
+      hipLaunchKernelGGL((repack_w_kernel<DtF32>), dim3(blocks), dim3(256), 0, 0, cfg->W[l], c->V,
+                         c->d, c->VT, c->KS, c->Wf[l]);
+    if ((e = hipGetLastError()) != hipSuccess) return bail(e, "repack launch");
+    if ((e = hipMemcpy(c->gamma[l], cfg->gamma[l], sizeof(float) * c->d, hipMemcpyDeviceToDevice)) != hipSuccess)
+      return bail(e, "copy gamma");
+    if ((e = hipMemcpy(c->beta[l], cfg->beta[l], sizeof(float) * c->d, hipMemcpyDeviceToDevice)) != hipSuccess)
+      return bail(e, "copy beta");
+    if (cfg->bias) {
+      if ((e = dev_alloc(c, &c->bias[l], (size_t)Vp)) != hipSuccess) return bail(e, "hipMalloc(bias)");
+      if ((e = hipMemset(c->bias[l], 0, sizeof(float) * Vp)) != hipSuccess) return bail(e, "memset bias");
+      if ((e = hipMemcpy(c->bias[l], cfg->bias[l], sizeof(float) * c->V, hipMemcpyDeviceToDevice)) != hipSuccess)
+        return bail(e, "copy bias");
+    }
+  }
+  const size_t y_frags = (size_t)(c->R_pad_max / 16 + kMaxNB) * c->KS * kWave;
+  if ((e = dev_alloc(c, &c->yf, y_frags)) != hipSuccess) return bail(e, "hipMalloc(y)");
+  if ((e = hipMemset(c->yf, 0, y_frags * sizeof(frag_t))) != hipSuccess) return bail(e, "memset y");
+  if ((e = dev_alloc(c, &c->partials, (size_t)kStreamGrid * c->R_pad_max)) != hipSuccess)
+    return bail(e, "hipMalloc(partials)");
+  if ((e = dev_alloc(c, &c->ws_H, (size_t)c->max_rows)) != hipSuccess) return bail(e, "hipMalloc(ws)");
+  if ((e = dev_alloc(c, &c->ws_lse, (size_t)c->max_rows)) != hipSuccess) return bail(e, "hipMalloc(ws)");
+  if ((e = dev_alloc(c, &c->ws_argmax, (size_t)c->max_rows)) != hipSuccess) return bail(e, "hipMalloc(ws)");
+  for (int i = 0; i < 2; ++i) {
+    if ((e = dev_alloc(c, &c->active[i], (size_t)c->max_rows)) != hipSuccess) return bail(e, "hipMalloc(ws)");
+    if ((e = dev_alloc(c, &c->n_active[i], (size_t)4)) != hipSuccess) return bail(e, "hipMalloc(ws)");
+  }
+  if ((e = hipDeviceSynchronize()) != hipSuccess) return bail(e, "eh_create sync");
+  *out = c;
+  return EH_OK;
+}
+
+eh_status eh_destroy(eh_ctx* ctx) {
+  if (!ctx) return EH_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  (void)hipDeviceSynchronize();
+  free_all(ctx);
+  delete ctx;
+  return EH_OK;
+}
+
+eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride,
+                  const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows, float* H,
+                  float* lse, int32_t* argmax, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (head < 0 || head >= ctx->n_heads) return fail(ctx, EH_ERR_RANGE, "head out of range");
+  if (n_rows == 0) return EH_OK;
+  if (!h) return fail(ctx, EH_ERR_NULL, "h is NULL");
+  eh_status st = check_rows(ctx, h, h_row_stride, n_rows);
+  if (st != EH_OK) return st;
+  DeviceGuard guard(ctx->device);
+  return run_head<false>(ctx, head, h, h_row_stride, row_idx, n_rows_dev, n_rows, H, lse, argmax,
+                         (hipStream_t)stream);
+}
+
+eh_status eh_exit_decide(eh_ctx* ctx, int32_t head, const float* H, const int32_t* argmax,
+                         const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows,
+                         int32_t* exit_layer, int32_t* token, int32_t* active_idx_out,
+                         int32_t* n_active_out, float tau_override, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (head < 0 || head >= ctx->n_heads) return fail(ctx, EH_ERR_RANGE, "head out of range");
+  if (n_rows < 0 || n_rows > ctx->max_rows) return fail(ctx, EH_ERR_WORKSPACE, "n_rows outside [0, max_rows]");
+  if (!H || !argmax || !exit_layer || !token || !active_idx_out || !n_active_out)
+    return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
+  if (active_idx_out == row_idx) return fail(ctx, EH_ERR_RANGE, "active_idx_out must not alias row_idx");
+  DeviceGuard guard(ctx->device);
+  const float tau = std::isnan(tau_override) ? ctx->tau[head] : tau_override;
+  hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, H, argmax, row_idx,
+                     n_rows_dev, n_rows, tau, head == ctx->n_heads - 1 ? 1 : 0, head, exit_layer, token,
+                     active_idx_out, n_active_out, (float*)nullptr, (unsigned long long*)nullptr);
+  EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
+}
+
+eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride, int64_t row_stride,
+                     int32_t n_rows, int32_t* exit_layer, int32_t* token, float* H_out,
+                     int64_t* n_evals_out, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (n_rows == 0) return EH_OK;
+  if (!h_layers || !exit_layer || !token) return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
+  eh_status st = check_rows(ctx, h_layers, row_stride, n_rows);
+  if (st != EH_OK) return st;
+  const int esz = ctx->dtype == EH_BF16 ? 2 : 4;
+  if (ctx->n_heads > 1 && (layer_stride * esz) % 16 != 0)
+    return fail(ctx, EH_ERR_SHAPE, "layer stride must keep rows 16-byte aligned");
+  DeviceGuard guard(ctx->device);
+  hipStream_t s = (hipStream_t)stream;
+  if (H_out) {
+    const int64_t n = (int64_t)ctx->n_heads * n_rows;
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, H_out, n, NAN);
+  }
+  for (int l = 0; l < ctx->n_heads; ++l) {
+    const int* idx = l == 0 ? nullptr : ctx->active[(l - 1) & 1];
+    const int* cnt = l == 0 ? nullptr : ctx->n_active[(l - 1) & 1];
+    const void* hl = (const char*)h_layers + (int64_t)l * layer_stride * esz;
+    st = run_head<false>(ctx, l, hl, row_stride, idx, cnt, n_rows, ctx->ws_H, ctx->ws_lse,
+                         ctx->ws_argmax, s);
+    if (st != EH_OK) return st;
+    hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(256), 0, s, ctx->ws_H, ctx->ws_argmax, idx, cnt,
+                       n_rows, ctx->tau[l], l == ctx->n_heads - 1 ? 1 : 0, l, exit_layer, token,
+                       ctx->active[l & 1], ctx->n_active[l & 1],
+                       H_out ? H_out + (int64_t)l * n_rows : nullptr, (unsigned long long*)n_evals_out);
+  }
+  EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
+}
+
+eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, const int32_t* draft_len,
+                      int32_t B, int32_t k, int32_t* accepted, int32_t* next_token, int32_t* target,
+                      void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (B < 0 || k < 0) return fail(ctx, EH_ERR_SHAPE, "B and k must be non-negative");
+  if (B == 0) return EH_OK;
+  if (!f_final || !accepted || !next_token || (k > 0 && !draft))
+    return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
+  const int64_t rows = (int64_t)B * (k + 1);
+  if (rows > ctx->max_rows) return fail(ctx, EH_ERR_WORKSPACE, "B*(k+1) exceeds max_rows");
+  eh_status st = check_rows(ctx, f_final, ctx->d, (int)rows);
+  if (st != EH_OK) return st;
+  DeviceGuard guard(ctx->device);
+  hipStream_t s = (hipStream_t)stream;
+  int* tgt = target ? target : ctx->ws_argmax;
+  st = run_head<true>(ctx, ctx->n_heads - 1, f_final, ctx->d, nullptr, nullptr, (int)rows, nullptr,
+                      nullptr, tgt, s);
+  if (st != EH_OK) return st;
+  hipLaunchKernelGGL(verify_compare_kernel, dim3((B + 63) / 64), dim3(64), 0, s, draft, draft_len, tgt, B,
+                     k, accepted, next_token);
+  EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
+}
+
+}  // extern "C"

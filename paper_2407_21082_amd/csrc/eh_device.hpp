@@ -1,0 +1,147 @@
+// Device-side building blocks shared by the libeh kernels (gfx950 only).
+//
+// Data layout ("fragment-major"): both GEMM operands are kept in HBM in the
+// order the 16x16 matrix-core instructions consume them, so that every wave
+// load is one contiguous, fully coalesced 1 KiB read and no LDS transpose is
+// needed.  A fragment is 64 lanes x 16 bytes:
+//   lane = q*16 + r  (r = lane % 16, q = lane / 16)
+//   W fragment (vt, ks):  lane holds W[vt*16 + r][ks*KPF + q*EPL .. +EPL)
+//   y fragment (nb, ks):  lane holds y[nb*16 + r][ks*KPF + q*EPL .. +EPL)
+// with EPL = elements per 16 bytes (8 bf16 / 4 f32) and KPF = 4*EPL the k
+// extent of a fragment.  Fragments are stored [tile][ks][lane].  Rows beyond V
+// (or beyond the live rows) and k beyond d are zero.
+//
+// One fragment pair feeds v_mfma_f32_16x16x32_bf16 (bf16) or four
+// v_mfma_f32_16x16x4_f32 (f32); lane (q, r) of A meets lane (q, n) of B on the
+// same k values, which is all the dot product needs.  The accumulator of a
+// 16x16 product holds, in lane l and register i, output row 4*(l/16)+i (a
+// vocabulary row) and column l%16 (a token): the softmax reduction over the
+// vocabulary therefore runs down registers and over time inside a lane, and
+// only the final merge crosses lanes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace eh {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t frag_t __attribute__((ext_vector_type(4)));  // 16 bytes of one lane
+__device__ __forceinline__ frag_t mk_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  return frag_t{a, b, c, d};
+}
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr double kLn2d = 0.69314718055994530942;
+constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no maximum yet" / masked rows
+
+struct DtBf16 {
+  static constexpr int EPL = 8;   // elements per lane per fragment
+  static constexpr int KPF = 32;  // k extent of a fragment
+  static constexpr int ESZ = 2;
+  static __device__ __forceinline__ f32x4 mma(const frag_t& a, const frag_t& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+
+struct DtF32 {
+  static constexpr int EPL = 4;
+  static constexpr int KPF = 16;
+  static constexpr int ESZ = 4;
+  static __device__ __forceinline__ f32x4 mma(const frag_t& a, const frag_t& b, f32x4 c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    return c;
+  }
+};
+
+// fp32 -> bf16, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Running softmax statistics of a set of logits z_i, kept in the base-2 domain
+// t_i = z_i * log2(e):  m = max t,  S = sum 2^(t-m),  U = sum (t-m) 2^(t-m),
+// (zb, ib) = largest logit and the lowest index attaining it.
+// Entropy (nats) = ln2 * (log2 S - U/S);  lse = ln2 * (m + log2 S).
+struct Stats {
+  float m, S, U, zb;
+  int ib;
+};
+
+__device__ __forceinline__ void stats_init(Stats& s) {
+  s.m = kNegBig; s.S = 0.f; s.U = 0.f; s.zb = -INFINITY; s.ib = 0x7fffffff;
+}
+
+// Associative merge: rescale both sides to the common maximum.
+__device__ __forceinline__ Stats stats_merge(const Stats& a, const Stats& b) {
+  Stats r;
+  const bool bw = (b.zb > a.zb) || (b.zb == a.zb && b.ib < a.ib);
+  r.zb = bw ? b.zb : a.zb;
+  r.ib = bw ? b.ib : a.ib;
+  const float m = fmaxf(a.m, b.m);
+  const float da = a.m - m, db = b.m - m;
+  const float ea = fast_exp2(da), eb = fast_exp2(db);
+  r.S = ea * a.S + eb * b.S;
+  r.U = ea * (a.U + da * a.S) + eb * (b.U + db * b.S);
+  r.m = m;
+  return r;
+}
+
+// Push four logits of consecutive vocabulary rows row0..row0+3 (rows >= V are
+// padding and ignored).  Rows must arrive in increasing order within a lane so
+// that "strictly greater" keeps the lowest index.
+template <bool ARGMAX_ONLY>
+__device__ __forceinline__ void stats_push4(Stats& s, f32x4 z, int row0, int V) {
+  if (row0 + 3 >= V) {
+    if (row0 + 0 >= V) z[0] = kNegBig;
+    if (row0 + 1 >= V) z[1] = kNegBig;
+    if (row0 + 2 >= V) z[2] = kNegBig;
+    if (row0 + 3 >= V) z[3] = kNegBig;
+  }
+  const float zmax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+  if (zmax > s.zb) {
+    const int j = (z[0] == zmax) ? 0 : (z[1] == zmax) ? 1 : (z[2] == zmax) ? 2 : 3;
+    if (!ARGMAX_ONLY) {
+      const float mn = zmax * kLog2e;
+      const float dm = s.m - mn;
+      const float sc = fast_exp2(dm);
+      s.U = sc * (s.U + dm * s.S);
+      s.S = sc * s.S;
+      s.m = mn;
+    }
+    s.zb = zmax;
+    s.ib = row0 + j;
+  }
+  if (!ARGMAX_ONLY) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float t = z[i] * kLog2e - s.m;   // <= 0 for finite logits
+      const float e = fast_exp2(t);
+      s.S += e;
+      s.U += t * e;
+    }
+  }
+}
+
+__device__ __forceinline__ Stats stats_shfl_xor(const Stats& s, int mask) {
+  Stats o;
+  o.m = __shfl_xor(s.m, mask);
+  o.S = __shfl_xor(s.S, mask);
+  o.U = __shfl_xor(s.U, mask);
+  o.zb = __shfl_xor(s.zb, mask);
+  o.ib = __shfl_xor(s.ib, mask);
+  return o;
+}
+
+}  // namespace eh

@@ -1,0 +1,353 @@
+// General-purpose kernels of libeh: weight re-tiling, LayerNorm + packing,
+// the streaming projection with fused softmax statistics, the cross-workgroup
+// merge, the exit decision with compaction and the DSSD prefix compare.
+// (arXiv 2407.21082: Section 3.2 heads, 3.4.1 entropy/argmax, 3.4.2 exit rule,
+// 4.3.1 verification.)
+#pragma once
+#include "eh_device.hpp"
+
+namespace eh {
+
+// ---------------------------------------------------------------------------
+// Row-major W [V, d] -> fragment-major copy (done once, at context creation).
+// One thread per 16-byte chunk of the destination.
+// ---------------------------------------------------------------------------
+template <typename DT>
+__global__ __launch_bounds__(256) void repack_w_kernel(const void* __restrict__ W, int V, int d,
+                                                       int VT, int KS, frag_t* __restrict__ Wf) {
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (int64_t)VT * KS * kWave;
+  if (o >= total) return;
+  const int lane = (int)(o % kWave);
+  const int64_t f = o / kWave;
+  const int ks = (int)(f % KS);
+  const int vt = (int)(f / KS);
+  const int r = lane & 15, q = lane >> 4;
+  const int row = vt * 16 + r;
+  const int k0 = ks * DT::KPF + q * DT::EPL;
+  frag_t v = mk_frag(0, 0, 0, 0);
+  if (row < V && k0 < d) {
+    const char* src = (const char*)W + ((int64_t)row * d + k0) * DT::ESZ;
+    v = *(const frag_t*)src;  // d % EPL == 0 and a 16-byte aligned base are checked by the host
+  }
+  Wf[o] = v;
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm of each live row, written as y fragments.  One wave per output
+// position p (gathered through row_idx).  Mean and variance are two-pass and
+// the whole normalisation runs in fp64: it costs nothing at these sizes and it
+// makes the bf16 rounding of y independent of the reduction order.
+// Positions >= live rows (up to R_pad) are zero-filled.
+// ---------------------------------------------------------------------------
+template <typename DT>
+__device__ __forceinline__ void load_elems(const void* row, int k0, float (&x)[DT::EPL]);
+
+template <>
+__device__ __forceinline__ void load_elems<DtBf16>(const void* row, int k0, float (&x)[8]) {
+  const frag_t v = *(const frag_t*)((const char*)row + (int64_t)k0 * 2);
+  x[0] = bf16_bits_to_f32(v.x & 0xffffu); x[1] = bf16_bits_to_f32(v.x >> 16);
+  x[2] = bf16_bits_to_f32(v.y & 0xffffu); x[3] = bf16_bits_to_f32(v.y >> 16);
+  x[4] = bf16_bits_to_f32(v.z & 0xffffu); x[5] = bf16_bits_to_f32(v.z >> 16);
+  x[6] = bf16_bits_to_f32(v.w & 0xffffu); x[7] = bf16_bits_to_f32(v.w >> 16);
+}
+template <>
+__device__ __forceinline__ void load_elems<DtF32>(const void* row, int k0, float (&x)[4]) {
+  const float4 v = *(const float4*)((const char*)row + (int64_t)k0 * 4);
+  x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+}
+
+template <typename DT>
+__device__ __forceinline__ frag_t pack_elems(const double (&y)[DT::EPL]);
+template <>
+__device__ __forceinline__ frag_t pack_elems<DtBf16>(const double (&y)[8]) {
+  uint32_t b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) b[i] = f32_to_bf16_bits((float)y[i]);
+  return mk_frag(b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16));
+}
+template <>
+__device__ __forceinline__ frag_t pack_elems<DtF32>(const double (&y)[4]) {
+  return mk_frag(__float_as_uint((float)y[0]), __float_as_uint((float)y[1]),
+                    __float_as_uint((float)y[2]), __float_as_uint((float)y[3]));
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// LayerNorm of one row by one wave; out(c, chunk) receives the packed chunk c
+// (EPL consecutive outputs starting at k = c*EPL) for every c < n_chunks.
+template <typename DT, typename OutFn>
+__device__ __forceinline__ void wave_layernorm(const void* row, int d, int n_chunks,
+                                               const float* __restrict__ gamma,
+                                               const float* __restrict__ beta, float eps, int lane,
+                                               OutFn out) {
+  const int live_chunks = d / DT::EPL;
+  double s = 0.0;
+  for (int c = lane; c < live_chunks; c += kWave) {
+    float x[DT::EPL];
+    load_elems<DT>(row, c * DT::EPL, x);
+#pragma unroll
+    for (int i = 0; i < DT::EPL; ++i) s += (double)x[i];
+  }
+  const double mu = wave_sum(s) / (double)d;
+  double v = 0.0;
+  for (int c = lane; c < live_chunks; c += kWave) {
+    float x[DT::EPL];
+    load_elems<DT>(row, c * DT::EPL, x);
+#pragma unroll
+    for (int i = 0; i < DT::EPL; ++i) {
+      const double cdev = (double)x[i] - mu;
+      v += cdev * cdev;
+    }
+  }
+  const double var = wave_sum(v) / (double)d;
+  const double rstd = 1.0 / sqrt(var + (double)eps);
+  for (int c = lane; c < n_chunks; c += kWave) {
+    frag_t o = mk_frag(0, 0, 0, 0);
+    if (c < live_chunks) {
+      float x[DT::EPL];
+      load_elems<DT>(row, c * DT::EPL, x);
+      double y[DT::EPL];
+#pragma unroll
+      for (int i = 0; i < DT::EPL; ++i) {
+        const int k = c * DT::EPL + i;
+        y[i] = (double)gamma[k] * (((double)x[i] - mu) * rstd) + (double)beta[k];
+      }
+      o = pack_elems<DT>(y);
+    }
+    out(c, o);
+  }
+}
+
+template <typename DT>
+__global__ __launch_bounds__(256) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
+                                                      const int* __restrict__ row_idx,
+                                                      const int* __restrict__ n_rows_dev, int n_rows,
+                                                      int R_pad, int d, int KS,
+                                                      const float* __restrict__ gamma,
+                                                      const float* __restrict__ beta, float eps,
+                                                      frag_t* __restrict__ yf) {
+  const int lane = threadIdx.x & 63;
+  const int p = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (p >= R_pad) return;
+  int n_live = n_rows;
+  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  const int nb = p >> 4, n = p & 15;
+  const int n_chunks = KS * 4;
+  frag_t* dst = yf + (int64_t)nb * KS * kWave;
+  auto put = [&](int c, const frag_t& v) { dst[(c >> 2) * kWave + (c & 3) * 16 + n] = v; };
+  if (p >= n_live) {
+    for (int c = lane; c < n_chunks; c += kWave) put(c, mk_frag(0, 0, 0, 0));
+    return;
+  }
+  const int64_t r = row_idx ? row_idx[p] : p;
+  const void* row = (const char*)h + r * row_stride * DT::ESZ;
+  wave_layernorm<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+}
+
+// ---------------------------------------------------------------------------
+// Streaming projection with fused softmax statistics (general row counts).
+// Each wave owns whole vocabulary tiles (16 rows, all of k) and NB token
+// blocks; both operands come straight from global memory in fragment order.
+// The logits live only in the accumulators.  Per workgroup one Stats record
+// per token is written to `partials[blockIdx.x][R_pad]`.
+// ---------------------------------------------------------------------------
+template <typename DT, int NB, bool ARGMAX_ONLY>
+__global__ __launch_bounds__(256) void stream_kernel(const frag_t* __restrict__ Wf,
+                                                     const frag_t* __restrict__ yf,
+                                                     const float* __restrict__ bias, int VT, int KS,
+                                                     int V, int nb0, const int* __restrict__ n_rows_dev,
+                                                     int n_rows, int R_pad, Stats* __restrict__ partials) {
+  __shared__ Stats red[4][NB][16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int q = lane >> 4, n = lane & 15;
+  int n_live = n_rows;
+  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  const int nb_live = min(NB, (n_live - nb0 * 16 + 15) >> 4);
+  if (nb_live <= 0) return;  // uniform over the grid
+
+  Stats st[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) stats_init(st[b]);
+
+  const int gw = blockIdx.x * 4 + wave, tw = gridDim.x * 4;
+  const frag_t* yp = yf + (int64_t)nb0 * KS * kWave + lane;
+  for (int vt = gw; vt < VT; vt += tw) {
+    f32x4 acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const frag_t* wp = Wf + (int64_t)vt * KS * kWave + lane;
+    constexpr int U = (NB <= 1) ? 8 : (NB <= 2) ? 4 : 2;
+    int ks = 0;
+    for (; ks + U <= KS; ks += U) {
+      frag_t a[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(wp + (int64_t)(ks + u) * kWave);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          if (b < nb_live) {
+            const frag_t y = yp[((int64_t)b * KS + ks + u) * kWave];
+            acc[b] = DT::mma(a[u], y, acc[b]);
+          }
+        }
+      }
+    }
+    for (; ks < KS; ++ks) {
+      const frag_t a = __builtin_nontemporal_load(wp + (int64_t)ks * kWave);
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        if (b < nb_live) {
+          const frag_t y = yp[((int64_t)b * KS + ks) * kWave];
+          acc[b] = DT::mma(a, y, acc[b]);
+        }
+      }
+    }
+    const int row0 = vt * 16 + q * 4;
+    f32x4 bz = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (bias) bz = *(const f32x4*)(bias + row0);  // bias is padded to VT*16 entries
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      if (b < nb_live) stats_push4<ARGMAX_ONLY>(st[b], acc[b] + bz, row0, V);
+    }
+  }
+
+  // lanes n, n+16, n+32, n+48 hold the same token: fold the four row groups
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    st[b] = stats_merge(st[b], stats_shfl_xor(st[b], 16));
+    st[b] = stats_merge(st[b], stats_shfl_xor(st[b], 32));
+    if (q == 0) red[wave][b][n] = st[b];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < NB * 16; i += blockDim.x) {
+    const int b = i >> 4, t = i & 15;
+    if (b < nb_live) {
+      Stats s = red[0][b][t];
+      s = stats_merge(s, red[1][b][t]);
+      s = stats_merge(s, red[2][b][t]);
+      s = stats_merge(s, red[3][b][t]);
+      partials[(int64_t)blockIdx.x * R_pad + (nb0 + b) * 16 + t] = s;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Merge the per-workgroup partials of each live row and finalise:
+// H = ln2 (log2 S - U/S), lse = ln2 (m + log2 S), argmax = ib.
+// One wave per row.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void stats_finalize(const Stats& s, float& H, float& lse) {
+  const double S = (double)s.S, U = (double)s.U;
+  const double l2 = log2(S);
+  H = (float)(kLn2d * (l2 - U / S));
+  lse = (float)(kLn2d * ((double)s.m + l2));
+}
+
+__global__ __launch_bounds__(64) void finalize_kernel(const Stats* __restrict__ partials, int n_parts,
+                                                      int R_pad, const int* __restrict__ n_rows_dev,
+                                                      int n_rows, float* __restrict__ H,
+                                                      float* __restrict__ lse, int* __restrict__ argmax) {
+  const int p = blockIdx.x, lane = threadIdx.x;
+  int n_live = n_rows;
+  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  if (p >= n_live) return;
+  Stats s;
+  stats_init(s);
+  for (int g = lane; g < n_parts; g += kWave) s = stats_merge(s, partials[(int64_t)g * R_pad + p]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s = stats_merge(s, stats_shfl_xor(s, o));
+  if (lane == 0) {
+    float h, l;
+    stats_finalize(s, h, l);
+    if (H) H[p] = h;
+    if (lse) lse[p] = l;
+    if (argmax) argmax[p] = s.ib;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Exit rule + stable compaction.  Single workgroup; positions are processed in
+// chunks of blockDim.x with a block-wide exclusive scan of the "stays" flags.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void decide_kernel(const float* __restrict__ H,
+                                                     const int* __restrict__ argmax,
+                                                     const int* __restrict__ row_idx,
+                                                     const int* __restrict__ n_rows_dev, int n_rows,
+                                                     float tau, int is_last, int head,
+                                                     int* __restrict__ exit_layer, int* __restrict__ token,
+                                                     int* __restrict__ active_out,
+                                                     int* __restrict__ n_active_out,
+                                                     float* __restrict__ H_out,
+                                                     unsigned long long* __restrict__ n_evals) {
+  __shared__ int wave_tot[4];
+  __shared__ int base_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int n_live = n_rows;
+  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  if (tid == 0) base_s = 0;
+  __syncthreads();
+  for (int start = 0; start < n_live; start += blockDim.x) {
+    const int p = start + tid;
+    const bool valid = p < n_live;
+    int r = 0;
+    bool stays = false;
+    if (valid) {
+      r = row_idx ? row_idx[p] : p;
+      const float hp = H[p];
+      const bool leaves = is_last || (hp < tau);
+      stays = !leaves;
+      if (leaves) {
+        exit_layer[r] = head;
+        token[r] = argmax[p];
+      }
+      if (H_out) H_out[r] = hp;
+    }
+    const unsigned long long bal = __ballot(stays);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int off = base_s;
+    for (int w = 0; w < wave; ++w) off += wave_tot[w];
+    if (stays) active_out[off + before] = r;
+    __syncthreads();
+    if (tid == 0) base_s += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    if (n_active_out) *n_active_out = base_s;
+    if (n_evals) *n_evals += (unsigned long long)n_live;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// DSSD: length of the accepted prefix and the token that follows it.
+// ---------------------------------------------------------------------------
+__global__ void verify_compare_kernel(const int* __restrict__ draft, const int* __restrict__ draft_len,
+                                      const int* __restrict__ target, int B, int k,
+                                      int* __restrict__ accepted, int* __restrict__ next_token) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int len = k;
+  if (draft_len) len = min(max(draft_len[b], 0), k);
+  int n = 0;
+  while (n < len && draft[(int64_t)b * k + n] == target[(int64_t)b * (k + 1) + n]) ++n;
+  accepted[b] = n;
+  next_token[b] = target[(int64_t)b * (k + 1) + n];
+}
+
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void fill_i32_kernel(int* p, int64_t n, int v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+}  // namespace eh

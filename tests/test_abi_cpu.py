@@ -1,0 +1,85 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching a device."""
+import ctypes as C
+import math
+import os
+import re
+
+import pytest
+
+from paper_2407_21082_amd import binding as B
+from workloads import generators as G
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "eh.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(eh_[a-z_]+|dssd_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(B.lib, n), f"libeh.so does not export {n}"
+    assert "gfx950" in B.eh_version()
+
+
+def _cfg(**kw):
+    one = (C.c_void_p * 1)(16)
+    tau = (C.c_float * 1)(1.0)
+    base = dict(d=64, V=100, n_heads=1, max_rows=4, w_dtype=B.EH_BF16, h_dtype=B.EH_BF16, ln_eps=1e-5,
+                device=0, W=one, gamma=one, beta=one, bias=None, tau=tau)
+    base.update(kw)
+    return B._Config(**base)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(d=0), 2), (dict(V=-1), 2), (dict(n_heads=0), 2), (dict(max_rows=0), 2),
+    (dict(w_dtype=7, h_dtype=7), 3), (dict(h_dtype=B.EH_F32), 3), (dict(d=12), 2),
+    (dict(ln_eps=0.0), 4), (dict(W=None), 1), (dict(tau=None), 1),
+    (dict(W=(C.c_void_p * 1)(8)), 2),          # misaligned weight pointer
+])
+def test_create_rejects_bad_config_on_host(kw, status):
+    out = C.c_void_p()
+    st = B.lib.eh_create(C.byref(_cfg(**kw)), C.byref(out))
+    assert st == status and not out.value
+    assert B.lib.eh_last_error(None)           # a message is always available
+
+
+def test_null_arguments():
+    assert B.lib.eh_create(None, None) == 1
+    assert B.lib.eh_destroy(None) == 1
+    assert B.lib.eh_eval(None, 0, None, 0, None, None, 0, None, None, None, None) == 1
+    assert B.lib.dssd_verify(None, None, None, None, 1, 1, None, None, None, None) == 1
+
+
+# ---------------------------------------------------------------- generators
+def test_generators_are_seeded_and_shaped():
+    w = G.Workload("t", d=64, V=500, n_heads=3, rows=10, dtype="bf16", seed=3)
+    a, b = G.make_heads(w), G.make_heads(w)
+    assert all((x == y).all() for x, y in zip(a.W, b.W))
+    assert a.W[0].shape == (500, 64) and a.gamma[0].dtype.is_floating_point
+    h1, h2 = G.make_hidden(w, a), G.make_hidden(w, b)
+    assert (h1.h == h2.h).all() and h1.h.shape == (3, 10, 64)
+    assert (h1.s >= w.s_lo).all() and (h1.s <= w.s_hi).all()
+    tau = G.tau_linear(w)
+    assert tau[0] == pytest.approx(0.5) and tau[1] == pytest.approx(3.0) and math.isinf(tau[2])
+
+
+def test_tau_for_schedule_follows_the_fractions():
+    import numpy as np
+    rng = np.random.default_rng(0)
+    n, R = 32, 64
+    H = np.sort(rng.uniform(0, 10, size=(n, R)), axis=0)[::-1] + rng.uniform(0, 1e-3, size=(n, R))
+    tau = G.tau_for_schedule(H, n)
+    active = np.ones(R, bool)
+    for l in range(n - 1):
+        active &= ~(H[l] < tau[l])
+        want = round(G.exit_schedule_fraction(l, n) * R)
+        assert abs((R - active.sum()) - want) <= 1
+    assert G.exit_schedule_fraction(7, 32) == pytest.approx(0.10)
+    assert G.exit_schedule_fraction(15, 32) == pytest.approx(0.40)
+    assert G.exit_schedule_fraction(23, 32) == pytest.approx(0.70)

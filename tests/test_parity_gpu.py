@@ -1,0 +1,317 @@
+"""GPU-vs-oracle parity, through the C ABI, on seeded synthetic inputs.
+
+Small ragged shapes exercise tile tails and every launch variant; the five
+workload configurations then run at their real sizes, compared either in full
+or on a stated sample of rows/steps the oracle can afford.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import eh_oracle as O
+from workloads import generators as G
+from tests import parity_util as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2407_21082_amd import binding
+    return binding
+
+
+def _outs(n):
+    return (torch.full((n,), float("nan"), device=DEV), torch.full((n,), float("nan"), device=DEV),
+            torch.full((n,), -7, dtype=torch.int32, device=DEV))
+
+
+def _eval_all(B, ctx, heads, hid, R, bf16, name, log, rows=None):
+    for l in range(len(heads.W)):
+        H, lse, am = _outs(R)
+        B.eh_eval(ctx, l, hid.h[l], R, H, lse, am)
+        torch.cuda.synchronize()
+        sel = slice(None) if rows is None else rows
+        orc = P.oracle_head(hid.h[l][sel], heads.gamma[l], heads.beta[l], heads.W[l], bf16)
+        P.compare_head(f"{name}/head{l}", H[sel], lse[sel], am[sel], orc, log)
+
+
+# --------------------------------------------------------------- small shapes
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V,d,R", [(1000, 200, 1), (1000, 200, 5), (4099 - 3, 96, 17), (777, 512, 37),
+                                    (2048, 256, 161), (16, 32, 16), (50, 8, 3)])
+def test_small_ragged_shapes(B, dtype, V, d, R):
+    if dtype == "f32" and d % 4:
+        pytest.skip("d must hold whole 16-byte groups")
+    w = G.Workload("small", d=d, V=V, n_heads=3, rows=R, dtype=dtype, seed=V * 31 + d + R)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    log = []
+    _eval_all(B, ctx, heads, hid, R, dtype == "bf16", f"small{V}x{d}x{R}", log)
+    B.eh_destroy(ctx)
+
+
+def test_bias_and_strided_rows(B):
+    w = G.Workload("bias", d=128, V=520, n_heads=1, rows=9, dtype="bf16", seed=5)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    gen = torch.Generator(device=DEV); gen.manual_seed(3)
+    bias = [torch.randn(w.V, generator=gen, device=DEV) * 2]
+    wide = torch.zeros((9, 256), dtype=torch.bfloat16, device=DEV)
+    wide[:, :128] = hid.h[0]
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")], max_rows=16, bias=bias)
+    H, lse, am = _outs(9)
+    B.eh_eval(ctx, 0, wide, 9, H, lse, am, row_stride=256)
+    torch.cuda.synchronize()
+    orc = O.head_eval(P.f64(hid.h[0]), P.f64(heads.gamma[0]), P.f64(heads.beta[0]), P.f64(heads.W[0]),
+                      1e-5, True, bias=P.f64(bias[0]))
+    P.compare_head("bias", H, lse, am, orc, [])
+    B.eh_destroy(ctx)
+
+
+def test_gather_and_device_row_count(B):
+    w = G.Workload("gather", d=256, V=3000, n_heads=1, rows=40, dtype="bf16", seed=11)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")], max_rows=40)
+    idx = torch.tensor([39, 0, 7, 7, 21, 3, 38, 12, 1, 30, 2], dtype=torch.int32, device=DEV)
+    n_dev = torch.tensor([9], dtype=torch.int32, device=DEV)        # only the first 9 are live
+    H, lse, am = _outs(11)
+    B.eh_eval(ctx, 0, hid.h[0], 11, H, lse, am, row_idx=idx, n_rows_dev=n_dev)
+    torch.cuda.synchronize()
+    sel = idx[:9].long()
+    orc = P.oracle_head(hid.h[0][sel], heads.gamma[0], heads.beta[0], heads.W[0], True)
+    P.compare_head("gather", H[:9], lse[:9], am[:9], orc, [])
+    assert torch.isnan(H[9:]).all() and (am[9:] == -7).all()     # dead positions untouched
+    B.eh_destroy(ctx)
+
+
+def test_exit_decide_and_manual_cascade_equals_eh_cascade(B):
+    w = G.Workload("casc", d=128, V=2000, n_heads=6, rows=70, dtype="bf16", seed=17, kappa=0.6)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    R, n = w.rows, w.n_heads
+    full = P.oracle_all_heads(heads, hid.h, True)
+    tau = G.tau_for_schedule(full[0], n)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=R)
+    # library cascade
+    ex = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    tok = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    Hout = torch.zeros((n, R), device=DEV)
+    nev = torch.zeros(1, dtype=torch.int64, device=DEV)
+    B.eh_cascade(ctx, hid.h, R, ex, tok, Hout, nev)
+    torch.cuda.synchronize()
+    log = []
+    P.compare_cascade("casc", ex, tok, Hout, full[0], full[2], full[3], tau, log)
+    assert len(set(ex.tolist())) >= 4
+    assert int(nev.item()) == int((ex.long() + 1).sum().item())
+    # the same thing through eh_eval + eh_exit_decide
+    ex2 = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    tok2 = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    act = [torch.zeros(R, dtype=torch.int32, device=DEV) for _ in range(2)]
+    cnt = [torch.zeros(1, dtype=torch.int32, device=DEV) for _ in range(2)]
+    H, lse, am = _outs(R)
+    for l in range(n):
+        idx = None if l == 0 else act[(l - 1) & 1]
+        c = None if l == 0 else cnt[(l - 1) & 1]
+        B.eh_eval(ctx, l, hid.h[l], R, H, lse, am, row_idx=idx, n_rows_dev=c)
+        B.eh_exit_decide(ctx, l, H, am, R, ex2, tok2, act[l & 1], cnt[l & 1], row_idx=idx, n_rows_dev=c)
+        torch.cuda.synchronize()
+        live = cnt[l & 1].item()
+        expect = [r for r in range(R) if ex2[r].item() < 0]
+        assert act[l & 1][:live].tolist() == expect          # stable compaction
+    assert torch.equal(ex, ex2) and torch.equal(tok, tok2)
+    B.eh_destroy(ctx)
+
+
+def test_nan_row_is_defined_behaviour(B):
+    w = G.Workload("nan", d=64, V=300, n_heads=2, rows=4, dtype="f32", seed=23)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    hid.h[0, 2, 5] = float("nan")
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [100.0, float("inf")], max_rows=4)
+    ex = torch.full((4,), -1, dtype=torch.int32, device=DEV)
+    tok = torch.full((4,), -1, dtype=torch.int32, device=DEV)
+    Hout = torch.zeros((2, 4), device=DEV)
+    B.eh_cascade(ctx, hid.h, 4, ex, tok, Hout, None)
+    torch.cuda.synchronize()
+    assert math.isnan(Hout[0, 2].item())
+    assert ex.tolist() == [0, 0, 1, 0]          # NaN never passes the test; falls to the final head
+    B.eh_destroy(ctx)
+
+
+def test_determinism(B):
+    w = G.scaled(G.CONFIGS["c1_decode"], n_heads=2, rows=8)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=8)
+    ref = None
+    for _ in range(20):
+        H, lse, am = _outs(8)
+        B.eh_eval(ctx, 1, hid.h[1], 8, H, lse, am)
+        torch.cuda.synchronize()
+        cur = (H.clone(), lse.clone(), am.clone())
+        if ref is not None:
+            assert all(torch.equal(a, b) for a, b in zip(ref, cur))
+        ref = cur
+    B.eh_destroy(ctx)
+
+
+# --------------------------------------------------------------- config 0
+def test_c0_tiny_full(B):
+    w = G.CONFIGS["c0_tiny"]
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    tau = G.tau_linear(w)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=w.rows)
+    log = []
+    _eval_all(B, ctx, heads, hid, w.rows, False, "c0", log)
+    full = P.oracle_all_heads(heads, hid.h, False)
+    ex = torch.full((w.rows,), -1, dtype=torch.int32, device=DEV)
+    tok = torch.full((w.rows,), -1, dtype=torch.int32, device=DEV)
+    Hout = torch.zeros((w.n_heads, w.rows), device=DEV)
+    B.eh_cascade(ctx, hid.h, w.rows, ex, tok, Hout, None)
+    torch.cuda.synchronize()
+    P.compare_cascade("c0", ex, tok, Hout, full[0], full[2], full[3], tau, log)
+    print("c0 exit layers:", ex.tolist(), "near-ties:", log)
+    B.eh_destroy(ctx)
+
+
+# --------------------------------------------------------------- config 1
+def test_c1_decode_steps(B):
+    """Batch-1 cascades over 2048 seeded decode steps; the oracle checks a
+    sample of 48 steps in full (every head), plus range properties on all."""
+    w = G.CONFIGS["c1_decode"]
+    heads = G.make_heads(w, DEV)
+    steps = w.steps
+    hid = G.make_hidden(w, heads, DEV, rows=steps)        # [24, 2048, 1024]: row t = decode step t
+    tau = G.tau_linear(w)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=1)
+    ex = torch.full((steps,), -1, dtype=torch.int32, device=DEV)
+    tok = torch.full((steps,), -1, dtype=torch.int32, device=DEV)
+    Hout = torch.zeros((steps, w.n_heads), device=DEV)
+    nev = torch.zeros(1, dtype=torch.int64, device=DEV)
+    for t in range(steps):
+        B.eh_cascade(ctx, hid.h[:, t:t + 1], 1, ex[t:t + 1], tok[t:t + 1], Hout[t], nev)
+    torch.cuda.synchronize()
+    assert ((ex >= 0) & (ex < w.n_heads)).all() and ((tok >= 0) & (tok < w.V)).all()
+    assert int(nev.item()) == int((ex.long() + 1).sum().item())
+    sample = torch.arange(0, steps, steps // 48, device=DEV)[:48]
+    full = P.oracle_all_heads(heads, hid.h, True, rows=sample)
+    log = []
+    flips = P.compare_cascade("c1", ex[sample], tok[sample], Hout[sample].T.contiguous(), full[0],
+                              full[2], full[3], tau, log)
+    print(f"c1: mean evals/step {nev.item() / steps:.2f}; sample exits {ex[sample].tolist()}; "
+          f"flips {flips}; log {log}")
+    assert len(set(ex.tolist())) >= 8          # exits are spread over many depths
+    B.eh_destroy(ctx)
+
+
+# --------------------------------------------------------------- config 2
+def test_c2_batched_calibration(B):
+    """All 24 heads on all 512 tokens; the oracle checks every head on 64
+    sampled tokens and three heads on all 512."""
+    w = G.CONFIGS["c2_calib"]
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    R = w.rows
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    sample = torch.arange(0, R, 8, device=DEV)
+    log = []
+    for l in range(w.n_heads):
+        H, lse, am = _outs(R)
+        B.eh_eval(ctx, l, hid.h[l], R, H, lse, am)
+        torch.cuda.synchronize()
+        sel = slice(None) if l in (0, 11, 23) else sample
+        orc = P.oracle_head(hid.h[l][sel], heads.gamma[l], heads.beta[l], heads.W[l], True)
+        P.compare_head(f"c2/head{l}", H[sel], lse[sel], am[sel], orc, log)
+    print("c2 near-ties:", log)
+    B.eh_destroy(ctx)
+
+
+# --------------------------------------------------------------- configs 3, 4
+@pytest.fixture(scope="module")
+def big(B):
+    """The 32 Pythia-2.8B-shaped heads shared by configs 3 and 4, with the
+    oracle's statistics of every head on config 3's 64 rows and on the
+    16 x 8 drafting rows of config 4."""
+    w3 = G.CONFIGS["c3_dynexit"]
+    heads = G.make_heads(w3, DEV)
+    hid3 = G.make_hidden(w3, heads, DEV)
+    hid4 = G.make_hidden(w3, heads, DEV, rows=16 * 8, seed_offset=404)
+    outs3, outs4 = [], []
+    for l in range(w3.n_heads):
+        W64 = P.f64(heads.W[l])
+        both = torch.cat([hid3.h[l], hid4.h[l]])
+        o = P.oracle_head(both, heads.gamma[l], heads.beta[l], None, True, W64=W64)
+        outs3.append([x[:64] for x in o])
+        outs4.append([x[64:] for x in o])
+        del W64
+    st = lambda outs, i: np.stack([o[i] for o in outs])
+    full3 = tuple(st(outs3, i) for i in range(4))
+    full4 = tuple(st(outs4, i) for i in range(4))
+    return dict(w=w3, heads=heads, hid3=hid3, hid4=hid4, full3=full3, full4=full4)
+
+
+def test_c3_dynamic_exit_with_compaction(B, big):
+    w, heads, hid, full = big["w"], big["heads"], big["hid3"], big["full3"]
+    tau = G.tau_for_schedule(full[0], w.n_heads)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=w.rows)
+    R = w.rows
+    ex = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    tok = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    Hout = torch.zeros((w.n_heads, R), device=DEV)
+    nev = torch.zeros(1, dtype=torch.int64, device=DEV)
+    B.eh_cascade(ctx, hid.h, R, ex, tok, Hout, nev)
+    torch.cuda.synchronize()
+    log = []
+    P.compare_cascade("c3", ex, tok, Hout, full[0], full[2], full[3], tau, log)
+    exl = ex.cpu().numpy()
+    frac = [(exl < l).mean() for l in (8, 16, 24)]
+    print(f"c3 exited fraction by layers 8/16/24: {frac}; evals {nev.item()}; log {log}")
+    assert abs(frac[0] - 0.10) < 0.05 and abs(frac[1] - 0.40) < 0.05 and abs(frac[2] - 0.70) < 0.05
+    big["tau3"] = tau
+    B.eh_destroy(ctx)
+
+
+def test_c4_dssd_verify(B, big):
+    w, heads, full4 = big["w"], big["heads"], big["full4"]
+    Bsz, k = 16, 8
+    tau = big.get("tau3") or G.tau_for_schedule(big["full3"][0], w.n_heads)
+    # drafts = the oracle's argmax at each drafting row's dynamic exit layer
+    draft = np.empty(Bsz * k, dtype=np.int64)
+    for r in range(Bsz * k):
+        e = O.exit_rule(full4[0][:, r], tau)
+        draft[r] = full4[2][e, r]
+    draft_t = torch.from_numpy(draft.reshape(Bsz, k)).to(DEV)
+    case = G.make_verify_case(w, heads, draft_t, DEV)
+    fin = w.n_heads - 1
+    acc_o, nxt_o, tgt_o, gap_o = O.dssd_verify(
+        P.f64(case.f_final), draft.reshape(Bsz, k), P.f64(heads.gamma[fin]), P.f64(heads.beta[fin]),
+        P.f64(heads.W[fin]), None, 1e-5, True)
+    assert gap_o.min() > 1e-2, "verification inputs must decide clearly"
+    ctx = B.eh_create(heads.W[fin:], heads.gamma[fin:], heads.beta[fin:], [float("inf")], max_rows=Bsz * (k + 1))
+    acc = torch.full((Bsz,), -1, dtype=torch.int32, device=DEV)
+    nxt = torch.full((Bsz,), -1, dtype=torch.int32, device=DEV)
+    tgt = torch.full((Bsz, k + 1), -1, dtype=torch.int32, device=DEV)
+    d32 = draft_t.to(torch.int32).contiguous()
+    B.dssd_verify(ctx, case.f_final, d32, None, acc, nxt, tgt)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(tgt.cpu().numpy(), tgt_o)
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), nxt_o)
+    # truncated drafts
+    dl = torch.tensor([0, 1, 2, 3, 4, 5, 6, 7, 8, 8, 3, 0, 8, 2, 5, 1], dtype=torch.int32, device=DEV)
+    B.dssd_verify(ctx, case.f_final, d32, dl, acc, nxt, None)
+    torch.cuda.synchronize()
+    acc_t, nxt_t, _, _ = O.dssd_verify(
+        P.f64(case.f_final), draft.reshape(Bsz, k), P.f64(heads.gamma[fin]), P.f64(heads.beta[fin]),
+        P.f64(heads.W[fin]), dl.cpu().numpy(), 1e-5, True)
+    np.testing.assert_array_equal(acc.cpu().numpy(), acc_t)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), nxt_t)
+    print(f"c4: accepted {acc_o.tolist()} mean {acc_o.mean():.2f}; agreement {case.agree[:, :k].float().mean().item():.2f}")
+    B.eh_destroy(ctx)
