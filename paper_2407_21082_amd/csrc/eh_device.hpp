@@ -34,7 +34,7 @@ __device__ __forceinline__ frag_t mk_frag(uint32_t a, uint32_t b, uint32_t c, ui
 constexpr int kWave = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr double kLn2d = 0.69314718055994530942;
-constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no maximum yet" / masked rows
+constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no maximum yet" (keeps m - m' finite)
 
 struct DtBf16 {
   static constexpr int EPL = 8;   // elements per lane per fragment
@@ -99,19 +99,17 @@ __device__ __forceinline__ Stats stats_merge(const Stats& a, const Stats& b) {
 }
 
 // Push four logits of consecutive vocabulary rows row0..row0+3 (rows >= V are
-// padding and ignored).  Rows must arrive in increasing order within a lane so
+// padding and skipped).  Rows must arrive in increasing order within a lane so
 // that "strictly greater" keeps the lowest index.
 template <bool ARGMAX_ONLY>
 __device__ __forceinline__ void stats_push4(Stats& s, f32x4 z, int row0, int V) {
-  if (row0 + 3 >= V) {
-    if (row0 + 0 >= V) z[0] = kNegBig;
-    if (row0 + 1 >= V) z[1] = kNegBig;
-    if (row0 + 2 >= V) z[2] = kNegBig;
-    if (row0 + 3 >= V) z[3] = kNegBig;
-  }
-  const float zmax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+  const int nvalid = V - row0;  // >= 4 everywhere but in the last tile
+  float zc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) zc[i] = (i < nvalid) ? z[i] : -INFINITY;
+  const float zmax = fmaxf(fmaxf(zc[0], zc[1]), fmaxf(zc[2], zc[3]));
   if (zmax > s.zb) {
-    const int j = (z[0] == zmax) ? 0 : (z[1] == zmax) ? 1 : (z[2] == zmax) ? 2 : 3;
+    const int j = (zc[0] == zmax) ? 0 : (zc[1] == zmax) ? 1 : (zc[2] == zmax) ? 2 : 3;
     if (!ARGMAX_ONLY) {
       const float mn = zmax * kLog2e;
       const float dm = s.m - mn;
@@ -126,10 +124,12 @@ __device__ __forceinline__ void stats_push4(Stats& s, f32x4 z, int row0, int V) 
   if (!ARGMAX_ONLY) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float t = z[i] * kLog2e - s.m;   // <= 0 for finite logits
-      const float e = fast_exp2(t);
-      s.S += e;
-      s.U += t * e;
+      if (i < nvalid) {
+        const float t = z[i] * kLog2e - s.m;  // <= 0 up to rounding for finite logits
+        const float e = fast_exp2(t);
+        s.S += e;
+        s.U += t * e;
+      }
     }
   }
 }
