@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the early-exit head evaluation hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1_decode]
+
+Default workload (the one the headline metric is quoted on): batch-1 decode,
+Pythia-410M-shaped heads (d=1024, V=50304, 23 exit heads + final, bf16 weights,
+fp32 accumulation).  One "step" is one pass of the whole hot path over one
+batch of synthetic input: 2048 seeded decode steps, each a dynamic-exit cascade
+(LayerNorm -> projection -> streaming entropy/argmax -> threshold test) that
+stops at the first head with H < tau.  All inputs are resident in HBM before
+the timed region starts.
+
+Prints ONE JSON line:  value = (row, head) evaluations per second over the
+timed steps; "roofline" = algorithmic bytes of the dominant kernel per launch
+over its average launch duration (HIP events on the launch stream) against
+the 8 TB/s HBM peak; "cpu_baseline" = the fp64 CPU oracle timed on a bounded
+sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c1_decode",
+                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify"])
+    ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per bench step (c1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def event_ms(fn, torch):
+    """Run fn() between two HIP events on the current (launch) stream."""
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1)
+
+
+def oracle_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"]
+        return max(n) if n else 1
+    except Exception:
+        return os.cpu_count() or 1
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build is single-GPU by construction; --gpus {args.gpus} is not "
+              "supported (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2407_21082_amd import binding as B     # raises if libeh.so is missing
+    from workloads import generators as G
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = G.CONFIGS[args.workload]
+    t_setup = time.time()
+    heads = G.make_heads(w, dev)
+    esz = 2 if w.dtype == "bf16" else 4
+    out = {}
+
+    if args.workload == "c1_decode":
+        n_dec = args.decode_steps or w.steps
+        hid = G.make_hidden(w, heads, dev, rows=n_dec)           # [n_heads, n_dec, d]
+        tau = G.tau_linear(w)
+        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=16)
+        ex = torch.full((n_dec,), -1, dtype=torch.int32, device=dev)
+        tok = torch.full((n_dec,), -1, dtype=torch.int32, device=dev)
+        nev = torch.zeros(1, dtype=torch.int64, device=dev)
+        views = [hid.h[:, t:t + 1] for t in range(n_dec)]
+
+        def step():
+            for t in range(n_dec):
+                B.eh_cascade(ctx, views[t], 1, ex[t:t + 1], tok[t:t + 1], None, nev)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        nev.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        evals = int(nev.item())
+        evals_per_step = evals / args.steps
+        value = evals / dt
+
+        # dominant kernel: one head on one row = one launch streaming the head's weights once.
+        Hb = torch.zeros(16, device=dev)
+        Lb = torch.zeros(16, device=dev)
+        Ab = torch.zeros(16, dtype=torch.int32, device=dev)
+        reps = 20
+        def sweep():
+            for _ in range(reps):
+                for l in range(w.n_heads):
+                    B.eh_eval(ctx, l, hid.h[l, 0:1], 1, Hb, Lb, Ab)
+        sweep()
+        torch.cuda.synchronize()
+        ms = event_ms(sweep, torch)
+        launches = reps * w.n_heads
+        bytes_per_launch = w.d * w.V * esz + w.d * esz + 12
+        avg_s = ms * 1e-3 / launches
+        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "kernel": "eh_eval (1 row, 1 head)", "avg_launch_us": avg_s * 1e6,
+                "bytes_per_launch": bytes_per_launch}
+        cfg = {"workload": "c1_decode: d=1024 V=50304 24 heads batch-1 bf16, "
+                           f"{n_dec} decode steps per bench step, exit at first H<tau",
+               "decode_steps": n_dec, "mean_evals_per_decode_step": evals_per_step / n_dec,
+               "mean_exit_layer": float(ex.float().mean().item())}
+        out.update(ms_per_step=dt / args.steps * 1e3)
+
+        cpu = None
+        if not args.no_cpu_baseline:
+            from oracle import eh_oracle as O
+            f64 = G.to_f64_numpy
+            W64 = [f64(Wl) for Wl in heads.W]                      # input marshalling, not timed
+            g64 = [f64(g) for g in heads.gamma]
+            b64 = [f64(b) for b in heads.beta]
+            done_evals, done_steps = 0, 0
+            t0 = time.perf_counter()
+            for t in range(0, n_dec):
+                hl = [f64(hid.h[l, t:t + 1]) for l in range(w.n_heads)]
+                r = O.cascade(hl, g64, b64, W64, tau, w.ln_eps, True)
+                done_evals += int(r["exit_layer"][0]) + 1
+                done_steps += 1
+                if time.perf_counter() - t0 > args.cpu_seconds:
+                    break
+            cdt = time.perf_counter() - t0
+            cpu = {"value": done_evals / cdt, "unit": "evals/s", "cores": oracle_threads(),
+                   "kind": "oracle",
+                   "sample": f"first {done_steps} decode steps of the same workload "
+                             f"({done_evals} evaluations, {cdt:.1f} s; fp64 numpy, weights pre-widened)"}
+        B.eh_destroy(ctx)
+    else:
+        raise SystemExit("workload not wired into bench.py yet: " + args.workload)
+
+    line = {"metric": "exit_head_evals_per_sec", "value": value, "unit": "evals/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": out["ms_per_step"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+            "data": "synthetic", "config": cfg, "roofline": roof, "cpu_baseline": cpu,
+            "setup_s": round(time.time() - t_setup, 1)}
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
