@@ -163,6 +163,28 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft,
                       const int32_t* draft_len, int32_t B, int32_t k, int32_t* accepted,
                       int32_t* next_token, int32_t* target, void* stream);
 
+/*
+ * Waits for `stream` and reports failures that only the device can see: the
+ * persistent decode kernel (used for calls with at most 16 rows) waits for other
+ * workgroups with a bounded spin, and a timeout there sets a sticky flag in the
+ * context.  Returns EH_ERR_HIP if the flag is set (every later call on the
+ * context is then a no-op on the device) or if the synchronisation fails.
+ */
+eh_status eh_check(eh_ctx* ctx, void* stream);
+
+/*
+ * Diagnostics of the persistent decode kernel.  With enable != 0, later decode
+ * launches make workgroup 0 record 16 wall-clock stamps (100 MHz ticks) per
+ * head; host_out (host, nullable, n entries) first receives the stamps recorded
+ * so far (the call synchronises the device): 16 per head, followed by four per
+ * workgroup (streaming start/end, records sent, decision known) for the fourth
+ * head of the launch.  Stamp slots of the per-head part:
+ * 0/1 first streaming wave starts / finishes the head, 4..8 service wave: passes
+ * the previous barrier, partial+ticket(+decision) done, live-row mask known,
+ * LayerNorm of the next head done, passes this head's barrier.
+ */
+eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n);
+
 /* Message describing the last error on this context (or, with ctx == NULL, the
  * last eh_create failure of the calling thread).  Never NULL.  The string is
  * owned by the library and valid until the next call on the same context. */

@@ -24,7 +24,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
 
 # every symbol include/eh.h declares
 EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify",
-           "eh_last_error", "eh_version"]
+           "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
 
 
 class EhError(RuntimeError):
@@ -55,11 +55,14 @@ def _load() -> C.CDLL:
     lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, f32, vp]
     lib.eh_cascade.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.eh_check.argtypes = [vp, vp]
+    lib.eh_decode_trace.argtypes = [vp, i32, vp, i32]
+    lib.eh_decode_trace.restype = C.c_int
     lib.eh_last_error.argtypes = [vp]
     lib.eh_last_error.restype = C.c_char_p
     lib.eh_version.argtypes = []
     lib.eh_version.restype = C.c_char_p
-    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify"):
+    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "eh_check"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -164,6 +167,26 @@ def eh_cascade(ctx: EhContext, h_layers: torch.Tensor, n_rows: int, exit_layer: 
     _check(lib.eh_cascade(ctx.handle, _ptr(h_layers), h_layers.stride(0), h_layers.stride(1), n_rows,
                           _ptr(exit_layer), _ptr(token), _ptr(H_out), _ptr(n_evals_out),
                           _stream(stream)), ctx.handle)
+
+
+def eh_check(ctx: EhContext, stream=None) -> None:
+    """Synchronise the stream and raise if a kernel reported a device-side failure."""
+    _check(lib.eh_check(ctx.handle, _stream(stream)), ctx.handle)
+
+
+def eh_decode_trace(ctx: EhContext, enable: bool, read: bool = False, per_workgroup: bool = False):
+    """Switch the decode kernel's per-head time stamps on/off; optionally return
+    what was recorded so far as a list of [n_heads][16] tick counts (100 MHz)."""
+    n = ctx.n_heads * 16
+    extra = 4 * 256 if per_workgroup else 0
+    buf = (C.c_uint64 * (n + extra))() if read else None
+    _check(lib.eh_decode_trace(ctx.handle, 1 if enable else 0, buf, (n + extra) if read else 0), ctx.handle)
+    if not read:
+        return None
+    heads = [[buf[l * 16 + k] for k in range(16)] for l in range(ctx.n_heads)]
+    if not per_workgroup:
+        return heads
+    return heads, [[buf[n + g * 4 + k] for k in range(4)] for g in range(256)]
 
 
 def dssd_verify(ctx: EhContext, f_final: torch.Tensor, draft: torch.Tensor,

@@ -10,6 +10,7 @@
 #include <string>
 #include <vector>
 
+#include "eh_internal.hpp"
 #include "eh_kernels.hpp"
 
 using namespace eh;
@@ -35,24 +36,6 @@ struct DeviceGuard {
 };
 
 }  // namespace
-
-struct eh_ctx {
-  int d = 0, V = 0, n_heads = 0, max_rows = 0, dtype = 0, device = 0;
-  float eps = 1e-5f;
-  int KS = 0, VT = 0, R_pad_max = 0;
-  std::vector<frag_t*> Wf;        // per head, fragment-major weights
-  std::vector<float*> gamma, beta, bias;
-  std::vector<float> tau;
-  frag_t* yf = nullptr;           // [R_pad_max/16][KS][64] activations in fragment order
-  Stats* partials = nullptr;      // [kStreamGrid][R_pad_max]
-  float* ws_H = nullptr;          // [max_rows] internal outputs (cascade, verify)
-  float* ws_lse = nullptr;
-  int* ws_argmax = nullptr;
-  int* active[2] = {nullptr, nullptr};
-  int* n_active[2] = {nullptr, nullptr};
-  std::vector<void*> allocs;
-  std::string err = "";
-};
 
 namespace {
 
@@ -140,6 +123,20 @@ eh_status check_rows(eh_ctx* ctx, const void* h, int64_t row_stride, int n_rows)
   if (!aligned16(h) || (row_stride * esz) % 16 != 0)
     return fail(ctx, EH_ERR_SHAPE, "hidden rows must be 16-byte aligned");
   return EH_OK;
+}
+
+// Rows <= 16 go through the persistent decode kernel when the shape fits it.
+bool use_decode(const eh_ctx* c, int n_rows) { return c->decode_grid > 0 && n_rows <= 16; }
+
+DecodeParams decode_base(eh_ctx* c) {
+  DecodeParams p{};
+  p.Wf = c->d_Wf; p.gamma = c->d_gamma; p.beta = c->d_beta; p.bias = c->d_bias; p.tau = c->d_tau;
+  p.n_heads = c->n_heads; p.V = c->V; p.d = c->d; p.KS = c->KS; p.VT = c->VT; p.eps = c->eps;
+  p.records = c->dec_records; p.n_heads_alloc = c->n_heads;
+  if (++c->dec_epoch == 0u) ++c->dec_epoch;  // never 0
+  p.epoch = c->dec_epoch; p.status = c->dec_status;
+  p.trace = c->dec_trace_on ? c->dec_trace : nullptr;
+  return p;
 }
 
 }  // namespace
@@ -235,6 +232,32 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
     if ((e = dev_alloc(c, &c->active[i], (size_t)c->max_rows)) != hipSuccess) return bail(e, "hipMalloc(ws)");
     if ((e = dev_alloc(c, &c->n_active[i], (size_t)4)) != hipSuccess) return bail(e, "hipMalloc(ws)");
   }
+  {
+    // device-side tables for the persistent decode kernel
+    const size_t np = (size_t)c->n_heads;
+    if ((e = dev_alloc(c, &c->d_Wf, np)) != hipSuccess) return bail(e, "hipMalloc(tables)");
+    if ((e = dev_alloc(c, &c->d_gamma, np)) != hipSuccess) return bail(e, "hipMalloc(tables)");
+    if ((e = dev_alloc(c, &c->d_beta, np)) != hipSuccess) return bail(e, "hipMalloc(tables)");
+    if ((e = dev_alloc(c, &c->d_tau, np)) != hipSuccess) return bail(e, "hipMalloc(tables)");
+    if ((e = hipMemcpy(c->d_Wf, c->Wf.data(), np * sizeof(void*), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "copy tables");
+    if ((e = hipMemcpy(c->d_gamma, c->gamma.data(), np * sizeof(void*), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "copy tables");
+    if ((e = hipMemcpy(c->d_beta, c->beta.data(), np * sizeof(void*), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "copy tables");
+    if ((e = hipMemcpy(c->d_tau, c->tau.data(), np * sizeof(float), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "copy tables");
+    if (cfg->bias) {
+      if ((e = dev_alloc(c, &c->d_bias, np)) != hipSuccess) return bail(e, "hipMalloc(tables)");
+      if ((e = hipMemcpy(c->d_bias, c->bias.data(), np * sizeof(void*), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "copy tables");
+    }
+    if ((e = decode_prepare(c)) != hipSuccess) return bail(e, "decode_prepare");
+    if (c->decode_grid > 0) {
+      const size_t nrec = 2 * np * c->decode_grid * 16 * 5;
+      if ((e = dev_alloc(c, &c->dec_records, nrec)) != hipSuccess) return bail(e, "hipMalloc(decode)");
+      if ((e = dev_alloc(c, &c->dec_status, (size_t)4)) != hipSuccess) return bail(e, "hipMalloc(decode)");
+      if ((e = hipMemset(c->dec_records, 0, nrec * sizeof(unsigned long long))) != hipSuccess) return bail(e, "memset");
+      if ((e = hipMemset(c->dec_status, 0, 16)) != hipSuccess) return bail(e, "memset");
+      if ((e = dev_alloc(c, &c->dec_trace, np * 16 + 4 * (size_t)c->decode_grid)) != hipSuccess) return bail(e, "hipMalloc(decode)");
+      if ((e = hipMemset(c->dec_trace, 0, (np * 16 + 4 * (size_t)c->decode_grid) * sizeof(unsigned long long))) != hipSuccess) return bail(e, "memset");
+    }
+  }
   if ((e = hipDeviceSynchronize()) != hipSuccess) return bail(e, "eh_create sync");
   *out = c;
   return EH_OK;
@@ -259,6 +282,17 @@ eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride
   eh_status st = check_rows(ctx, h, h_row_stride, n_rows);
   if (st != EH_OK) return st;
   DeviceGuard guard(ctx->device);
+  if (use_decode(ctx, n_rows)) {
+    DecodeParams p = decode_base(ctx);
+    p.h = h; p.layer_stride = 0; p.row_stride = h_row_stride; p.row_idx = row_idx;
+    p.n_rows_dev = n_rows_dev; p.n_rows = n_rows; p.l0 = 0; p.l1 = 1; p.decide = 0;
+    // evaluation mode addresses one head: shift the tables instead of the layer stride
+    p.Wf += head; p.gamma += head; p.beta += head; if (p.bias) p.bias += head;
+    p.records += (size_t)head * ctx->decode_grid * 16 * 5;
+    p.H = H; p.lse = lse; p.argmax = argmax;
+    EH_HIP(ctx, decode_launch(ctx, p, (hipStream_t)stream));
+    return EH_OK;
+  }
   return run_head<false>(ctx, head, h, h_row_stride, row_idx, n_rows_dev, n_rows, H, lse, argmax,
                          (hipStream_t)stream);
 }
@@ -295,6 +329,15 @@ eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride, in
     return fail(ctx, EH_ERR_SHAPE, "layer stride must keep rows 16-byte aligned");
   DeviceGuard guard(ctx->device);
   hipStream_t s = (hipStream_t)stream;
+  if (use_decode(ctx, n_rows)) {
+    DecodeParams p = decode_base(ctx);
+    p.h = h_layers; p.layer_stride = layer_stride; p.row_stride = row_stride;
+    p.n_rows = n_rows; p.l0 = 0; p.l1 = ctx->n_heads; p.decide = 1;
+    p.exit_layer = exit_layer; p.token = token; p.H_out = H_out;
+    p.n_evals = (unsigned long long*)n_evals_out;
+    EH_HIP(ctx, decode_launch(ctx, p, s));
+    return EH_OK;
+  }
   if (H_out) {
     const int64_t n = (int64_t)ctx->n_heads * n_rows;
     hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, H_out, n, NAN);
@@ -336,6 +379,33 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, co
   hipLaunchKernelGGL(verify_compare_kernel, dim3((B + 63) / 64), dim3(64), 0, s, draft, draft_len, tgt, B,
                      k, accepted, next_token);
   EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
+}
+
+eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n) {
+  if (!ctx) return EH_ERR_NULL;
+  if (!ctx->dec_trace) return fail(ctx, EH_ERR_RANGE, "this context has no decode kernel");
+  DeviceGuard guard(ctx->device);
+  if (host_out) {
+    if (n < 0 || n > ctx->n_heads * 16 + 4 * ctx->decode_grid)
+      return fail(ctx, EH_ERR_RANGE, "n outside [0, 16 * n_heads + 4 * workgroups]");
+    EH_HIP(ctx, hipDeviceSynchronize());
+    EH_HIP(ctx, hipMemcpy(host_out, ctx->dec_trace, sizeof(uint64_t) * n, hipMemcpyDeviceToHost));
+  }
+  ctx->dec_trace_on = enable ? 1 : 0;
+  return EH_OK;
+}
+
+eh_status eh_check(eh_ctx* ctx, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  EH_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));
+  if (ctx->dec_status) {
+    int flag = 0;
+    EH_HIP(ctx, hipMemcpy(&flag, ctx->dec_status, sizeof(int), hipMemcpyDeviceToHost));
+    if (flag != 0)
+      return fail(ctx, EH_ERR_HIP, "decode kernel gave up waiting for another workgroup (context disabled)");
+  }
   return EH_OK;
 }
 

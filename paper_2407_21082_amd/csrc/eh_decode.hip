@@ -1,0 +1,711 @@
+// Persistent decode kernel: up to 16 rows through heads l0 .. l1-1 in ONE launch
+// (arXiv 2407.21082, Section 3.4.2 exit rule in the entropy form of Section
+// 4.3.1; per head the LayerNorm -> projection -> entropy/argmax of Sections 3.2
+// and 3.4.1).
+//
+// Batch-1 decode is a pure weight stream (1 flop per byte), so the design goal
+// is to keep HBM reads back to back from the first head to the exit head:
+//
+//  * one workgroup per CU, each owning a contiguous, tile-aligned slice of the
+//    vocabulary of every head; inside it, 4 "streamer" waves split the slice's
+//    fragments evenly and each reads its own contiguous span through a
+//    register ring of P loads that runs on across head boundaries;
+//  * the matrix cores do the k-reduction (one 16x16 tile of logits per 1 KiB
+//    fragment pair); the streamers fold finished tiles into running softmax
+//    statistics, tiles split between two waves are summed by the service wave;
+//  * two more waves do everything that needs global round trips so that the
+//    streamers never drain their rings: a LayerNorm wave prepares the next
+//    head's rows in LDS (double buffered), and an exchange wave all-gathers
+//    the workgroups' partial statistics through tagged records, merges them
+//    and applies the threshold test (every workgroup reaches the same
+//    decision from the same records; workgroup 0 writes the outputs);
+//  * heads are speculated one ahead: streamers start head l+1 while the
+//    decision for head l is still being formed and drop it if every row has
+//    exited.  Nothing of a dropped head is ever published.
+//
+// Every wait on another workgroup is bounded (kSpinLimit); a timeout sets the
+// context's sticky status word and makes every wave leave.
+#include "eh_internal.hpp"
+#include "eh_kernels.hpp"
+
+namespace eh {
+
+namespace {
+
+constexpr int kStreamers = 4;
+constexpr int kThreads = (kStreamers + 2) * kWave;  // streamers + exchange wave + LayerNorm wave
+constexpr int kRing = 8;              // fragments per ring buffer (two buffers per streamer wave)
+constexpr int kSpinLimit = 1 << 22;   // polls of a global flag before giving up
+constexpr int kMaxChunksPerLane = 4;  // LayerNorm keeps a row in registers: d <= 4*64*EPL
+
+// LDS-only barrier: waits for this wave's LDS traffic, not for the global loads
+// still in flight in the ring.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+#define EH_LDS __attribute__((address_space(3)))
+#define EH_GLOBAL __attribute__((address_space(1)))
+// Pointers read out of the per-head tables are generic to the compiler; casting
+// them to the global address space keeps the weight stream on global_load (one
+// counter, exact in-order waits) instead of flat_load.
+typedef EH_GLOBAL const frag_t gfrag_t;
+typedef EH_GLOBAL const f32x4 gf32x4_t;
+typedef EH_GLOBAL const float gfloat_t;
+// The per-head pointer tables are written once at context creation; reading them
+// through the constant address space lets the streamers fetch a head's base with
+// a scalar load instead of a vector load whose wait would drain the ring.
+__device__ __forceinline__ gfrag_t* head_weights(const frag_t* const* table, int l) {
+  typedef const frag_t* entry_t;
+  typedef __attribute__((address_space(4))) const entry_t centry_t;
+  return (gfrag_t*)((centry_t*)table)[l];
+}
+typedef EH_LDS frag_t lds_frag_t;
+typedef EH_LDS f32x4 lds_f32x4_t;
+typedef EH_LDS float lds_float_t;
+typedef EH_LDS int lds_int_t;
+typedef EH_LDS volatile int lds_vint_t;
+
+// LDS layout (byte offsets from the dynamic LDS base); "par" is the head parity.
+struct Smem {
+  EH_LDS char* base;
+  unsigned y_bytes;  // KS * 1 KiB
+  __device__ __forceinline__ lds_frag_t* ybuf(int par) const { return (lds_frag_t*)(base + par * y_bytes); }
+  __device__ __forceinline__ unsigned o1() const { return 2 * y_bytes; }
+  // tile pieces that start at k > 0: [par][4][64] f32x4
+  __device__ __forceinline__ lds_f32x4_t* part(int par) const {
+    return (lds_f32x4_t*)(base + o1() + par * (kStreamers * kWave * 16));
+  }
+  // tile pieces that start at k = 0 but end early: [par][4][64] f32x4
+  __device__ __forceinline__ lds_f32x4_t* pend(int par) const {
+    return (lds_f32x4_t*)(base + o1() + (2 + par) * (kStreamers * kWave * 16));
+  }
+  // per-lane statistics of the streamers: [par][5][4][64] float (ib stored as bits)
+  __device__ __forceinline__ lds_float_t* wst(int par) const {
+    return (lds_float_t*)(base + o1() + 4 * (kStreamers * kWave * 16) + par * (5 * kStreamers * kWave * 4));
+  }
+  __device__ __forceinline__ unsigned o2() const {
+    return o1() + 4 * (kStreamers * kWave * 16) + 2 * (5 * kStreamers * kWave * 4);
+  }
+  __device__ __forceinline__ lds_int_t* part_tile(int par) const { return (lds_int_t*)(base + o2() + par * 16); }
+  __device__ __forceinline__ lds_int_t* pend_tile(int par) const { return (lds_int_t*)(base + o2() + 32 + par * 16); }
+  __device__ __forceinline__ lds_vint_t* abort_flag(int par) const { return (lds_vint_t*)(base + o2() + 64 + par * 4); }
+  // rows entering head l, left by the exchange wave for the LayerNorm wave (by parity of l)
+  __device__ __forceinline__ lds_vint_t* live_word(int par) const { return (lds_vint_t*)(base + o2() + 72 + par * 4); }
+  // number of streamer waves that have finished the head of this parity
+  __device__ __forceinline__ lds_vint_t* arrived(int par) const { return (lds_vint_t*)(base + o2() + 80 + par * 4); }
+};
+
+inline size_t smem_bytes(int KS) {
+  return 2 * (size_t)KS * kWave * 16 + 4 * kStreamers * kWave * 16 + 2 * 5 * kStreamers * kWave * 4 + 64 + 32;
+}
+
+// Push with an explicit index tie-break (rows may arrive in any order).
+__device__ __forceinline__ void stats_push4_any(Stats& s, f32x4 z, int row0, int V) {
+  const int nvalid = V - row0;
+  float zc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) zc[i] = (i < nvalid) ? z[i] : -INFINITY;
+  const float zmax = fmaxf(fmaxf(zc[0], zc[1]), fmaxf(zc[2], zc[3]));
+  const int j = (zc[0] == zmax) ? 0 : (zc[1] == zmax) ? 1 : (zc[2] == zmax) ? 2 : 3;
+  if (zmax > s.zb || (zmax == s.zb && row0 + j < s.ib && nvalid > 0)) {
+    if (zmax > s.zb) {
+      const float mn = zmax * kLog2e;
+      const float dm = s.m - mn;
+      const float sc = fast_exp2(dm);
+      s.U = sc * (s.U + dm * s.S);
+      s.S = sc * s.S;
+      s.m = mn;
+    }
+    s.zb = zmax;
+    s.ib = row0 + j;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (i < nvalid) {
+      const float t = z[i] * kLog2e - s.m;
+      const float e = fast_exp2(t);
+      s.S += e;
+      s.U += t * e;
+    }
+  }
+}
+
+// LayerNorm of one row held in registers (one global pass), fp64 arithmetic,
+// written to LDS in fragment order as token column n.
+template <typename DT>
+__device__ __forceinline__ void ln_row_to_lds(const void* row, int d, int KS,
+                                              const float* __restrict__ gamma,
+                                              const float* __restrict__ beta, float eps, int lane, int n,
+                                              lds_frag_t* ybuf) {
+  const int live_chunks = d / DT::EPL;
+  float x[kMaxChunksPerLane][DT::EPL];
+#pragma unroll
+  for (int i = 0; i < kMaxChunksPerLane; ++i) {
+    const int c = lane + i * kWave;
+    if (c < live_chunks) load_elems<DT>(row, c * DT::EPL, x[i]);
+  }
+  double s = 0.0;
+#pragma unroll
+  for (int i = 0; i < kMaxChunksPerLane; ++i) {
+    if (lane + i * kWave < live_chunks) {
+#pragma unroll
+      for (int e = 0; e < DT::EPL; ++e) s += (double)x[i][e];
+    }
+  }
+  const double mu = wave_sum(s) / (double)d;
+  double v = 0.0;
+#pragma unroll
+  for (int i = 0; i < kMaxChunksPerLane; ++i) {
+    if (lane + i * kWave < live_chunks) {
+#pragma unroll
+      for (int e = 0; e < DT::EPL; ++e) {
+        const double c = (double)x[i][e] - mu;
+        v += c * c;
+      }
+    }
+  }
+  const double rstd = 1.0 / sqrt(wave_sum(v) / (double)d + (double)eps);
+#pragma unroll
+  for (int i = 0; i < kMaxChunksPerLane; ++i) {
+    const int c = lane + i * kWave;
+    if (c < KS * 4) {
+      frag_t o = mk_frag(0, 0, 0, 0);
+      if (c < live_chunks) {
+        double y[DT::EPL];
+#pragma unroll
+        for (int e = 0; e < DT::EPL; ++e) {
+          const int k = c * DT::EPL + e;
+          y[e] = (double)gamma[k] * (((double)x[i][e] - mu) * rstd) + (double)beta[k];
+        }
+        o = pack_elems<DT>(y);
+      }
+      ybuf[(c >> 2) * kWave + (c & 3) * 16 + n] = o;
+    }
+  }
+}
+
+// Diagnostics: workgroup 0 stamps the 100 MHz wall clock at the phases of head l.
+// slots: 0 streamer0 starts head, 1 streamer0 reaches the head's barrier,
+// 4 exchange wave passes the previous barrier, 5 records of head l-1 sent,
+// 6 exchange and decision for head l-1 done, 7 LayerNorm(l+1) done (LayerNorm
+// wave), 8 exchange wave passes barrier l.
+__device__ __forceinline__ void stamp(const DecodeParams& p, int l, int slot, int lane) {
+  if (p.trace && lane == 0) {
+    if (blockIdx.x == 0) p.trace[l * 16 + slot] = wall_clock64();
+    // every workgroup's view of one head (the fourth of the launch): slots 0, 1, 5, 6
+    if (l == p.l0 + 3 && (slot < 2 || slot == 5 || slot == 6))
+      p.trace[p.n_heads_alloc * 16 + blockIdx.x * 4 + (slot < 2 ? slot : slot - 3)] = wall_clock64();
+  }
+}
+
+__device__ __forceinline__ unsigned long long poll_mask(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The vocabulary slice of a workgroup.  Slices are cut at multiples of four rows
+// (the rows one lane's accumulator registers hold), not at tile boundaries, so
+// that every workgroup streams the same number of bytes to within 2 %: with
+// whole tiles, 3144 tiles over 256 workgroups leave some with 13 tiles and some
+// with 12, and everybody waits for the 13s.  A tile cut by a slice boundary is
+// visited by both neighbours; each fetches only its own rows (the other lanes
+// are pointed at one shared dummy address) and counts only its own rows.
+struct Slice {
+  int row_lo, row_hi;  // rows [row_lo, row_hi) are mine
+  int T0, T1;          // tiles [T0, T1) contain them
+};
+__device__ __forceinline__ Slice my_slice(int V) {
+  const int grid = gridDim.x, bid = blockIdx.x;
+  const int U = (V + 3) >> 2;
+  Slice s;
+  s.row_lo = (int)((long long)U * bid / grid) * 4;
+  s.row_hi = min((int)((long long)U * (bid + 1) / grid) * 4, V);
+  s.T0 = s.row_lo >> 4;
+  s.T1 = s.row_hi > s.row_lo ? (s.row_hi + 15) >> 4 : s.T0;
+  return s;
+}
+
+// ------------------------------------------------------------------ streamers
+// The weight stream of one wave is cut into groups of kRing fragments.  Two
+// register buffers of one group each alternate: while one is consumed the other
+// (and the rest of this one) is in flight, so 8..15 KiB per wave are always on
+// their way, across head boundaries too.  Per head the number of groups is
+// rounded up to an even count so that the buffers keep their roles; a padding
+// group consumes nothing and re-reads the span's last fragment (a cache hit).
+template <typename DT>
+__device__ __forceinline__ void streamer(const DecodeParams& p, const Smem& sm, int wave, int lane) {
+  constexpr int P = kRing;
+  const int KS = p.KS;
+  const Slice sl = my_slice(p.V);
+  const int T0 = sl.T0, T1 = sl.T1;
+  const int nF = (T1 - T0) * KS;
+  const int F0 = (int)((long long)nF * wave / kStreamers), F1 = (int)((long long)nF * (wave + 1) / kStreamers);
+  const int n_w = F1 - F0;
+  const int G = (n_w + P - 1) / P;
+  const int G2 = (G + 1) & ~1;
+  const long long fb = (long long)T0 * KS + F0;
+  const int q = lane >> 4;
+  const int last = n_w > 0 ? n_w - 1 : 0;
+  // lanes whose row of the slice's first / last tile belongs to a neighbour
+  const bool lo_foreign = (T0 * 16 + (lane & 15)) < sl.row_lo;
+  const bool hi_foreign = ((T1 - 1) * 16 + (lane & 15)) >= sl.row_hi;
+
+  // fragment idx of my span in the head whose weights start at `head`; foreign
+  // rows are not fetched: their lanes all read the head's first 16 bytes instead
+  auto load_slot = [&](gfrag_t* head, int idx) {
+    const int f = F0 + idx;
+    const bool foreign = (f < KS && lo_foreign) || (f >= nF - KS && hi_foreign);
+    gfrag_t* a = foreign ? head : head + (fb + idx) * kWave + lane;
+    return __builtin_nontemporal_load(a);
+  };
+
+  frag_t bufA[P], bufB[P];
+  {
+    gfrag_t* h0 = head_weights(p.Wf, p.l0);
+#pragma unroll
+    for (int j = 0; j < P; ++j) bufA[j] = load_slot(h0, min(j, last));
+#pragma unroll
+    for (int j = 0; j < P; ++j) bufB[j] = load_slot(h0, min(P + j, last));
+  }
+  lds_barrier();  // y of head l0 is in LDS
+
+  for (int l = p.l0; l < p.l1; ++l) {
+    const int par = l & 1;
+    gfrag_t* wcur = head_weights(p.Wf, l);
+    const bool has_next = l + 1 < p.l1;
+    gfrag_t* wnxt = has_next ? head_weights(p.Wf, l + 1) : wcur;
+    const lds_frag_t* yb = sm.ybuf(par) + lane;
+    Stats st;
+    stats_init(st);
+    int t = T0 + F0 / KS, ks = F0 % KS;
+    int piece_k0 = ks;
+    bool have_part = false, have_pend = false;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (wave == 0) stamp(p, l, 0, lane);
+
+    // A piece (a run of k-steps of one tile) is complete: fold it into the running
+    // statistics if it is the whole tile, otherwise park it in LDS for the service wave.
+    auto flush = [&](bool tile_end) {
+      const int row0 = t * 16 + q * 4;
+      if (piece_k0 == 0 && tile_end) {
+        if (row0 >= sl.row_lo) stats_push4<false>(st, acc, row0, sl.row_hi);
+      } else if (piece_k0 > 0) {
+        sm.part(par)[wave * kWave + lane] = acc;
+        if (lane == 0) sm.part_tile(par)[wave] = t;
+        have_part = true;
+      } else {
+        sm.pend(par)[wave * kWave + lane] = acc;
+        if (lane == 0) sm.pend_tile(par)[wave] = t;
+        have_pend = true;
+      }
+      acc = f32x4{0.f, 0.f, 0.f, 0.f};
+      piece_k0 = 0;
+    };
+
+    // consume group g held in buf
+    auto consume = [&](const frag_t (&buf)[P], int g) {
+      const int i0 = g * P;
+      if (i0 + P <= n_w && ks + P <= KS) {
+        // fast path: the whole group lies inside one tile
+        frag_t y[P];
+#pragma unroll
+        for (int j = 0; j < P; ++j) y[j] = yb[(ks + j) * kWave];
+#pragma unroll
+        for (int j = 0; j < P; ++j) acc = DT::mma(buf[j], y[j], acc);
+        ks += P;
+        const bool tile_end = (ks == KS);
+        if (tile_end || i0 + P == n_w) flush(tile_end);
+        if (tile_end) { ks = 0; ++t; }
+      } else {
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+          if (i0 + j < n_w) {
+            const frag_t y = yb[ks * kWave];
+            acc = DT::mma(buf[j], y, acc);
+            const bool tile_end = (ks == KS - 1);
+            if (tile_end || i0 + j == n_w - 1) flush(tile_end);
+            if (++ks == KS) { ks = 0; ++t; }
+          }
+        }
+      }
+    };
+
+    // refill buf with group gg of this head, or of the next head once gg >= G2.
+    // Unconditional on purpose: a load under a branch makes the compiler drain
+    // the ring before every use.  With nothing left to fetch the slots re-read
+    // this wave's last fragment.
+    auto refill = [&](frag_t (&buf)[P], int gg) {
+      const bool same = gg < G2;
+      gfrag_t* src = same ? wcur : wnxt;
+      const int base = (same ? gg : gg - G2) * P;
+      const bool real = same || has_next;
+#pragma unroll
+      for (int j = 0; j < P; ++j) buf[j] = load_slot(src, real ? min(base + j, last) : last);
+    };
+
+    for (int g = 0; g < G2; g += 2) {
+      if (*sm.abort_flag(par)) break;  // every row has exited: drop this (speculative) head
+      consume(bufA, g);
+      refill(bufA, g + 2);
+      consume(bufB, g + 1);
+      refill(bufB, g + 3);
+    }
+    if (lane == 0) {
+      if (!have_part) sm.part_tile(par)[wave] = -1;
+      if (!have_pend) sm.pend_tile(par)[wave] = -1;
+    }
+    lds_float_t* ws = sm.wst(par) + wave * kWave + lane;
+    ws[0 * kStreamers * kWave] = st.m;
+    ws[1 * kStreamers * kWave] = st.S;
+    ws[2 * kStreamers * kWave] = st.U;
+    ws[3 * kStreamers * kWave] = st.zb;
+    ws[4 * kStreamers * kWave] = __int_as_float(st.ib);
+    if (wave == 0) stamp(p, l, 1, lane);
+    if (lane == 0) __hip_atomic_fetch_add((EH_LDS int*)sm.arrived(par), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    lds_barrier();  // B_l
+    if (*sm.abort_flag(par)) return;
+  }
+}
+
+// ------------------------------------------------------------------ service wave
+// Cross-workgroup exchange.  Statistics travel in records of five 64-bit words
+// {tag, payload}, written with device-scope stores and read with device-scope
+// loads until every word carries this launch's tag.  The all-gather runs in two
+// rounds of radix 16 (workgroups of my group, then one member of every group):
+// two memory hops, no tickets, no counters and no word that more than 16
+// workgroups poll (a single hot word polled by all 256 slowed the whole weight
+// stream down when it was tried).  All workgroups merge the same records in the
+// same order, so they all reach the same (bitwise identical) statistics and the
+// same exit decision on their own.  Records of a speculated head that is dropped
+// are never written; a tag from an older launch never matches, so nothing has to
+// be reset between launches.
+struct Service {
+  const DecodeParams& p;
+  const Smem sm;
+  int lane;
+  unsigned live;  // rows that enter the oldest head not yet decided
+
+  __device__ __forceinline__ void fail_all(int par) {
+    if (lane == 0) {
+      atomicExch(p.status, 1);
+      *sm.abort_flag(par) = 1;
+    }
+  }
+
+  // Statistics of this workgroup for head l (parity par), one record per token in lanes 0..15.
+  __device__ __forceinline__ Stats gather_wg(int par) {
+    const Slice sl = my_slice(p.V);
+    Stats s;
+    stats_init(s);
+    const lds_float_t* ws = sm.wst(par) + lane;
+#pragma unroll
+    for (int w = 0; w < kStreamers; ++w) {
+      Stats o;
+      o.m = ws[(0 * kStreamers + w) * kWave];
+      o.S = ws[(1 * kStreamers + w) * kWave];
+      o.U = ws[(2 * kStreamers + w) * kWave];
+      o.zb = ws[(3 * kStreamers + w) * kWave];
+      o.ib = __float_as_int(ws[(4 * kStreamers + w) * kWave]);
+      s = stats_merge(s, o);
+    }
+    const int q = lane >> 4;
+    for (int w = 0; w < kStreamers; ++w) {
+      const int t = sm.pend_tile(par)[w];
+      if (t < 0) continue;
+      f32x4 z = sm.pend(par)[w * kWave + lane];
+      for (int w2 = w + 1; w2 < kStreamers; ++w2)  // later pieces of the same tile, in wave order
+        if (sm.part_tile(par)[w2] == t) z += sm.part(par)[w2 * kWave + lane];
+      const int row0 = t * 16 + q * 4;
+      if (row0 >= sl.row_lo) stats_push4_any(s, z, row0, sl.row_hi);
+    }
+    s = stats_merge(s, stats_shfl_xor(s, 16));
+    s = stats_merge(s, stats_shfl_xor(s, 32));
+    return s;
+  }
+
+  // record of workgroup g, row n, head l in exchange round `round` (0 or 1)
+  __device__ __forceinline__ unsigned long long* record(int round, int l, int g, int n) const {
+    return p.records + ((((long long)round * p.n_heads_alloc + l) * gridDim.x + g) * 16 + n) * 5;
+  }
+
+  __device__ __forceinline__ void write_record(unsigned long long* r, const Stats& s) const {
+    const unsigned long long tag = (unsigned long long)p.epoch << 32;
+    const unsigned w[5] = {__float_as_uint(s.m), __float_as_uint(s.S), __float_as_uint(s.U),
+                           __float_as_uint(s.zb), (unsigned)s.ib};
+#pragma unroll
+    for (int i = 0; i < 5; ++i)
+      __hip_atomic_store(r + i, tag | w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // Reads a record; false while it does not carry this launch's tag in every word.
+  __device__ __forceinline__ bool read_record(const unsigned long long* r, Stats& o) const {
+    unsigned long long w[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) w[i] = __hip_atomic_load(r + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i < 5; ++i) ok = ok && ((unsigned)(w[i] >> 32) == p.epoch);
+    o.m = __uint_as_float((unsigned)w[0]);
+    o.S = __uint_as_float((unsigned)w[1]);
+    o.U = __uint_as_float((unsigned)w[2]);
+    o.zb = __uint_as_float((unsigned)w[3]);
+    o.ib = (int)(unsigned)w[4];
+    return ok;
+  }
+
+  // One attempt at one round of the exchange for row n: lane i < count reads the
+  // record of workgroup src(i).  If every record is there they are merged in lane
+  // order (fixed tree), so every reader of the same records gets bitwise the same
+  // result, and true is returned; otherwise false (nothing is kept: the caller
+  // tries again later).
+  template <typename SrcFn>
+  __device__ __forceinline__ bool try_round(int round, int l, int n, int count, SrcFn src, Stats& out) {
+    Stats s;
+    stats_init(s);
+    bool have = true;
+    if (lane < count) have = read_record(record(round, l, src(lane), n), s);
+    if (!__all(have)) return false;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) s = stats_merge(s, stats_shfl_xor(s, o));
+    // the merge is not bitwise symmetric in its operands (fused multiply-adds), so
+    // lanes may differ in the last bit: everybody takes lane 0's result, which is
+    // computed from the same operands in the same order in every workgroup
+    out.m = __shfl(s.m, 0); out.S = __shfl(s.S, 0); out.U = __shfl(s.U, 0);
+    out.zb = __shfl(s.zb, 0); out.ib = __shfl(s.ib, 0);
+    return true;
+  }
+
+  // First half of what follows the streamers' work on head l: this workgroup's
+  // round-0 records go out.
+  __device__ __forceinline__ void announce(int l) {
+    const Stats mine = gather_wg(l & 1);
+    if (lane < 16 && ((live >> lane) & 1u)) write_record(record(0, l, blockIdx.x, lane), mine);
+  }
+
+  // Second half: a two-round all-gather with radix kRadix, then finalise and
+  // decide.  Round 0: the statistics of the workgroups of my group -> my round-1
+  // record (identical for all members of a group).  Round 1: one member of every
+  // group -> the statistics of the whole vocabulary.  A record is polled by at
+  // most kRadix workgroups, and a workgroup polls at most 2*kRadix records per
+  // row, so the waiting costs little bandwidth and has no hot spot.
+  //
+  // The exchange of head c advances row by row as records come in (done0: rows
+  // whose round-1 record this workgroup has written; done1: rows decided), so it
+  // can be resumed: attempt() makes one pass and returns true once head c is
+  // decided, with `live` then holding the rows that go on to head c+1.
+  static constexpr int kRadix = 16;
+  unsigned done0 = 0, done1 = 0, stay = 0;
+
+  __device__ __forceinline__ bool attempt(int c) {
+    const int grid = gridDim.x, me = blockIdx.x;
+    const int member = me % kRadix;
+    const int g0 = (me / kRadix) * kRadix;
+    const int gsize = min(kRadix, grid - g0);
+    const int ngroups = (grid + kRadix - 1) / kRadix;
+    const bool writer = me == 0 && lane == 0;
+    for (int n = 0; n < 16; ++n) {
+      if (!(((live & ~done0) >> n) & 1u)) continue;
+      Stats s;
+      if (try_round(0, c, n, gsize, [&](int i) { return g0 + i; }, s)) {
+        if (lane == 0) write_record(record(1, c, me, n), s);
+        done0 |= 1u << n;
+      }
+    }
+    for (int n = 0; n < 16; ++n) {
+      if (!(((done0 & ~done1) >> n) & 1u)) continue;
+      Stats s;
+      auto src = [&](int j) { return j * kRadix + min(member, min(kRadix, grid - j * kRadix) - 1); };
+      if (!try_round(1, c, n, ngroups, src, s)) continue;
+      done1 |= 1u << n;
+      float H, lse;
+      stats_finalize(s, H, lse);
+      if (p.decide) {
+        const bool leaves = (c == p.n_heads - 1) || (H < p.tau[c]);
+        if (!leaves) stay |= 1u << n;
+        if (writer) {
+          if (leaves) {
+            p.exit_layer[n] = c;
+            p.token[n] = s.ib;
+          }
+          if (p.H_out) p.H_out[(long long)c * p.n_rows + n] = H;
+        }
+      } else if (writer) {
+        if (p.H) p.H[n] = H;
+        if (p.lse) p.lse[n] = lse;
+        if (p.argmax) p.argmax[n] = s.ib;
+      }
+    }
+    if (done1 != live) return false;
+    if (writer && p.decide) {
+      if (p.n_evals) atomicAdd(p.n_evals, (unsigned long long)__popc(live));
+      if (p.H_out) {
+        for (int n = 0; n < p.n_rows; ++n)
+          if (!((live >> n) & 1u)) p.H_out[(long long)c * p.n_rows + n] = NAN;
+        if (stay == 0u || c == p.l1 - 1) {
+          const int total = (p.n_heads - (c + 1)) * p.n_rows;
+          for (int i = 0; i < total; ++i) p.H_out[(long long)(c + 1) * p.n_rows + i] = NAN;
+        }
+      }
+    }
+    live = p.decide ? stay : 0u;
+    done0 = done1 = stay = 0u;
+    return true;
+  }
+
+  // Drives attempt(c) until head c is decided (1), until the streamers of this
+  // workgroup have all finished the head they are on and `may_defer` allows
+  // carrying the exchange over to the next window (0), or until the bounded wait
+  // runs out (-1).
+  __device__ __forceinline__ int collect(int c, bool may_defer, int par) {
+    for (int spins = 0;; ++spins) {
+      if (attempt(c)) return 1;
+      if (may_defer && *sm.arrived(par) >= kStreamers) return 0;
+      if (spins > kSpinLimit) return -1;
+      __builtin_amdgcn_s_sleep(4);
+    }
+  }
+
+  template <typename DT>
+  __device__ __forceinline__ void layernorm_rows(int l, unsigned rows, lds_frag_t* ybuf) {
+    const int esz = DT::ESZ;
+    for (int n = 0; n < 16; ++n) {
+      if (!((rows >> n) & 1u)) continue;
+      const long long r = p.row_idx ? p.row_idx[n] : n;
+      const char* row = (const char*)p.h + ((long long)l * p.layer_stride + r * p.row_stride) * esz;
+      ln_row_to_lds<DT>(row, p.d, p.KS, p.gamma[l], p.beta[l], p.eps, lane, n, ybuf);
+    }
+  }
+
+  __device__ __forceinline__ unsigned initial_live() const {
+    int n_live = p.n_rows;
+    if (p.n_rows_dev) n_live = min(max(*p.n_rows_dev, 0), p.n_rows);
+    return n_live >= 32 ? 0xffffffffu : ((1u << n_live) - 1u);
+  }
+
+  // Exchange wave.  In the window in which the streamers work on head l it sends
+  // this workgroup's records of head l-1 and then drives the exchanges that are
+  // still open, oldest first.  The exchange of head l-1 may be carried over into
+  // the next window if it is not complete when the streamers are done (so a slow
+  // workgroup somewhere does not stall this one at once); anything older must
+  // complete now.  The streamers are therefore at most two heads ahead of the
+  // last decision, and they are told as soon as every row has exited.
+  __device__ __forceinline__ void run_exchange() {
+    live = initial_live();
+    if (lane == 0) *sm.live_word((p.l0 + 1) & 1) = (int)live;  // read by the LayerNorm wave in the first window
+    int c = p.l0;  // oldest head not yet decided
+    lds_barrier();  // B_{-1}
+    for (int l = p.l0; l < p.l1; ++l) {
+      const int par = l & 1;
+      stamp(p, l, 4, lane);
+      if (lane == 0) *sm.arrived(par ^ 1) = 0;  // next window's count of finished streamers
+      if (l > p.l0) announce(l - 1);
+      stamp(p, l, 5, lane);
+      while (c < l) {
+        const int r = collect(c, c == l - 1, par);
+        if (r == 0) break;
+        if (r < 0) { fail_all(par); break; }
+        ++c;
+        if (live == 0u) {
+          if (lane == 0) *sm.abort_flag(par) = 1;
+          break;
+        }
+      }
+      if (lane == 0) *sm.live_word(par) = (int)live;
+      stamp(p, l, 6, lane);
+      lds_barrier();  // B_l
+      stamp(p, l, 8, lane);
+      if (*sm.abort_flag(par)) return;
+    }
+    announce(p.l1 - 1);
+    while (c < p.l1) {
+      if (collect(c, false, 0) < 0) {
+        if (lane == 0) atomicExch(p.status, 1);
+        return;
+      }
+      ++c;
+      if (live == 0u) return;
+    }
+  }
+
+  // LayerNorm wave: one head ahead of the streamers (speculative: a row that turns
+  // out to have exited only wastes its column).  The set of rows it normalises is
+  // the one the exchange wave knew a window earlier, a superset of the live rows.
+  template <typename DT>
+  __device__ __forceinline__ void run_layernorm() {
+    live = initial_live();
+    layernorm_rows<DT>(p.l0, live, sm.ybuf(p.l0 & 1));
+    lds_barrier();  // B_{-1}
+    for (int l = p.l0; l < p.l1; ++l) {
+      const int par = l & 1;
+      live = (unsigned)*sm.live_word(par ^ 1);
+      if (l + 1 < p.l1) layernorm_rows<DT>(l + 1, live, sm.ybuf(par ^ 1));
+      stamp(p, l, 7, lane);
+      lds_barrier();  // B_l
+      if (*sm.abort_flag(par)) return;
+    }
+  }
+};
+
+template <typename DT>
+__global__ __launch_bounds__(kThreads, 1) void decode_kernel(const DecodeParams p) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  Smem sm;
+  sm.base = (EH_LDS char*)smem_raw;
+  sm.y_bytes = (unsigned)p.KS * kWave * 16;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in an SGPR
+  if (*(volatile int*)p.status != 0) return;  // a previous launch failed: do nothing
+  // zero both activation buffers (columns of rows that are not live stay zero)
+  {
+    lds_frag_t* y = sm.ybuf(0);
+    const int total = 2 * p.KS * kWave;
+    for (int i = threadIdx.x; i < total; i += kThreads) y[i] = mk_frag(0, 0, 0, 0);
+    if (threadIdx.x < 2) {
+      *sm.abort_flag(threadIdx.x) = 0;
+      *sm.arrived(threadIdx.x) = 0;
+    }
+  }
+  lds_barrier();
+  if (wave < kStreamers) {
+    streamer<DT>(p, sm, wave, lane);
+  } else {
+    Service sv{p, sm, lane, 0u};
+    if (wave == kStreamers) sv.run_exchange();
+    else sv.template run_layernorm<DT>();
+  }
+}
+
+}  // namespace
+
+hipError_t decode_prepare(eh_ctx* c) {
+  c->decode_grid = 0;
+  const int epl = c->dtype == EH_BF16 ? 8 : 4;
+  if (c->d > kMaxChunksPerLane * kWave * epl) return hipSuccess;  // row does not fit the register LayerNorm
+  if (!c->bias.empty()) return hipSuccess;  // heads with a bias vector take the general path
+  const size_t smem = smem_bytes(c->KS);
+  hipDeviceProp_t prop;
+  hipError_t e = hipGetDeviceProperties(&prop, c->device);
+  if (e != hipSuccess) return e;
+  if (smem > (size_t)prop.sharedMemPerBlock && smem > (size_t)prop.maxSharedMemoryPerMultiProcessor) return hipSuccess;
+  const void* fn = c->dtype == EH_BF16 ? (const void*)decode_kernel<DtBf16> : (const void*)decode_kernel<DtF32>;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) { (void)hipGetLastError(); return hipSuccess; }
+  int per_cu = 0;
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, smem);
+  if (e != hipSuccess || per_cu < 1) { (void)hipGetLastError(); return hipSuccess; }
+  // the kernel waits on other workgroups, so all of them must be resident at once
+  c->num_cu = prop.multiProcessorCount;
+  c->decode_grid = std::min(prop.multiProcessorCount, c->VT);
+  c->decode_smem = smem;
+  return hipSuccess;
+}
+
+hipError_t decode_launch(const eh_ctx* c, const DecodeParams& p, hipStream_t s) {
+  if (c->dtype == EH_BF16)
+    hipLaunchKernelGGL((decode_kernel<DtBf16>), dim3(c->decode_grid), dim3(kThreads), c->decode_smem, s, p);
+  else
+    hipLaunchKernelGGL((decode_kernel<DtF32>), dim3(c->decode_grid), dim3(kThreads), c->decode_smem, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace eh

@@ -1,0 +1,81 @@
+// Host-side internals shared by the translation units of libeh.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "eh.h"
+#include "eh_device.hpp"
+
+struct eh_ctx {
+  int d = 0, V = 0, n_heads = 0, max_rows = 0, dtype = 0, device = 0;
+  float eps = 1e-5f;
+  int KS = 0, VT = 0, R_pad_max = 0;
+  int num_cu = 0;
+  std::vector<eh::frag_t*> Wf;  // per head, fragment-major weights
+  std::vector<float*> gamma, beta, bias;
+  std::vector<float> tau;
+  // device-side copies of the per-head tables (read by the persistent kernel)
+  eh::frag_t** d_Wf = nullptr;
+  float** d_gamma = nullptr;
+  float** d_beta = nullptr;
+  float** d_bias = nullptr;
+  float* d_tau = nullptr;
+  eh::frag_t* yf = nullptr;     // [R_pad_max/16][KS][64] activations in fragment order
+  eh::Stats* partials = nullptr;  // [kStreamGrid][R_pad_max]
+  float* ws_H = nullptr;        // [max_rows] internal outputs (cascade, verify)
+  float* ws_lse = nullptr;
+  int* ws_argmax = nullptr;
+  int* active[2] = {nullptr, nullptr};
+  int* n_active[2] = {nullptr, nullptr};
+  // persistent decode kernel: control block and per-head partials
+  int decode_grid = 0;          // 0 = shape not supported by the decode kernel
+  size_t decode_smem = 0;
+  unsigned long long* dec_records = nullptr;  // [2 rounds][n_heads][decode_grid][16][5] {tag, payload} words
+  int* dec_status = nullptr;                // sticky device-side failure flag
+  unsigned dec_epoch = 0;
+  unsigned long long* dec_trace = nullptr;  // [n_heads][16] timestamps of workgroup 0 (diagnostics)
+  int dec_trace_on = 0;
+  std::vector<void*> allocs;
+  std::string err = "";
+};
+
+namespace eh {
+
+// Arguments of the persistent decode kernel (<= 16 rows, heads l0 .. l1-1).
+struct DecodeParams {
+  const frag_t* const* Wf;
+  const float* const* gamma;
+  const float* const* beta;
+  const float* const* bias;  // nullable
+  const float* tau;
+  const void* h;
+  long long layer_stride, row_stride;  // elements
+  const int* row_idx;                  // nullable gather list (evaluation mode)
+  const int* n_rows_dev;               // nullable live-row count
+  int n_rows, l0, l1, n_heads, decide;
+  int V, d, KS, VT;
+  float eps;
+  unsigned long long* records;  // [2 rounds][n_heads_alloc][grid][16][5]
+  int n_heads_alloc;            // head stride of the record array
+  unsigned epoch;               // this launch's tag, never 0
+  int* status;
+  float* H;
+  float* lse;
+  int* argmax;       // evaluation mode outputs [n_rows]
+  int* exit_layer;
+  int* token;        // cascade outputs [n_rows]
+  float* H_out;      // nullable [n_heads][n_rows]
+  unsigned long long* n_evals;  // nullable
+  unsigned long long* trace;    // nullable: [n_heads][16] wall-clock stamps written by workgroup 0
+};
+
+// Sets up the decode kernel for this context (grid, LDS size, function
+// attributes).  Leaves ctx->decode_grid = 0 if the shape does not fit.
+hipError_t decode_prepare(eh_ctx* ctx);
+// Enqueues the decode kernel.
+hipError_t decode_launch(const eh_ctx* ctx, const DecodeParams& p, hipStream_t s);
+
+}  // namespace eh

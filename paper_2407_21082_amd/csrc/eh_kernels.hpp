@@ -249,7 +249,7 @@ __device__ __forceinline__ void stats_finalize(const Stats& s, float& H, float& 
   lse = (float)(kLn2d * ((double)s.m + l2));
 }
 
-__global__ __launch_bounds__(64) void finalize_kernel(const Stats* __restrict__ partials, int n_parts,
+static __global__ __launch_bounds__(64) void finalize_kernel(const Stats* __restrict__ partials, int n_parts,
                                                       int R_pad, const int* __restrict__ n_rows_dev,
                                                       int n_rows, float* __restrict__ H,
                                                       float* __restrict__ lse, int* __restrict__ argmax) {
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(64) void finalize_kernel(const Stats* __restrict__ 
 // Exit rule + stable compaction.  Single workgroup; positions are processed in
 // chunks of blockDim.x with a block-wide exclusive scan of the "stays" flags.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void decide_kernel(const float* __restrict__ H,
+static __global__ __launch_bounds__(256) void decide_kernel(const float* __restrict__ H,
                                                      const int* __restrict__ argmax,
                                                      const int* __restrict__ row_idx,
                                                      const int* __restrict__ n_rows_dev, int n_rows,
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256) void decide_kernel(const float* __restrict__ H
 // ---------------------------------------------------------------------------
 // DSSD: length of the accepted prefix and the token that follows it.
 // ---------------------------------------------------------------------------
-__global__ void verify_compare_kernel(const int* __restrict__ draft, const int* __restrict__ draft_len,
+static __global__ void verify_compare_kernel(const int* __restrict__ draft, const int* __restrict__ draft_len,
                                       const int* __restrict__ target, int B, int k,
                                       int* __restrict__ accepted, int* __restrict__ next_token) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -341,11 +341,11 @@ __global__ void verify_compare_kernel(const int* __restrict__ draft, const int* 
   next_token[b] = target[(int64_t)b * (k + 1) + n];
 }
 
-__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+static __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
-__global__ void fill_i32_kernel(int* p, int64_t n, int v) {
+static __global__ void fill_i32_kernel(int* p, int64_t n, int v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
