@@ -30,6 +30,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until measured for the current kernel.
+TRAFFIC = None
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -109,34 +112,36 @@ def main():
         torch.cuda.synchronize()
         nev.zero_()
         torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
+        ev0.record()
         for _ in range(args.steps):
             step()
+        ev1.record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        ev_s = ev0.elapsed_time(ev1) * 1e-3
+        B.eh_check(ctx)                       # raises if the kernel reported a device-side failure
         evals = int(nev.item())
         evals_per_step = evals / args.steps
         value = evals / dt
 
-        # dominant kernel: one head on one row = one launch streaming the head's weights once.
-        Hb = torch.zeros(16, device=dev)
-        Lb = torch.zeros(16, device=dev)
-        Ab = torch.zeros(16, dtype=torch.int32, device=dev)
-        reps = 20
-        def sweep():
-            for _ in range(reps):
-                for l in range(w.n_heads):
-                    B.eh_eval(ctx, l, hid.h[l, 0:1], 1, Hb, Lb, Ab)
-        sweep()
-        torch.cuda.synchronize()
-        ms = event_ms(sweep, torch)
-        launches = reps * w.n_heads
-        bytes_per_launch = w.d * w.V * esz + w.d * esz + 12
-        avg_s = ms * 1e-3 / launches
+        # Dominant kernel: the persistent decode kernel, one launch per decode step
+        # (LayerNorm, projection, entropy/argmax, exchange and exit test of every head
+        # up to the exit head).  Algorithmic bytes per launch = evaluations in that
+        # launch x (weights of one head + one hidden row + 12 bytes of results);
+        # average launch duration from HIP events around the timed region, on the
+        # stream the launches went to (launches are back to back).
+        launches = args.steps * n_dec
+        bytes_per_eval = w.d * w.V * esz + w.d * esz + 12
+        bytes_per_launch = bytes_per_eval * evals / launches
+        avg_s = ev_s / launches
         roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
-                "kernel": "eh_eval (1 row, 1 head)", "avg_launch_us": avg_s * 1e6,
-                "bytes_per_launch": bytes_per_launch}
+                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC,
+                "kernel": "eh::decode_kernel<DtBf16> (one launch = one decode step's cascade)",
+                "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch,
+                "launches": launches}
         cfg = {"workload": "c1_decode: d=1024 V=50304 24 heads batch-1 bf16, "
                            f"{n_dec} decode steps per bench step, exit at first H<tau",
                "decode_steps": n_dec, "mean_evals_per_decode_step": evals_per_step / n_dec,

@@ -32,9 +32,10 @@ namespace eh {
 
 namespace {
 
-constexpr int kStreamers = 4;
+constexpr int kStreamers = 8;
 constexpr int kThreads = (kStreamers + 2) * kWave;  // streamers + exchange wave + LayerNorm wave
-constexpr int kRing = 8;              // fragments per ring buffer (two buffers per streamer wave)
+constexpr int kRing = 4;              // fragments per ring buffer (two buffers per streamer wave)
+constexpr int kMaxLag = 3;            // heads the streamers may be ahead of the oldest open exchange
 constexpr int kSpinLimit = 1 << 22;   // polls of a global flag before giving up
 constexpr int kMaxChunksPerLane = 4;  // LayerNorm keeps a row in registers: d <= 4*64*EPL
 
@@ -87,17 +88,18 @@ struct Smem {
   __device__ __forceinline__ unsigned o2() const {
     return o1() + 4 * (kStreamers * kWave * 16) + 2 * (5 * kStreamers * kWave * 4);
   }
-  __device__ __forceinline__ lds_int_t* part_tile(int par) const { return (lds_int_t*)(base + o2() + par * 16); }
-  __device__ __forceinline__ lds_int_t* pend_tile(int par) const { return (lds_int_t*)(base + o2() + 32 + par * 16); }
-  __device__ __forceinline__ lds_vint_t* abort_flag(int par) const { return (lds_vint_t*)(base + o2() + 64 + par * 4); }
+  __device__ __forceinline__ lds_int_t* part_tile(int par) const { return (lds_int_t*)(base + o2() + par * (kStreamers * 4)); }
+  __device__ __forceinline__ lds_int_t* pend_tile(int par) const { return (lds_int_t*)(base + o2() + (2 + par) * (kStreamers * 4)); }
+  __device__ __forceinline__ unsigned o3() const { return o2() + 4 * (kStreamers * 4); }
+  __device__ __forceinline__ lds_vint_t* abort_flag(int par) const { return (lds_vint_t*)(base + o3() + par * 4); }
   // rows entering head l, left by the exchange wave for the LayerNorm wave (by parity of l)
-  __device__ __forceinline__ lds_vint_t* live_word(int par) const { return (lds_vint_t*)(base + o2() + 72 + par * 4); }
+  __device__ __forceinline__ lds_vint_t* live_word(int par) const { return (lds_vint_t*)(base + o3() + 8 + par * 4); }
   // number of streamer waves that have finished the head of this parity
-  __device__ __forceinline__ lds_vint_t* arrived(int par) const { return (lds_vint_t*)(base + o2() + 80 + par * 4); }
+  __device__ __forceinline__ lds_vint_t* arrived(int par) const { return (lds_vint_t*)(base + o3() + 16 + par * 4); }
 };
 
 inline size_t smem_bytes(int KS) {
-  return 2 * (size_t)KS * kWave * 16 + 4 * kStreamers * kWave * 16 + 2 * 5 * kStreamers * kWave * 4 + 64 + 32;
+  return 2 * (size_t)KS * kWave * 16 + 4 * kStreamers * kWave * 16 + 2 * 5 * kStreamers * kWave * 4 + 4 * kStreamers * 4 + 32;
 }
 
 // Push with an explicit index tie-break (rows may arrive in any order).
@@ -408,16 +410,36 @@ struct Service {
       o.ib = __float_as_int(ws[(4 * kStreamers + w) * kWave]);
       s = stats_merge(s, o);
     }
+    stamp(p, dbg_l, 11, lane);
     const int q = lane >> 4;
+    // tile ids of all parked pieces in one LDS round trip, then scalar copies
+    const int my_pend = lane < kStreamers ? sm.pend_tile(par)[lane] : -1;
+    const int my_part = lane < kStreamers ? sm.part_tile(par)[lane] : -1;
+    int pend_t[kStreamers], part_t[kStreamers];
+#pragma unroll
     for (int w = 0; w < kStreamers; ++w) {
-      const int t = sm.pend_tile(par)[w];
+      pend_t[w] = __builtin_amdgcn_readlane(my_pend, w);
+      part_t[w] = __builtin_amdgcn_readlane(my_part, w);
+    }
+    // all piece slots in one go (slots without a piece hold stale data and are not used)
+    f32x4 pend_v[kStreamers], part_v[kStreamers];
+#pragma unroll
+    for (int w = 0; w < kStreamers; ++w) {
+      pend_v[w] = sm.pend(par)[w * kWave + lane];
+      part_v[w] = sm.part(par)[w * kWave + lane];
+    }
+#pragma unroll
+    for (int w = 0; w < kStreamers; ++w) {
+      const int t = pend_t[w];
       if (t < 0) continue;
-      f32x4 z = sm.pend(par)[w * kWave + lane];
+      f32x4 z = pend_v[w];
+#pragma unroll
       for (int w2 = w + 1; w2 < kStreamers; ++w2)  // later pieces of the same tile, in wave order
-        if (sm.part_tile(par)[w2] == t) z += sm.part(par)[w2 * kWave + lane];
+        if (part_t[w2] == t) z += part_v[w2];
       const int row0 = t * 16 + q * 4;
       if (row0 >= sl.row_lo) stats_push4_any(s, z, row0, sl.row_hi);
     }
+    stamp(p, dbg_l, 12, lane);
     s = stats_merge(s, stats_shfl_xor(s, 16));
     s = stats_merge(s, stats_shfl_xor(s, 32));
     return s;
@@ -437,33 +459,38 @@ struct Service {
       __hip_atomic_store(r + i, tag | w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
-  // Reads a record; false while it does not carry this launch's tag in every word.
-  __device__ __forceinline__ bool read_record(const unsigned long long* r, Stats& o) const {
+  // A record as loaded: five {tag, payload} words.
+  struct Raw {
     unsigned long long w[5];
+  };
+  __device__ __forceinline__ Raw load_record(const unsigned long long* r) const {
+    Raw x;
 #pragma unroll
-    for (int i = 0; i < 5; ++i) w[i] = __hip_atomic_load(r + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int i = 0; i < 5; ++i) x.w[i] = __hip_atomic_load(r + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return x;
+  }
+  // True if every word carries this launch's tag; then `o` is the record.
+  __device__ __forceinline__ bool decode_record(const Raw& x, Stats& o) const {
     bool ok = true;
 #pragma unroll
-    for (int i = 0; i < 5; ++i) ok = ok && ((unsigned)(w[i] >> 32) == p.epoch);
-    o.m = __uint_as_float((unsigned)w[0]);
-    o.S = __uint_as_float((unsigned)w[1]);
-    o.U = __uint_as_float((unsigned)w[2]);
-    o.zb = __uint_as_float((unsigned)w[3]);
-    o.ib = (int)(unsigned)w[4];
+    for (int i = 0; i < 5; ++i) ok = ok && ((unsigned)(x.w[i] >> 32) == p.epoch);
+    o.m = __uint_as_float((unsigned)x.w[0]);
+    o.S = __uint_as_float((unsigned)x.w[1]);
+    o.U = __uint_as_float((unsigned)x.w[2]);
+    o.zb = __uint_as_float((unsigned)x.w[3]);
+    o.ib = (int)(unsigned)x.w[4];
     return ok;
   }
 
-  // One attempt at one round of the exchange for row n: lane i < count reads the
-  // record of workgroup src(i).  If every record is there they are merged in lane
-  // order (fixed tree), so every reader of the same records gets bitwise the same
-  // result, and true is returned; otherwise false (nothing is kept: the caller
-  // tries again later).
-  template <typename SrcFn>
-  __device__ __forceinline__ bool try_round(int round, int l, int n, int count, SrcFn src, Stats& out) {
+  // Lane i < count holds (in `x`) the record of the i-th source of a round.  If
+  // every record is there they are merged in lane order (fixed tree), so every
+  // reader of the same records gets bitwise the same result, and true is
+  // returned; otherwise false (nothing is kept: the caller tries again later).
+  __device__ __forceinline__ bool merge_round(const Raw& x, int count, Stats& out) const {
     Stats s;
     stats_init(s);
     bool have = true;
-    if (lane < count) have = read_record(record(round, l, src(lane), n), s);
+    if (lane < count) have = decode_record(x, s);
     if (!__all(have)) return false;
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) s = stats_merge(s, stats_shfl_xor(s, o));
@@ -478,7 +505,10 @@ struct Service {
   // First half of what follows the streamers' work on head l: this workgroup's
   // round-0 records go out.
   __device__ __forceinline__ void announce(int l) {
+    stamp(p, l + 1, 9, lane);
+    dbg_l = l + 1;
     const Stats mine = gather_wg(l & 1);
+    stamp(p, l + 1, 10, lane);
     if (lane < 16 && ((live >> lane) & 1u)) write_record(record(0, l, blockIdx.x, lane), mine);
   }
 
@@ -489,53 +519,86 @@ struct Service {
   // most kRadix workgroups, and a workgroup polls at most 2*kRadix records per
   // row, so the waiting costs little bandwidth and has no hot spot.
   //
-  // The exchange of head c advances row by row as records come in (done0: rows
-  // whose round-1 record this workgroup has written; done1: rows decided), so it
-  // can be resumed: attempt() makes one pass and returns true once head c is
+  // Several heads are in flight at once: `c` is the oldest head not yet decided,
+  // `sent` the number of heads announced so far.  Round 0 runs for every announced
+  // head (its result does not depend on earlier decisions; rows that turn out to
+  // have exited only cost a wasted record), round 1 and the decision run for head
+  // c only, in order.  done0 holds, for the heads c .. c+3 (slot = head & 3), the
+  // rows whose round-1 record this workgroup has written; done1 the rows of head
+  // c that are decided.  pass() makes one sweep and returns true if head c got
   // decided, with `live` then holding the rows that go on to head c+1.
   static constexpr int kRadix = 16;
-  unsigned done0 = 0, done1 = 0, stay = 0;
+  static constexpr int kWindow = 4;
+  unsigned long long done0 = 0;
+  unsigned done1 = 0, stay = 0;
+  int c = 0, sent = 0;
+  int dbg_l = 0;
 
-  __device__ __forceinline__ bool attempt(int c) {
+  __device__ __forceinline__ bool pass() {
     const int grid = gridDim.x, me = blockIdx.x;
     const int member = me % kRadix;
     const int g0 = (me / kRadix) * kRadix;
     const int gsize = min(kRadix, grid - g0);
     const int ngroups = (grid + kRadix - 1) / kRadix;
     const bool writer = me == 0 && lane == 0;
-    for (int n = 0; n < 16; ++n) {
-      if (!(((live & ~done0) >> n) & 1u)) continue;
-      Stats s;
-      if (try_round(0, c, n, gsize, [&](int i) { return g0 + i; }, s)) {
-        if (lane == 0) write_record(record(1, c, me, n), s);
-        done0 |= 1u << n;
+    // One row per open head and round in a sweep (the lowest one that still needs
+    // work), with all loads of the sweep issued before any is looked at, so that a
+    // sweep costs one memory round trip however many heads are open.
+    Raw x0[kWindow], x1;
+    int row0[kWindow], row1 = -1;
+#pragma unroll
+    for (int k = 0; k < kWindow; ++k) {
+      const int h = c + k;
+      const int sh = (h & (kWindow - 1)) * 16;
+      const unsigned todo = (h < sent) ? (live & ~(unsigned)((done0 >> sh) & 0xffffu)) : 0u;
+      row0[k] = todo ? __ffs(todo) - 1 : -1;
+      if (row0[k] >= 0 && lane < gsize) x0[k] = load_record(record(0, h, g0 + lane, row0[k]));
+    }
+    const int sc = (c & (kWindow - 1)) * 16;
+    if (c < sent) {
+      const unsigned todo = (unsigned)((done0 >> sc) & 0xffffu) & live & ~done1;
+      row1 = todo ? __ffs(todo) - 1 : -1;
+      if (row1 >= 0 && lane < ngroups) {
+        const int j = lane;
+        const int src = j * kRadix + min(member, min(kRadix, grid - j * kRadix) - 1);
+        x1 = load_record(record(1, c, src, row1));
       }
     }
-    for (int n = 0; n < 16; ++n) {
-      if (!(((done0 & ~done1) >> n) & 1u)) continue;
+#pragma unroll
+    for (int k = 0; k < kWindow; ++k) {
+      if (row0[k] < 0) continue;
+      const int h = c + k;
       Stats s;
-      auto src = [&](int j) { return j * kRadix + min(member, min(kRadix, grid - j * kRadix) - 1); };
-      if (!try_round(1, c, n, ngroups, src, s)) continue;
-      done1 |= 1u << n;
-      float H, lse;
-      stats_finalize(s, H, lse);
-      if (p.decide) {
-        const bool leaves = (c == p.n_heads - 1) || (H < p.tau[c]);
-        if (!leaves) stay |= 1u << n;
-        if (writer) {
-          if (leaves) {
-            p.exit_layer[n] = c;
-            p.token[n] = s.ib;
+      if (merge_round(x0[k], gsize, s)) {
+        if (lane == 0) write_record(record(1, h, me, row0[k]), s);
+        done0 |= 1ull << ((h & (kWindow - 1)) * 16 + row0[k]);
+      }
+    }
+    if (row1 >= 0) {
+      const int n = row1;
+      Stats s;
+      if (merge_round(x1, ngroups, s)) {
+        done1 |= 1u << n;
+        float H, lse;
+        stats_finalize(s, H, lse);
+        if (p.decide) {
+          const bool leaves = (c == p.n_heads - 1) || (H < p.tau[c]);
+          if (!leaves) stay |= 1u << n;
+          if (writer) {
+            if (leaves) {
+              p.exit_layer[n] = c;
+              p.token[n] = s.ib;
+            }
+            if (p.H_out) p.H_out[(long long)c * p.n_rows + n] = H;
           }
-          if (p.H_out) p.H_out[(long long)c * p.n_rows + n] = H;
+        } else if (writer) {
+          if (p.H) p.H[n] = H;
+          if (p.lse) p.lse[n] = lse;
+          if (p.argmax) p.argmax[n] = s.ib;
         }
-      } else if (writer) {
-        if (p.H) p.H[n] = H;
-        if (p.lse) p.lse[n] = lse;
-        if (p.argmax) p.argmax[n] = s.ib;
       }
     }
-    if (done1 != live) return false;
+    if (c >= sent || done1 != live) return false;
     if (writer && p.decide) {
       if (p.n_evals) atomicAdd(p.n_evals, (unsigned long long)__popc(live));
       if (p.H_out) {
@@ -548,21 +611,10 @@ struct Service {
       }
     }
     live = p.decide ? stay : 0u;
-    done0 = done1 = stay = 0u;
+    done0 &= ~(0xffffull << sc);
+    done1 = stay = 0u;
+    ++c;
     return true;
-  }
-
-  // Drives attempt(c) until head c is decided (1), until the streamers of this
-  // workgroup have all finished the head they are on and `may_defer` allows
-  // carrying the exchange over to the next window (0), or until the bounded wait
-  // runs out (-1).
-  __device__ __forceinline__ int collect(int c, bool may_defer, int par) {
-    for (int spins = 0;; ++spins) {
-      if (attempt(c)) return 1;
-      if (may_defer && *sm.arrived(par) >= kStreamers) return 0;
-      if (spins > kSpinLimit) return -1;
-      __builtin_amdgcn_s_sleep(4);
-    }
   }
 
   template <typename DT>
@@ -583,32 +635,45 @@ struct Service {
   }
 
   // Exchange wave.  In the window in which the streamers work on head l it sends
-  // this workgroup's records of head l-1 and then drives the exchanges that are
-  // still open, oldest first.  The exchange of head l-1 may be carried over into
-  // the next window if it is not complete when the streamers are done (so a slow
-  // workgroup somewhere does not stall this one at once); anything older must
-  // complete now.  The streamers are therefore at most two heads ahead of the
-  // last decision, and they are told as soon as every row has exited.
+  // this workgroup's records of head l-1 and then keeps sweeping the open
+  // exchanges until the streamers have finished head l.  Only when the oldest open
+  // exchange falls more than kMaxLag heads behind does it hold the streamers back
+  // (bounded wait), so one slow workgroup somewhere does not stall this one at
+  // once.  The streamers are told as soon as every row has exited.
   __device__ __forceinline__ void run_exchange() {
     live = initial_live();
     if (lane == 0) *sm.live_word((p.l0 + 1) & 1) = (int)live;  // read by the LayerNorm wave in the first window
-    int c = p.l0;  // oldest head not yet decided
+    c = sent = p.l0;
     lds_barrier();  // B_{-1}
     for (int l = p.l0; l < p.l1; ++l) {
       const int par = l & 1;
       stamp(p, l, 4, lane);
       if (lane == 0) *sm.arrived(par ^ 1) = 0;  // next window's count of finished streamers
-      if (l > p.l0) announce(l - 1);
+      if (l > p.l0) {
+        announce(l - 1);
+        sent = l;
+      }
       stamp(p, l, 5, lane);
-      while (c < l) {
-        const int r = collect(c, c == l - 1, par);
-        if (r == 0) break;
-        if (r < 0) { fail_all(par); break; }
-        ++c;
-        if (live == 0u) {
-          if (lane == 0) *sm.abort_flag(par) = 1;
-          break;
+      for (int spins = 0; c < sent; ++spins) {
+        if (pass()) {
+          spins = 0;
+          if (live == 0u) {
+            if (lane == 0) *sm.abort_flag(par) = 1;
+            break;
+          }
+          continue;
         }
+        // The streamers must not wait for this wave: between sweeps, watch (in LDS,
+        // which costs nothing) for them to finish the head, and carry what is
+        // still open over into the next window when they have.
+        const bool may_defer = c >= l - kMaxLag;
+        bool done = false;
+        for (int k = 0; k < 24 && !done; ++k) {
+          done = may_defer && *sm.arrived(par) >= kStreamers;
+          if (!done) __builtin_amdgcn_s_sleep(2);
+        }
+        if (done) break;
+        if (spins > kSpinLimit) { fail_all(par); break; }
       }
       if (lane == 0) *sm.live_word(par) = (int)live;
       stamp(p, l, 6, lane);
@@ -617,13 +682,14 @@ struct Service {
       if (*sm.abort_flag(par)) return;
     }
     announce(p.l1 - 1);
-    while (c < p.l1) {
-      if (collect(c, false, 0) < 0) {
+    sent = p.l1;
+    for (int spins = 0; c < sent && live != 0u; ++spins) {
+      if (pass()) { spins = 0; continue; }
+      if (spins > kSpinLimit) {
         if (lane == 0) atomicExch(p.status, 1);
         return;
       }
-      ++c;
-      if (live == 0u) return;
+      __builtin_amdgcn_s_sleep(4);
     }
   }
 
