@@ -73,33 +73,31 @@ struct Smem {
   unsigned y_bytes;  // KS * 1 KiB
   __device__ __forceinline__ lds_frag_t* ybuf(int par) const { return (lds_frag_t*)(base + par * y_bytes); }
   __device__ __forceinline__ unsigned o1() const { return 2 * y_bytes; }
-  // tile pieces that start at k > 0: [par][4][64] f32x4
+  // head pieces (the part of a wave's first tile that starts at k > 0): [par][kStreamers][64] f32x4
   __device__ __forceinline__ lds_f32x4_t* part(int par) const {
     return (lds_f32x4_t*)(base + o1() + par * (kStreamers * kWave * 16));
   }
-  // tile pieces that start at k = 0 but end early: [par][4][64] f32x4
-  __device__ __forceinline__ lds_f32x4_t* pend(int par) const {
-    return (lds_f32x4_t*)(base + o1() + (2 + par) * (kStreamers * kWave * 16));
-  }
-  // per-lane statistics of the streamers: [par][5][4][64] float (ib stored as bits)
+  // per-token statistics of each streamer wave: [par][5][kStreamers][16] float (ib stored as bits)
   __device__ __forceinline__ lds_float_t* wst(int par) const {
-    return (lds_float_t*)(base + o1() + 4 * (kStreamers * kWave * 16) + par * (5 * kStreamers * kWave * 4));
+    return (lds_float_t*)(base + o1() + 2 * (kStreamers * kWave * 16) + par * (5 * kStreamers * 16 * 4));
   }
   __device__ __forceinline__ unsigned o2() const {
-    return o1() + 4 * (kStreamers * kWave * 16) + 2 * (5 * kStreamers * kWave * 4);
+    return o1() + 2 * (kStreamers * kWave * 16) + 2 * (5 * kStreamers * 16 * 4);
   }
-  __device__ __forceinline__ lds_int_t* part_tile(int par) const { return (lds_int_t*)(base + o2() + par * (kStreamers * 4)); }
-  __device__ __forceinline__ lds_int_t* pend_tile(int par) const { return (lds_int_t*)(base + o2() + (2 + par) * (kStreamers * 4)); }
-  __device__ __forceinline__ unsigned o3() const { return o2() + 4 * (kStreamers * 4); }
+  // head id + 1 of the head piece currently in part(par)[wave]
+  __device__ __forceinline__ lds_vint_t* part_flag(int par) const { return (lds_vint_t*)(base + o2() + par * (kStreamers * 4)); }
+  __device__ __forceinline__ unsigned o3() const { return o2() + 2 * (kStreamers * 4); }
   __device__ __forceinline__ lds_vint_t* abort_flag(int par) const { return (lds_vint_t*)(base + o3() + par * 4); }
   // rows entering head l, left by the exchange wave for the LayerNorm wave (by parity of l)
   __device__ __forceinline__ lds_vint_t* live_word(int par) const { return (lds_vint_t*)(base + o3() + 8 + par * 4); }
   // number of streamer waves that have finished the head of this parity
   __device__ __forceinline__ lds_vint_t* arrived(int par) const { return (lds_vint_t*)(base + o3() + 16 + par * 4); }
+  // number of heads (absolute index + 1 of the last one) whose records this workgroup has sent
+  __device__ __forceinline__ lds_vint_t* sent_word() const { return (lds_vint_t*)(base + o3() + 24); }
 };
 
 inline size_t smem_bytes(int KS) {
-  return 2 * (size_t)KS * kWave * 16 + 4 * kStreamers * kWave * 16 + 2 * 5 * kStreamers * kWave * 4 + 4 * kStreamers * 4 + 32;
+  return 2 * (size_t)KS * kWave * 16 + 2 * kStreamers * kWave * 16 + 2 * 5 * kStreamers * 16 * 4 + 2 * kStreamers * 4 + 32;
 }
 
 // Push with an explicit index tie-break (rows may arrive in any order).
@@ -227,6 +225,19 @@ __device__ __forceinline__ Slice my_slice(int V) {
   return s;
 }
 
+// record of workgroup g, row n, head l in exchange round `round` (0 or 1)
+__device__ __forceinline__ unsigned long long* record_ptr(const DecodeParams& p, int round, int l, int g, int n) {
+  return p.records + ((((long long)round * p.n_heads_alloc + l) * gridDim.x + g) * 16 + n) * 5;
+}
+__device__ __forceinline__ void write_record(const DecodeParams& p, unsigned long long* r, const Stats& s) {
+  const unsigned long long tag = (unsigned long long)p.epoch << 32;
+  const unsigned w[5] = {__float_as_uint(s.m), __float_as_uint(s.S), __float_as_uint(s.U),
+                         __float_as_uint(s.zb), (unsigned)s.ib};
+#pragma unroll
+  for (int i = 0; i < 5; ++i)
+    __hip_atomic_store(r + i, tag | w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ------------------------------------------------------------------ streamers
 // The weight stream of one wave is cut into groups of kRing fragments.  Two
 // register buffers of one group each alternate: while one is consumed the other
@@ -241,7 +252,12 @@ __device__ __forceinline__ void streamer(const DecodeParams& p, const Smem& sm, 
   const Slice sl = my_slice(p.V);
   const int T0 = sl.T0, T1 = sl.T1;
   const int nF = (T1 - T0) * KS;
-  const int F0 = (int)((long long)nF * wave / kStreamers), F1 = (int)((long long)nF * (wave + 1) / kStreamers);
+  // The slice's fragments are split evenly over the streamer waves, so a tile
+  // may be cut between two neighbouring waves (never more: every span is at least
+  // a tile long).  Slices too small for that are split by whole tiles instead.
+  const bool even = nF >= kStreamers * KS;
+  const int F0 = even ? (int)((long long)nF * wave / kStreamers) : KS * ((T1 - T0) * wave / kStreamers);
+  const int F1 = even ? (int)((long long)nF * (wave + 1) / kStreamers) : KS * ((T1 - T0) * (wave + 1) / kStreamers);
   const int n_w = F1 - F0;
   const int G = (n_w + P - 1) / P;
   const int G2 = (G + 1) & ~1;
@@ -281,24 +297,26 @@ __device__ __forceinline__ void streamer(const DecodeParams& p, const Smem& sm, 
     stats_init(st);
     int t = T0 + F0 / KS, ks = F0 % KS;
     int piece_k0 = ks;
-    bool have_part = false, have_pend = false;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     if (wave == 0) stamp(p, l, 0, lane);
 
-    // A piece (a run of k-steps of one tile) is complete: fold it into the running
-    // statistics if it is the whole tile, otherwise park it in LDS for the service wave.
+    // A piece (a run of k-steps of one tile) is complete.  A whole tile is folded
+    // into the running statistics.  A head piece (my first tile, begun by the
+    // previous wave) is parked in LDS at once for that wave to pick up; a tail
+    // piece (my last tile, finished by the next wave) stays in `tail` until the
+    // end of the head.
+    f32x4 tail = f32x4{0.f, 0.f, 0.f, 0.f};
+    int tail_tile = -1;
     auto flush = [&](bool tile_end) {
       const int row0 = t * 16 + q * 4;
       if (piece_k0 == 0 && tile_end) {
         if (row0 >= sl.row_lo) stats_push4<false>(st, acc, row0, sl.row_hi);
       } else if (piece_k0 > 0) {
         sm.part(par)[wave * kWave + lane] = acc;
-        if (lane == 0) sm.part_tile(par)[wave] = t;
-        have_part = true;
+        if (lane == 0) sm.part_flag(par)[wave] = l + 1;  // after the data: LDS keeps a wave's order
       } else {
-        sm.pend(par)[wave * kWave + lane] = acc;
-        if (lane == 0) sm.pend_tile(par)[wave] = t;
-        have_pend = true;
+        tail = acc;
+        tail_tile = t;
       }
       acc = f32x4{0.f, 0.f, 0.f, 0.f};
       piece_k0 = 0;
@@ -352,16 +370,39 @@ __device__ __forceinline__ void streamer(const DecodeParams& p, const Smem& sm, 
       consume(bufB, g + 1);
       refill(bufB, g + 3);
     }
-    if (lane == 0) {
-      if (!have_part) sm.part_tile(par)[wave] = -1;
-      if (!have_pend) sm.pend_tile(par)[wave] = -1;
+    const bool dropped = *sm.abort_flag(par) != 0;
+    if (tail_tile >= 0 && !dropped) {
+      // the rest of my last tile is the next wave's head piece, parked long ago
+      bool there = false;
+      for (int spins = 0; spins < kSpinLimit && !there; ++spins) {
+        there = sm.part_flag(par)[wave + 1] == l + 1;
+        if (!there) {
+          if (*sm.abort_flag(par)) break;
+          __builtin_amdgcn_s_sleep(2);
+        }
+      }
+      if (there) {
+        tail += sm.part(par)[(wave + 1) * kWave + lane];
+        const int row0 = tail_tile * 16 + q * 4;
+        if (row0 >= sl.row_lo) stats_push4<false>(st, tail, row0, sl.row_hi);
+      } else if (!*sm.abort_flag(par)) {
+        if (lane == 0) {  // cannot happen unless a wave is stuck: give up cleanly
+          atomicExch(p.status, 1);
+          *sm.abort_flag(par) = 1;
+        }
+      }
     }
-    lds_float_t* ws = sm.wst(par) + wave * kWave + lane;
-    ws[0 * kStreamers * kWave] = st.m;
-    ws[1 * kStreamers * kWave] = st.S;
-    ws[2 * kStreamers * kWave] = st.U;
-    ws[3 * kStreamers * kWave] = st.zb;
-    ws[4 * kStreamers * kWave] = __int_as_float(st.ib);
+    // one record per token: fold the four row groups, leave them for the exchange wave
+    st = stats_merge(st, stats_shfl_xor(st, 16));
+    st = stats_merge(st, stats_shfl_xor(st, 32));
+    lds_float_t* ws = sm.wst(par);
+    if (lane < 16) {
+      ws[(0 * kStreamers + wave) * 16 + lane] = st.m;
+      ws[(1 * kStreamers + wave) * 16 + lane] = st.S;
+      ws[(2 * kStreamers + wave) * 16 + lane] = st.U;
+      ws[(3 * kStreamers + wave) * 16 + lane] = st.zb;
+      ws[(4 * kStreamers + wave) * 16 + lane] = __int_as_float(st.ib);
+    }
     if (wave == 0) stamp(p, l, 1, lane);
     if (lane == 0) __hip_atomic_fetch_add((EH_LDS int*)sm.arrived(par), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     lds_barrier();  // B_l
@@ -394,69 +435,25 @@ struct Service {
     }
   }
 
-  // Statistics of this workgroup for head l (parity par), one record per token in lanes 0..15.
-  __device__ __forceinline__ Stats gather_wg(int par) {
-    const Slice sl = my_slice(p.V);
-    Stats s;
-    stats_init(s);
-    const lds_float_t* ws = sm.wst(par) + lane;
+  // Sends this workgroup's round-0 records of head l (parity par): the streamer
+  // waves have left one record per token each in LDS; merged in wave order.
+  __device__ __forceinline__ void announce(int l) {
+    const lds_float_t* ws = sm.wst(l & 1);
+    if (lane < 16 && ((live >> lane) & 1u)) {
+      Stats s;
+      stats_init(s);
 #pragma unroll
-    for (int w = 0; w < kStreamers; ++w) {
-      Stats o;
-      o.m = ws[(0 * kStreamers + w) * kWave];
-      o.S = ws[(1 * kStreamers + w) * kWave];
-      o.U = ws[(2 * kStreamers + w) * kWave];
-      o.zb = ws[(3 * kStreamers + w) * kWave];
-      o.ib = __float_as_int(ws[(4 * kStreamers + w) * kWave]);
-      s = stats_merge(s, o);
+      for (int w = 0; w < kStreamers; ++w) {
+        Stats o;
+        o.m = ws[(0 * kStreamers + w) * 16 + lane];
+        o.S = ws[(1 * kStreamers + w) * 16 + lane];
+        o.U = ws[(2 * kStreamers + w) * 16 + lane];
+        o.zb = ws[(3 * kStreamers + w) * 16 + lane];
+        o.ib = __float_as_int(ws[(4 * kStreamers + w) * 16 + lane]);
+        s = stats_merge(s, o);
+      }
+      write_record(p, record_ptr(p, 0, l, blockIdx.x, lane), s);
     }
-    stamp(p, dbg_l, 11, lane);
-    const int q = lane >> 4;
-    // tile ids of all parked pieces in one LDS round trip, then scalar copies
-    const int my_pend = lane < kStreamers ? sm.pend_tile(par)[lane] : -1;
-    const int my_part = lane < kStreamers ? sm.part_tile(par)[lane] : -1;
-    int pend_t[kStreamers], part_t[kStreamers];
-#pragma unroll
-    for (int w = 0; w < kStreamers; ++w) {
-      pend_t[w] = __builtin_amdgcn_readlane(my_pend, w);
-      part_t[w] = __builtin_amdgcn_readlane(my_part, w);
-    }
-    // all piece slots in one go (slots without a piece hold stale data and are not used)
-    f32x4 pend_v[kStreamers], part_v[kStreamers];
-#pragma unroll
-    for (int w = 0; w < kStreamers; ++w) {
-      pend_v[w] = sm.pend(par)[w * kWave + lane];
-      part_v[w] = sm.part(par)[w * kWave + lane];
-    }
-#pragma unroll
-    for (int w = 0; w < kStreamers; ++w) {
-      const int t = pend_t[w];
-      if (t < 0) continue;
-      f32x4 z = pend_v[w];
-#pragma unroll
-      for (int w2 = w + 1; w2 < kStreamers; ++w2)  // later pieces of the same tile, in wave order
-        if (part_t[w2] == t) z += part_v[w2];
-      const int row0 = t * 16 + q * 4;
-      if (row0 >= sl.row_lo) stats_push4_any(s, z, row0, sl.row_hi);
-    }
-    stamp(p, dbg_l, 12, lane);
-    s = stats_merge(s, stats_shfl_xor(s, 16));
-    s = stats_merge(s, stats_shfl_xor(s, 32));
-    return s;
-  }
-
-  // record of workgroup g, row n, head l in exchange round `round` (0 or 1)
-  __device__ __forceinline__ unsigned long long* record(int round, int l, int g, int n) const {
-    return p.records + ((((long long)round * p.n_heads_alloc + l) * gridDim.x + g) * 16 + n) * 5;
-  }
-
-  __device__ __forceinline__ void write_record(unsigned long long* r, const Stats& s) const {
-    const unsigned long long tag = (unsigned long long)p.epoch << 32;
-    const unsigned w[5] = {__float_as_uint(s.m), __float_as_uint(s.S), __float_as_uint(s.U),
-                           __float_as_uint(s.zb), (unsigned)s.ib};
-#pragma unroll
-    for (int i = 0; i < 5; ++i)
-      __hip_atomic_store(r + i, tag | w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // A record as loaded: five {tag, payload} words.
@@ -502,17 +499,7 @@ struct Service {
     return true;
   }
 
-  // First half of what follows the streamers' work on head l: this workgroup's
-  // round-0 records go out.
-  __device__ __forceinline__ void announce(int l) {
-    stamp(p, l + 1, 9, lane);
-    dbg_l = l + 1;
-    const Stats mine = gather_wg(l & 1);
-    stamp(p, l + 1, 10, lane);
-    if (lane < 16 && ((live >> lane) & 1u)) write_record(record(0, l, blockIdx.x, lane), mine);
-  }
-
-  // Second half: a two-round all-gather with radix kRadix, then finalise and
+  // A two-round all-gather with radix kRadix, then finalise and
   // decide.  Round 0: the statistics of the workgroups of my group -> my round-1
   // record (identical for all members of a group).  Round 1: one member of every
   // group -> the statistics of the whole vocabulary.  A record is polled by at
@@ -532,7 +519,6 @@ struct Service {
   unsigned long long done0 = 0;
   unsigned done1 = 0, stay = 0;
   int c = 0, sent = 0;
-  int dbg_l = 0;
 
   __device__ __forceinline__ bool pass() {
     const int grid = gridDim.x, me = blockIdx.x;
@@ -552,7 +538,7 @@ struct Service {
       const int sh = (h & (kWindow - 1)) * 16;
       const unsigned todo = (h < sent) ? (live & ~(unsigned)((done0 >> sh) & 0xffffu)) : 0u;
       row0[k] = todo ? __ffs(todo) - 1 : -1;
-      if (row0[k] >= 0 && lane < gsize) x0[k] = load_record(record(0, h, g0 + lane, row0[k]));
+      if (row0[k] >= 0 && lane < gsize) x0[k] = load_record(record_ptr(p, 0, h, g0 + lane, row0[k]));
     }
     const int sc = (c & (kWindow - 1)) * 16;
     if (c < sent) {
@@ -561,7 +547,7 @@ struct Service {
       if (row1 >= 0 && lane < ngroups) {
         const int j = lane;
         const int src = j * kRadix + min(member, min(kRadix, grid - j * kRadix) - 1);
-        x1 = load_record(record(1, c, src, row1));
+        x1 = load_record(record_ptr(p, 1, c, src, row1));
       }
     }
 #pragma unroll
@@ -570,7 +556,7 @@ struct Service {
       const int h = c + k;
       Stats s;
       if (merge_round(x0[k], gsize, s)) {
-        if (lane == 0) write_record(record(1, h, me, row0[k]), s);
+        if (lane == 0) write_record(p, record_ptr(p, 1, h, me, row0[k]), s);
         done0 |= 1ull << ((h & (kWindow - 1)) * 16 + row0[k]);
       }
     }
@@ -730,6 +716,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(const DecodeParams 
       *sm.abort_flag(threadIdx.x) = 0;
       *sm.arrived(threadIdx.x) = 0;
     }
+    if (threadIdx.x == 2) *sm.sent_word() = 0;
+    if (threadIdx.x < 2 * kStreamers) sm.part_flag(0)[threadIdx.x] = 0;
   }
   lds_barrier();
   if (wave < kStreamers) {
