@@ -30,9 +30,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (see profiles/); None until measured for the current kernel.
-TRAFFIC = None
+# HBM traffic of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs scaled
+# by what the same counters read for a plain 1 GiB elementwise kernel (factors 2.0 and 1.0):
+# measured bytes per launch / algorithmic bytes per launch of the same launches
+# (profiles/c1_decode_persistent_kernel.md).  Reported as that ratio times this run's
+# algorithmic bytes per launch.
+TRAFFIC_RATIO_C1 = (1.9281e9 + 1.42e6) / 1.7635e9
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -45,6 +48,9 @@ def parse():
                     choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify"])
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per bench step (c1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of known size (1 GiB read + 1 GiB written each), "
+                         "to scale rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -87,6 +93,17 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(7)
+        dst = torch.empty(n, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        for _ in range(10):
+            torch.add(src, 1, out=dst)      # an elementwise kernel: reads n bytes, writes n bytes
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"kernel": "torch.add(uint8, 1) elementwise",
+                                               "bytes_read": n, "bytes_written": n, "copies": 10}}))
+        return
     w = G.CONFIGS[args.workload]
     t_setup = time.time()
     heads = G.make_heads(w, dev)
@@ -138,7 +155,8 @@ def main():
         bytes_per_launch = bytes_per_eval * evals / launches
         avg_s = ev_s / launches
         roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC,
+                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
+                "traffic": TRAFFIC_RATIO_C1 * bytes_per_launch,
                 "kernel": "eh::decode_kernel<DtBf16> (one launch = one decode step's cascade)",
                 "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch,
                 "launches": launches}
