@@ -188,6 +188,45 @@ def main():
                    "sample": f"first {done_steps} decode steps of the same workload "
                              f"({done_evals} evaluations, {cdt:.1f} s; fp64 numpy, weights pre-widened)"}
         B.eh_destroy(ctx)
+    elif args.workload == "c2_calib":
+        # every head on every token; one step = all 24 heads on 512 tokens
+        hid = G.make_hidden(w, heads, dev)
+        R = w.rows
+        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+        Hb = torch.zeros((w.n_heads, R), device=dev)
+        Lb = torch.zeros((w.n_heads, R), device=dev)
+        Ab = torch.zeros((w.n_heads, R), dtype=torch.int32, device=dev)
+
+        def step():
+            for l in range(w.n_heads):
+                B.eh_eval(ctx, l, hid.h[l], R, Hb[l], Lb[l], Ab[l])
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(args.steps):
+            step()
+        ev1.record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ev_s = ev0.elapsed_time(ev1) * 1e-3
+        evals = args.steps * w.n_heads * R
+        value = evals / dt
+        launches = args.steps * w.n_heads
+        flops_per_launch = 2.0 * w.d * w.V * R
+        avg_s = ev_s / launches
+        roof = {"bound": "mfma", "achieved": flops_per_launch / avg_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": flops_per_launch / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None, "kernel": "eh_eval (512 rows, 1 head)", "avg_launch_us": avg_s * 1e6,
+                "flops_per_launch": flops_per_launch, "launches": launches}
+        cfg = {"workload": "c2_calib: d=2048 V=50304 24 heads x 512 tokens bf16, all heads on all tokens"}
+        out.update(ms_per_step=dt / args.steps * 1e3)
+        cpu = None
+        B.eh_destroy(ctx)
     else:
         raise SystemExit("workload not wired into bench.py yet: " + args.workload)
 

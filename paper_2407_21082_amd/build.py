@@ -17,7 +17,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libeh.so")
-SOURCES = ["eh_api.hip", "eh_decode.hip"]
+SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -33,18 +33,48 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True) -> str:
-    cmd = [hipcc_path(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in proc.stdout.splitlines()
                     if "packed-fp32-ops' is not a recognized feature" not in l)
-    if verbose and out.strip():
-        print(out, flush=True)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
+    return out
+
+
+def build(verbose: bool = True) -> str:
+    """Compiles every translation unit for gfx950 (in parallel) and links libeh.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = hipcc_path()
+    objdir = os.path.join(PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc, *compile_flags, "-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+             os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    # The batched kernel waits for hand-counted loads; its device assembly is produced
+    # alongside (same flags) and checked for register hazards before anything is linked.
+    gemm_asm = os.path.join(objdir, "eh_gemm.s")
+    cmds.append([hipcc, *compile_flags, "-S", "--cuda-device-only", "-I", os.path.join(ROOT, "include"),
+                 "-I", CSRC, os.path.join(CSRC, "eh_gemm.hip"), "-o", gemm_asm])
+    with ThreadPoolExecutor(max_workers=min(4, len(cmds))) as ex:
+        outs = list(ex.map(lambda c: _run(c, verbose), cmds))
+    from . import check_gemm_asm
+    with open(gemm_asm) as f:
+        findings, n_kernels, n_loads = check_gemm_asm.check_asm(f.read())
+    if findings or n_kernels == 0:
+        if os.path.exists(LIB):
+            os.remove(LIB)
+        raise RuntimeError("eh_gemm.hip: unsafe code generated for the hand-counted loads "
+                           f"({n_kernels} kernels checked):\n" + "\n".join(findings[:10]))
+    if verbose:
+        print(f"check_gemm_asm: {n_kernels} kernels, {n_loads} hand-counted loads, no hazard", flush=True)
+    outs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objs, "-o", LIB], verbose))
+    text = "\n".join(o for o in outs if o.strip())
+    if verbose and text:
+        print(text, flush=True)
     return LIB
 
 

@@ -1,0 +1,206 @@
+"""Static check of the batched kernel's hand-counted loads in the compiled gfx950 assembly.
+
+`csrc/eh_gemm.hip` loads activation fragments with `global_load_dwordx4` instructions the
+compiler does not track (inline asm), and waits for them with `s_waitcnt vmcnt(N)` on a
+compile-time count of younger loads.  That is only sound if, in the generated code,
+
+  * no instruction reads or writes a destination register of such a load while the load
+    may still be in flight (a register handed out again too early lets the returning data
+    overwrite an address or an operand), and
+  * no path reaches the end of the program with such a load still in flight.
+
+This module proves both properties on the assembly text: for every `global_load_dwordx4`
+into VGPRs it walks every path of the kernel's control-flow graph forward from the load,
+counting vector-memory loads issued after it (loads return in order, so
+`s_waitcnt vmcnt(N)` guarantees the load has landed once at least N younger ones were
+issued), and reports any instruction that names one of the load's destination registers
+before such a wait.  The build runs it on every `gemm_stats_kernel` instantiation and
+fails on a finding, so a compiler or source change cannot silently bring the hazard back.
+
+    python -m paper_2407_21082_amd.check_gemm_asm file.s
+"""
+from __future__ import annotations
+
+import re
+import sys
+from collections import deque
+
+KERNEL_RE = re.compile(r"^(_Z\w*gemm_stats_kernel\w*):")
+LABEL_RE = re.compile(r"^(\.L\w+):")
+VREG_RE = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+UNTRACKED_RE = re.compile(r"^global_load_dwordx4\s+v\[(\d+):(\d+)\]\s*,")
+VMCNT_RE = re.compile(r"vmcnt\((\d+)\)")
+VMEM_RE = re.compile(r"^(global_|buffer_|flat_|scratch_)")
+# only loads are counted as "younger": a store may retire ahead of an older load
+VLOAD_RE = re.compile(r"^(global|buffer|flat|scratch)_load")
+LONG_BRANCH_RE = re.compile(r"\((\.L\w+)-\.Lpost_getpc\d+\)")
+
+
+def _vregs(text: str) -> set:
+    regs = set()
+    for m in VREG_RE.finditer(text):
+        if m.group(1) is not None:
+            regs.add(int(m.group(1)))
+        else:
+            regs.update(range(int(m.group(2)), int(m.group(3)) + 1))
+    return regs
+
+
+def split_kernels(asm: str) -> dict:
+    """name -> list of lines of each gemm_stats_kernel body."""
+    out, name, body = {}, None, []
+    for line in asm.split("\n"):
+        m = KERNEL_RE.match(line)
+        if m:
+            name, body = m.group(1), []
+            continue
+        if name is not None:
+            if line.startswith(".Lfunc_end"):
+                out[name] = body
+                name = None
+            else:
+                body.append(line)
+    return out
+
+
+class Program:
+    def __init__(self, lines):
+        self.ins = []        # instruction text (mnemonic + operands, comments stripped)
+        self.label_at = {}   # label -> index of the next instruction
+        for line in lines:
+            m = LABEL_RE.match(line)
+            if m:
+                self.label_at[m.group(1)] = len(self.ins)
+                continue
+            t = line.split(";")[0].strip()
+            if not t or t.startswith("."):
+                continue
+            self.ins.append(t)
+        n = len(self.ins)
+        self.succ = [None] * n
+        for i, t in enumerate(self.ins):
+            op = t.split()[0]
+            if op == "s_endpgm":
+                self.succ[i] = ()
+            elif op == "s_branch":
+                self.succ[i] = (self.label_at[t.split()[1]],)
+            elif op.startswith("s_cbranch"):
+                self.succ[i] = (self.label_at[t.split()[1]], i + 1)
+            elif op.startswith("s_setpc"):
+                # branch relaxation: s_getpc / s_add_u32 (.Ltarget-.Lpost_getpc) / s_addc / s_setpc
+                tgt = None
+                for j in range(i - 1, max(i - 6, -1), -1):
+                    m = LONG_BRANCH_RE.search(self.ins[j])
+                    if m:
+                        tgt = self.label_at[m.group(1)]
+                        break
+                if tgt is None:
+                    raise ValueError("indirect branch with unknown target: " + t)
+                self.succ[i] = (tgt,)
+            else:
+                self.succ[i] = (i + 1,) if i + 1 < n else ()
+
+
+def check_kernel(lines, max_report=5):
+    """Findings (strings) for one kernel body."""
+    prog = Program(lines)
+    ins = prog.ins
+    regs_of = [_vregs(t) for t in ins]
+    is_vmem = [bool(VLOAD_RE.match(t)) for t in ins]
+    wait_n = []
+    for t in ins:
+        m = VMCNT_RE.search(t) if t.startswith("s_waitcnt") else None
+        wait_n.append(int(m.group(1)) if m else None)
+    findings = []
+    n_loads = 0
+    for i, t in enumerate(ins):
+        m = UNTRACKED_RE.match(t)
+        if not m:
+            continue
+        n_loads += 1
+        dest = set(range(int(m.group(1)), int(m.group(2)) + 1))
+        seen = set()
+        todo = deque((s, 0) for s in prog.succ[i])
+        while todo:
+            pc, younger = todo.popleft()
+            if (pc, younger) in seen:
+                continue
+            seen.add((pc, younger))
+            if wait_n[pc] is not None and younger >= wait_n[pc]:
+                continue                      # landed on this path
+            if regs_of[pc] & dest:
+                findings.append(f"load #{i} `{t}`: `{ins[pc]}` (#{pc}) touches its destination "
+                                f"with only {younger} younger loads and no wait")
+                break
+            if ins[pc].startswith("s_endpgm"):
+                findings.append(f"load #{i} `{t}` still in flight at s_endpgm (#{pc})")
+                break
+            y2 = min(younger + 1, 64) if is_vmem[pc] else younger
+            for s in prog.succ[pc]:
+                todo.append((s, y2))
+        if len(findings) >= max_report:
+            break
+    return findings, n_loads
+
+
+NB_RE = re.compile(r"gemm_stats_kernelINS_\w+?ELi(\d+)ELb")
+
+
+def check_step_counts(name, lines, max_report=5):
+    """Every k-step must issue exactly 2 DMA loads and NB register loads and no other
+    vector-memory instruction: the waits count on it.  Checked on each stretch of code
+    between two step syncs (`s_waitcnt vmcnt(2+NB) lgkmcnt(0)` followed by `s_barrier`)."""
+    m = NB_RE.search(name)
+    if not m:
+        return ["cannot read NB from the kernel name"], 0
+    nb = int(m.group(1))
+    ins = Program(lines).ins
+    want = f"vmcnt({2 + nb})"
+    syncs = [i for i in range(1, len(ins))
+             if ins[i] == "s_barrier" and ins[i - 1].startswith("s_waitcnt") and want in ins[i - 1]]
+    findings = []
+    checked = 0
+    for a, b in zip(syncs, syncs[1:]):
+        seg = ins[a + 1:b]
+        if any(t.startswith("s_barrier") or t.startswith("s_endpgm") for t in seg):
+            continue                      # a pass boundary lies in between
+        dma = sum(t.startswith("global_load_lds_dwordx4") for t in seg)
+        reg = sum(bool(UNTRACKED_RE.match(t)) for t in seg)
+        other = [t for t in seg if VMEM_RE.match(t) and not t.startswith("global_load_lds_dwordx4")
+                 and not UNTRACKED_RE.match(t)]
+        checked += 1
+        if dma != 2 or reg != nb or other:
+            findings.append(f"k-step before sync #{b}: {dma} DMA loads, {reg} register loads "
+                            f"(want 2 and {nb}), other vector memory: {other[:2]}")
+            if len(findings) >= max_report:
+                break
+    if checked == 0:
+        findings.append("no k-step found between step syncs")
+    return findings, checked
+
+
+def check_asm(asm: str):
+    """(findings, kernels checked, loads checked) for every gemm_stats_kernel in the text."""
+    kernels = split_kernels(asm)
+    findings, loads = [], 0
+    for name, body in kernels.items():
+        f, n = check_kernel(body)
+        g, _ = check_step_counts(name, body)
+        loads += n
+        findings += [f"{name}: {x}" for x in f + g]
+    return findings, len(kernels), loads
+
+
+def main(argv):
+    if len(argv) != 2:
+        print(__doc__)
+        return 2
+    findings, nk, nl = check_asm(open(argv[1]).read())
+    for f in findings:
+        print("HAZARD", f)
+    print(f"check_gemm_asm: {nk} kernels, {nl} untracked loads, {len(findings)} findings")
+    return 1 if findings or nk == 0 else 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv))

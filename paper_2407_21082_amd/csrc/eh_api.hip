@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -104,12 +105,17 @@ eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const
       hipLaunchKernelGGL((ln_pack_kernel<DtF32>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
                          n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
   }
-  for (int nb0 = 0; nb0 < NBtot; nb0 += kMaxNB) {
-    const int nbc = std::min(kMaxNB, NBtot - nb0);
-    if (bf) launch_stream<DtBf16, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
-    else launch_stream<DtF32, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
+  int n_parts = kStreamGrid;
+  if (c->bias.empty() && c->use_gemm) {
+    EH_HIP(c, gemm_launch(c, head, n_rows_dev, n_rows, AO, &n_parts, s));
+  } else {
+    for (int nb0 = 0; nb0 < NBtot; nb0 += kMaxNB) {
+      const int nbc = std::min(kMaxNB, NBtot - nb0);
+      if (bf) launch_stream<DtBf16, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
+      else launch_stream<DtF32, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
+    }
   }
-  hipLaunchKernelGGL(finalize_kernel, dim3(n_rows), dim3(64), 0, s, c->partials, kStreamGrid, R_pad,
+  hipLaunchKernelGGL(finalize_kernel, dim3(n_rows), dim3(64), 0, s, c->partials, n_parts, R_pad,
                      n_rows_dev, n_rows, AO ? nullptr : H, AO ? nullptr : lse, argmax);
   EH_HIP(c, hipGetLastError());
   return EH_OK;
@@ -220,7 +226,9 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
         return bail(e, "copy bias");
     }
   }
-  const size_t y_frags = (size_t)(c->R_pad_max / 16 + kMaxNB) * c->KS * kWave;
+  // the kernels read whole groups of token blocks: up to kMaxNB (stream kernel) or 4 waves x 8
+  // blocks (batched kernel) starting inside the padded rows, so 32 zero blocks follow them
+  const size_t y_frags = (size_t)(c->R_pad_max / 16 + 32) * c->KS * kWave;
   if ((e = dev_alloc(c, &c->yf, y_frags)) != hipSuccess) return bail(e, "hipMalloc(y)");
   if ((e = hipMemset(c->yf, 0, y_frags * sizeof(frag_t))) != hipSuccess) return bail(e, "memset y");
   if ((e = dev_alloc(c, &c->partials, (size_t)kStreamGrid * c->R_pad_max)) != hipSuccess)
@@ -248,6 +256,13 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
       if ((e = hipMemcpy(c->d_bias, c->bias.data(), np * sizeof(void*), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "copy tables");
     }
     if ((e = decode_prepare(c)) != hipSuccess) return bail(e, "decode_prepare");
+    {
+      hipDeviceProp_t prop;
+      if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return bail(e, "device properties");
+      c->num_cu = prop.multiProcessorCount;
+      const char* env = getenv("EH_DISABLE_GEMM");   // diagnostics: force the simple streaming kernel
+      c->use_gemm = !(env && env[0] == '1');
+    }
     if (c->decode_grid > 0) {
       const size_t nrec = 2 * np * c->decode_grid * 16 * 5;
       if ((e = dev_alloc(c, &c->dec_records, nrec)) != hipSuccess) return bail(e, "hipMalloc(decode)");

@@ -14,6 +14,7 @@ struct eh_ctx {
   float eps = 1e-5f;
   int KS = 0, VT = 0, R_pad_max = 0;
   int num_cu = 0;
+  bool use_gemm = true;
   std::vector<eh::frag_t*> Wf;  // per head, fragment-major weights
   std::vector<float*> gamma, beta, bias;
   std::vector<float> tau;
@@ -75,6 +76,11 @@ struct DecodeParams {
 // Sets up the decode kernel for this context (grid, LDS size, function
 // attributes).  Leaves ctx->decode_grid = 0 if the shape does not fit.
 hipError_t decode_prepare(eh_ctx* ctx);
+// Enqueues the batched projection + statistics kernel for one head on the rows
+// already laid out in ctx->yf; per-workgroup partial statistics go to
+// ctx->partials[*n_parts][R_pad].  Heads with a bias vector are not supported.
+hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
+                       int* n_parts, hipStream_t s);
 // Enqueues the decode kernel.
 hipError_t decode_launch(const eh_ctx* ctx, const DecodeParams& p, hipStream_t s);
 
