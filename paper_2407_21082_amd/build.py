@@ -17,7 +17,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libeh.so")
-SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip"]
+SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip", "eh_gemm32.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -54,23 +54,26 @@ def build(verbose: bool = True) -> str:
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
     cmds = [[hipcc, *compile_flags, "-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
              os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
-    # The batched kernel waits for hand-counted loads; its device assembly is produced
+    # The batched kernels wait for hand-counted loads; their device assembly is produced
     # alongside (same flags) and checked for register hazards before anything is linked.
-    gemm_asm = os.path.join(objdir, "eh_gemm.s")
-    cmds.append([hipcc, *compile_flags, "-S", "--cuda-device-only", "-I", os.path.join(ROOT, "include"),
-                 "-I", CSRC, os.path.join(CSRC, "eh_gemm.hip"), "-o", gemm_asm])
-    with ThreadPoolExecutor(max_workers=min(4, len(cmds))) as ex:
+    checked = [s for s in SOURCES if s.startswith("eh_gemm")]
+    asms = [os.path.join(objdir, s.replace(".hip", ".s")) for s in checked]
+    cmds += [[hipcc, *compile_flags, "-S", "--cuda-device-only", "-I", os.path.join(ROOT, "include"),
+              "-I", CSRC, os.path.join(CSRC, s), "-o", a] for s, a in zip(checked, asms)]
+    with ThreadPoolExecutor(max_workers=min(6, len(cmds))) as ex:
         outs = list(ex.map(lambda c: _run(c, verbose), cmds))
     from . import check_gemm_asm
-    with open(gemm_asm) as f:
-        findings, n_kernels, n_loads = check_gemm_asm.check_asm(f.read())
-    if findings or n_kernels == 0:
-        if os.path.exists(LIB):
-            os.remove(LIB)
-        raise RuntimeError("eh_gemm.hip: unsafe code generated for the hand-counted loads "
-                           f"({n_kernels} kernels checked):\n" + "\n".join(findings[:10]))
-    if verbose:
-        print(f"check_gemm_asm: {n_kernels} kernels, {n_loads} hand-counted loads, no hazard", flush=True)
+    for src, path in zip(checked, asms):
+        with open(path) as f:
+            findings, n_kernels, n_loads = check_gemm_asm.check_asm(f.read())
+        if findings or n_kernels == 0:
+            if os.path.exists(LIB):
+                os.remove(LIB)
+            raise RuntimeError(f"{src}: unsafe code generated for the hand-counted loads "
+                               f"({n_kernels} kernels checked):\n" + "\n".join(findings[:10]))
+        if verbose:
+            print(f"check_gemm_asm {src}: {n_kernels} kernels, {n_loads} hand-counted loads, no hazard",
+                  flush=True)
     outs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objs, "-o", LIB], verbose))
     text = "\n".join(o for o in outs if o.strip())
     if verbose and text:

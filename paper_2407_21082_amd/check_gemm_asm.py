@@ -25,10 +25,10 @@ import re
 import sys
 from collections import deque
 
-KERNEL_RE = re.compile(r"^(_Z\w*gemm_stats_kernel\w*):")
+KERNEL_RE = re.compile(r"^(_Z\w*gemm(?:32)?_stats_kernel\w*):")
 LABEL_RE = re.compile(r"^(\.L\w+):")
 VREG_RE = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
-UNTRACKED_RE = re.compile(r"^global_load_dwordx4\s+v\[(\d+):(\d+)\]\s*,")
+UNTRACKED_RE = re.compile(r"^global_load_dwordx4\s+v\[(\d+):(\d+)\]\s*,")  # any addressing form
 VMCNT_RE = re.compile(r"vmcnt\((\d+)\)")
 VMEM_RE = re.compile(r"^(global_|buffer_|flat_|scratch_)")
 # only loads are counted as "younger": a store may retire ahead of an older load
@@ -143,24 +143,26 @@ def check_kernel(lines, max_report=5):
     return findings, n_loads
 
 
-NB_RE = re.compile(r"gemm_stats_kernelINS_\w+?ELi(\d+)ELb")
+STEP_SYNC_RE = re.compile(r"^s_waitcnt vmcnt\((\d+)\)(?: lgkmcnt\(0\))?$")
 
 
 def check_step_counts(name, lines, max_report=5):
-    """Every k-step must issue exactly 2 DMA loads and NB register loads and no other
-    vector-memory instruction: the waits count on it.  Checked on each stretch of code
-    between two step syncs (`s_waitcnt vmcnt(2+NB) lgkmcnt(0)` followed by `s_barrier`)."""
-    m = NB_RE.search(name)
-    if not m:
-        return ["cannot read NB from the kernel name"], 0
-    nb = int(m.group(1))
+    """The waits count on every k-step issuing the same loads.  A step sync is
+    `s_waitcnt vmcnt(N)` (N > 0, with or without lgkmcnt(0)) directly followed by `s_barrier`; N must be
+    DEPTH times the number of loads (DMA + register loads) issued between the previous
+    step sync and this one, and nothing else may use vector memory there.  DEPTH is the
+    number of k-steps a load may stay in flight beyond the next one: 1 for the 16x16
+    kernel (two activation register sets), 2 for the 32x32 kernel (three sets)."""
+    depth = 2 if "gemm32_stats_kernel" in name else 1
     ins = Program(lines).ins
-    want = f"vmcnt({2 + nb})"
-    syncs = [i for i in range(1, len(ins))
-             if ins[i] == "s_barrier" and ins[i - 1].startswith("s_waitcnt") and want in ins[i - 1]]
+    syncs = []
+    for i in range(1, len(ins)):
+        m = STEP_SYNC_RE.match(ins[i - 1])
+        if ins[i] == "s_barrier" and m and int(m.group(1)) > 0:
+            syncs.append((i, int(m.group(1))))
     findings = []
     checked = 0
-    for a, b in zip(syncs, syncs[1:]):
+    for (a, _), (b, n) in zip(syncs, syncs[1:]):
         seg = ins[a + 1:b]
         if any(t.startswith("s_barrier") or t.startswith("s_endpgm") for t in seg):
             continue                      # a pass boundary lies in between
@@ -168,10 +170,12 @@ def check_step_counts(name, lines, max_report=5):
         reg = sum(bool(UNTRACKED_RE.match(t)) for t in seg)
         other = [t for t in seg if VMEM_RE.match(t) and not t.startswith("global_load_lds_dwordx4")
                  and not UNTRACKED_RE.match(t)]
+        if dma + reg == 0 and not other:
+            continue                      # prologue: operands of step 0 fetched from LDS only
         checked += 1
-        if dma != 2 or reg != nb or other:
-            findings.append(f"k-step before sync #{b}: {dma} DMA loads, {reg} register loads "
-                            f"(want 2 and {nb}), other vector memory: {other[:2]}")
+        if depth * (dma + reg) != n or dma == 0 or reg == 0 or other:
+            findings.append(f"k-step before sync #{b}: {dma} DMA loads + {reg} register loads, wait "
+                            f"vmcnt({n}) (want {depth} x loads), other vector memory: {other[:2]}")
             if len(findings) >= max_report:
                 break
     if checked == 0:

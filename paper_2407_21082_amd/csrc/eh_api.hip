@@ -93,22 +93,31 @@ template <bool AO>
 eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const int* row_idx,
                    const int* n_rows_dev, int n_rows, float* H, float* lse, int* argmax,
                    hipStream_t s) {
-  const int R_pad = (n_rows + 15) & ~15;
-  const int NBtot = R_pad / 16;
   const bool bf = c->dtype == EH_BF16;
+  // heads without bias go to the batched kernels: bf16 in blocks of 32 rows
+  // (32x32x16 matrix instructions), f32 in blocks of 16
+  const bool batched = c->bias.empty() && c->use_gemm;
+  const int RB = (batched && bf) ? 32 : 16;
+  const int R_pad = (n_rows + RB - 1) / RB * RB;
   {
     dim3 g((R_pad + 3) / 4), b(256);
-    if (bf)
-      hipLaunchKernelGGL((ln_pack_kernel<DtBf16>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
+    if (bf && RB == 32)
+      hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
+                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
+    else if (bf)
+      hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 16>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
                          n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
     else
-      hipLaunchKernelGGL((ln_pack_kernel<DtF32>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
+      hipLaunchKernelGGL((ln_pack_kernel<DtF32, 16>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
                          n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
   }
   int n_parts = kStreamGrid;
-  if (c->bias.empty() && c->use_gemm) {
+  if (batched && bf) {
+    EH_HIP(c, gemm32_launch(c, head, n_rows_dev, n_rows, AO, &n_parts, s));
+  } else if (batched) {
     EH_HIP(c, gemm_launch(c, head, n_rows_dev, n_rows, AO, &n_parts, s));
   } else {
+    const int NBtot = R_pad / 16;
     for (int nb0 = 0; nb0 < NBtot; nb0 += kMaxNB) {
       const int nbc = std::min(kMaxNB, NBtot - nb0);
       if (bf) launch_stream<DtBf16, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
@@ -188,7 +197,7 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
   c->dtype = cfg->w_dtype; c->device = cfg->device; c->eps = cfg->ln_eps;
   c->KS = (cfg->d + kpf - 1) / kpf;
   c->VT = (cfg->V + 15) / 16;
-  c->R_pad_max = (cfg->max_rows + 15) & ~15;
+  c->R_pad_max = (cfg->max_rows + 31) & ~31;
   c->tau.assign(cfg->tau, cfg->tau + cfg->n_heads);
 
   DeviceGuard guard(c->device);

@@ -246,13 +246,9 @@ hipError_t gemm_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_r
   dim3 g(gx, groups);
   *n_parts = gx;
   const frag_t* Wf = c->Wf[head];
-  if (c->dtype == EH_BF16) {
-    if (argmax_only) launch_nb<DtBf16, true>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
-    else launch_nb<DtBf16, false>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
-  } else {
-    if (argmax_only) launch_nb<DtF32, true>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
-    else launch_nb<DtF32, false>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
-  }
+  if (c->dtype != EH_F32) return hipErrorInvalidValue;  // bf16 has its own kernel (32x32x16 instructions)
+  if (argmax_only) launch_nb<DtF32, true>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+  else launch_nb<DtF32, false>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
   return hipGetLastError();
 }
 

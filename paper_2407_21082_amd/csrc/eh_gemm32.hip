@@ -1,0 +1,329 @@
+// Batched projection with fused softmax statistics for many rows, bf16 (arXiv
+// 2407.21082, Sections 3.2 and 3.4.1: every head on every token of a calibration
+// batch, Section 3.4.1 "Calibration of Confidence Thresholds"; the same kernel
+// serves the large row counts of the dynamic-exit cascade, Section 3.4.2).
+//
+// This is the compute-bound shape (512 rows x 50304 logits x d = 2048: about 500
+// flop per byte of weights), so the kernel is organised around matrix-core
+// throughput:
+//
+//  * v_mfma_f32_32x32x16_bf16: one wave per SIMD issues these back to back at the
+//    full rate of the matrix core (the 16x16x32 form needs two waves per SIMD for
+//    that, which would halve the accumulator tile a wave can hold);
+//  * one workgroup of 4 waves per CU.  The workgroup owns a contiguous slice of
+//    the vocabulary, walked in passes of at most 7 tiles of 32 rows, and a group
+//    of 4*NB blocks of 32 tokens; a wave owns NB token blocks and all tiles of
+//    the pass: up to 7*2 accumulator tiles = 224 registers;
+//  * the weights stay in the layout the decode kernel uses (fragments of 16 rows
+//    x 32 k).  They travel global -> LDS by DMA loads, once per workgroup, four
+//    k-steps ahead, and the LDS read applies the lane permutation that turns two
+//    16-row fragments into the two 32-row x 16-k operands of a k-step, so no
+//    second copy of the weights is needed.  A weight operand is re-read for the
+//    next k-step right after its last matrix instruction of this one;
+//  * the activations (L2 resident, private to a wave) are written by the
+//    LayerNorm kernel directly in 32x16 operand order and loaded straight into
+//    registers three k-steps ahead, into the registers just freed;
+//  * every wave issues the same, compile-time number of loads per k-step in
+//    program order, so "what the next step needs has landed" is a wait on a
+//    count, followed by the one barrier per k-step that publishes the weights;
+//  * at the end of a pass the accumulator tiles are folded into per-lane running
+//    statistics (one exponential per logit); logits are never stored.
+#include "eh_internal.hpp"
+#include "eh_kernels.hpp"
+
+namespace eh {
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kG32Waves = 4;
+constexpr int kG32Threads = kG32Waves * kWave;
+constexpr int kMaxMT = 7;     // 32-row tiles per pass
+constexpr int kSlots = 8;     // LDS ring: k-steps of weight fragments (a slot is rewritten 7 steps after its last read)
+constexpr int kSlotBytes = 2 * kMaxMT * 1024;
+constexpr int kDepth = 3;     // activation register sets = k-steps a load may take
+__host__ __device__ constexpr size_t g32_lds_bytes() { return (size_t)kSlots * kSlotBytes; }
+
+#define EH_LDS __attribute__((address_space(3)))
+#define EH_GLOBAL __attribute__((address_space(1)))
+typedef EH_LDS frag_t lds_frag_t;
+
+// A 16-byte global load the compiler does not track: the kernel keeps its own
+// count of loads in flight (see pass32), so the register must not be read
+// before the matching wait.  The build checks the generated code for that.
+// Address = wave-uniform base (scalar registers) + per-lane byte offset + IMM.
+template <int IMM>
+__device__ __forceinline__ void load_untracked(frag_t& dst, const EH_GLOBAL char* base, uint32_t lane_off) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(lane_off), "s"(base), "n"(IMM) : "memory");
+}
+
+// Makes the compiler keep a wave-uniform pointer in scalar registers.
+__device__ __forceinline__ const EH_GLOBAL char* uniform_ptr(const void* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const EH_GLOBAL char*)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ f32x16 mma32(const frag_t& a, const frag_t& b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// DMA loads a wave issues per k-step: the 2*MT fragments of a step are dealt
+// round-robin to the four waves; a wave with fewer real fragments repeats its
+// last one (same bytes to the same place) so that all waves count alike.
+__host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Waves - 1) / kG32Waves; }
+
+// One pass: MT tiles of 32 vocabulary rows starting at tile T, all of k, this
+// wave's NB blocks of 32 tokens.
+//
+// k-step s (32 values of k) uses, per tile m, the operands a[m][0], a[m][1] (the
+// two 16-k halves, 32 rows each) and, per token block n, b[s % 3][n][0..1].
+// Schedule, with SYNC(s) at the start of step s:
+//   SYNC(s):  wait until my loads up to B(s) and DMA(s+1) have landed; barrier;
+//             issue DMA(s+4).  Its ring slot (8 slots) was last read during step
+//             s-5 and those reads fed matrix instructions of step s-4, so nobody
+//             is reading it and the sync need not wait for LDS reads at all.
+//   step s:   for each tile m: its 2*NB matrix instructions, then a[m] <- LDS
+//             slot of step s+1; after the last tile's use of b[n][h], that
+//             register is reloaded with B(s+3).
+// Loads return in order, so at SYNC(s+1) the loads that may still be in flight
+// are exactly the last two groups issued: DMA(s+3)+B(s+2)... counted below.
+template <int MT, int NB, bool ARGMAX_ONLY>
+__device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq,
+                                       int T, int VT16, int KS, int V, int lane, int wave,
+                                       EH_LDS char* lds, Stats (&st)[NB]) {
+  constexpr int kDma = dma_per_wave(MT);
+  constexpr int kGroup = kDma + 2 * NB;            // loads a wave issues per k-step
+  constexpr int kInFlight = (kDepth - 1) * kGroup;  // younger than what SYNC needs
+  static_assert(kInFlight < 64, "vmcnt field");
+  constexpr int NF = 2 * MT;  // 16-row fragments per k-step
+
+  f32x16 acc[MT][NB];
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int n = 0; n < NB; ++n)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
+
+  const int lastk = KS - 1;
+  const uint32_t lane16 = (uint32_t)lane << 4;  // byte offset of a lane inside a fragment
+  // DMA sources of this wave: fragment f = wave + 4*i of the step (or a repeat);
+  // wave-uniform byte offsets of (tile, k = 0) from the start of the weights
+  const EH_GLOBAL char* wbase = uniform_ptr(Wf);
+  long long wsrc[kDma];
+  int wdst[kDma];
+#pragma unroll
+  for (int i = 0; i < kDma; ++i) {
+    int f = wave + kG32Waves * i;
+    if (f >= NF) f = (wave < NF) ? wave + kG32Waves * ((NF - 1 - wave) / kG32Waves) : NF - 1;
+    const int t16 = min(2 * T + f, VT16 - 1);  // a missing odd half tile repeats the last one (masked later)
+    wsrc[i] = ((long long)t16 * KS) << 10;
+    wdst[i] = f * 1024;
+  }
+  auto dma = [&](int ks) {  // weight fragments of k-step ks into their ring slot
+    const int k = min(ks, lastk);
+    EH_LDS char* slot = lds + (ks & (kSlots - 1)) * kSlotBytes;
+#pragma unroll
+    for (int i = 0; i < kDma; ++i)
+      __builtin_amdgcn_global_load_lds((const EH_GLOBAL void*)(wbase + wsrc[i] + ((long long)k << 10) + lane16),
+                                       (EH_LDS void*)(slot + wdst[i]), 16, 0, 0);
+  };
+  // activations: block n, k-step ks, half h -> fragment (n, 2*ks + h) of 2*KS per block
+  const EH_GLOBAL char* ybase = uniform_ptr(yq);
+  auto load_b = [&](frag_t (&dst)[2], int n, int ks) {
+    const EH_GLOBAL char* p = ybase + (((long long)n * 2 * KS + 2 * min(ks, lastk)) << 10);
+    load_untracked<0>(dst[0], p, lane16);
+    load_untracked<1024>(dst[1], p, lane16);
+  };
+  // LDS read with the 16x32 -> 32x16 lane permutation: lane l takes row l%32 and
+  // k group 2h + l/32, i.e. lane (2h + l/32)*16 + l%16 of fragment (l%32)/16.
+  const int laneoff = ((lane & 31) >> 4) * 1024 + (((lane >> 5) * 16 + (lane & 15)) << 4);
+  auto fetch_a = [&](frag_t (&a)[2], int m, int ks) {
+    EH_LDS const char* p = lds + (ks & (kSlots - 1)) * kSlotBytes + laneoff + m * 2048;
+    a[0] = *(const lds_frag_t*)(p);
+    a[1] = *(const lds_frag_t*)(p + 512);
+  };
+
+  frag_t a[MT][2];
+  frag_t b0[NB][2], b1[NB][2], b2[NB][2];
+  // one k-step on register set b (holding B(ks)); refills a for ks+1 and b with B(ks+3)
+  auto step = [&](frag_t (&b)[NB][2], int ks) {
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) acc[m][n] = mma32(a[m][h], b[n][h], acc[m][n]);
+        if (m == MT - 1) load_b(b[n], n, ks + kDepth);
+      }
+      fetch_a(a[m], m, ks + 1);
+    }
+  };
+#define EH_SYNC(bset, s_)                                                                          \
+  do {                                                                                             \
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kInFlight) : "memory");                  \
+    _Pragma("unroll") for (int n_ = 0; n_ < NB; ++n_) {                                            \
+      asm volatile("" : "+v"(bset[n_][0]));                                                        \
+      asm volatile("" : "+v"(bset[n_][1]));                                                        \
+    }                                                                                              \
+    dma((s_) + 4);                                                                                 \
+  } while (0)
+
+  // nobody may still be reading the ring (previous pass) when it is refilled
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  // Prologue.  Issue order: DMA(0) DMA(1) | B(0) DMA(2) | B(1) DMA(3) | B(2)
+  dma(0);
+  dma(1);
+#pragma unroll
+  for (int n = 0; n < NB; ++n) load_b(b0[n], n, 0);
+  dma(2);
+#pragma unroll
+  for (int n = 0; n < NB; ++n) load_b(b1[n], n, 1);
+  dma(3);
+#pragma unroll
+  for (int n = 0; n < NB; ++n) load_b(b2[n], n, 2);
+  // DMA(0) landed everywhere (younger: B(0) DMA(2) B(1) DMA(3) B(2)), then a <- slot 0
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kGroup + 2 * NB + kDma) : "memory");
+#pragma unroll
+  for (int m = 0; m < MT; ++m) fetch_a(a[m], m, 0);
+  // From here every SYNC(s) sees, younger than B(s) and DMA(s+1):
+  //   [B(s+1) DMA(s+3)] [B(s+2)]  at s = 0 (DMA(4) not yet issued: one group less kDma, so the
+  //   wait is only stricter), and [DMA(s+3) B(s+1)... in steady state two whole groups.
+  int ks = 0;
+  for (; ks + 2 < KS; ks += 3) {
+    EH_SYNC(b0, ks);
+    step(b0, ks);
+    EH_SYNC(b1, ks + 1);
+    step(b1, ks + 1);
+    EH_SYNC(b2, ks + 2);
+    step(b2, ks + 2);
+  }
+  if (ks < KS) {
+    EH_SYNC(b0, ks);
+    step(b0, ks);
+    if (ks + 1 < KS) {
+      EH_SYNC(b1, ks + 1);
+      step(b1, ks + 1);
+    }
+  }
+#undef EH_SYNC
+  // The loads issued past the end (clamped) still write their registers: wait for
+  // them, and keep every destination register reserved until here, or the
+  // compiler would hand it out again while a load is still on its way to it.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int n = 0; n < NB; ++n)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) asm volatile("" ::"v"(b0[n][h]), "v"(b1[n][h]), "v"(b2[n][h]));
+
+  // accumulator register 4g+i of lane l: vocabulary row 32*tile + 8g + 4*(l/32) + i, token l%32
+  const int half = lane >> 5;
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int row0 = (T + m) * 32 + g * 8 + half * 4;
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        const f32x4 z = {acc[m][n][4 * g], acc[m][n][4 * g + 1], acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]};
+        stats_push4<ARGMAX_ONLY>(st[n], z, row0, V);
+      }
+      // keep the instruction scheduler from pulling all accumulators into
+      // vector registers at once (it would spill inside the k loop's tail)
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// grid.x = workgroups over the vocabulary, grid.y = groups of 4*NB blocks of 32 tokens
+template <int NB, bool ARGMAX_ONLY>
+__global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
+    const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq, int VT16, int KS, int V,
+    const int* __restrict__ n_rows_dev, int n_rows, int R_pad, Stats* __restrict__ partials) {
+  extern __shared__ __attribute__((aligned(16))) char g32_smem[];
+  EH_LDS char* lds = (EH_LDS char*)g32_smem;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int n_live = n_rows;
+  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  const int live_blocks = (n_live + 31) >> 5;
+  // the whole workgroup leaves if its token group is empty (the waves share
+  // barriers, so a single wave must not leave on its own; waves beyond the live
+  // rows compute on zero or stale activation fragments and write nothing)
+  if (live_blocks - (int)(blockIdx.y * kG32Waves * NB) <= 0) return;
+  const int nb_first = (blockIdx.y * kG32Waves + wave) * NB;  // my first token block
+  const int nb_live = min(NB, live_blocks - nb_first);
+  const int VT32 = (VT16 + 1) >> 1;
+  const int T0 = (int)((long long)VT32 * blockIdx.x / gridDim.x);
+  const int T1 = (int)((long long)VT32 * (blockIdx.x + 1) / gridDim.x);
+  Stats st[NB];
+#pragma unroll
+  for (int n = 0; n < NB; ++n) stats_init(st[n]);
+  const frag_t* ybase = yq + (long long)nb_first * 2 * KS * kWave;
+  for (int t = T0; t < T1;) {
+    const int left = T1 - t;
+    // split what is left into passes of at most kMaxMT tiles of about equal size
+    const int passes = (left + kMaxMT - 1) / kMaxMT;
+    const int mt = (left + passes - 1) / passes;
+    switch (mt) {
+      case 7: pass32<7, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 6: pass32<6, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 5: pass32<5, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 4: pass32<4, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 3: pass32<3, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 2: pass32<2, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      default: pass32<1, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+    }
+    t += mt;
+  }
+  // lanes l and l+32 hold the same token: fold the two row groups
+#pragma unroll
+  for (int n = 0; n < NB; ++n) {
+    st[n] = stats_merge(st[n], stats_shfl_xor(st[n], 32));
+    if (lane < 32 && n < nb_live)
+      partials[(long long)blockIdx.x * R_pad + (nb_first + n) * 32 + lane] = st[n];
+  }
+}
+
+template <int NB, bool AO>
+void launch32(dim3 g, hipStream_t s, const frag_t* Wf, const frag_t* yq, int VT16, int KS, int V,
+              const int* n_rows_dev, int n_rows, int R_pad, Stats* partials) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)gemm32_stats_kernel<NB, AO>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)g32_lds_bytes());
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm32_stats_kernel<NB, AO>), g, dim3(kG32Threads), g32_lds_bytes(), s, Wf, yq,
+                     VT16, KS, V, n_rows_dev, n_rows, R_pad, partials);
+}
+
+}  // namespace
+
+hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
+                         int* n_parts, hipStream_t s) {
+  const int R_pad = (n_rows + 31) & ~31;
+  const int blocks = R_pad / 32;
+  const int nb = blocks <= kG32Waves ? 1 : 2;
+  const int groups = (blocks + kG32Waves * nb - 1) / (kG32Waves * nb);
+  const int cus = c->num_cu > 0 ? c->num_cu : 256;
+  const int VT32 = (c->VT + 1) / 2;
+  const int gx = std::max(1, std::min(VT32, cus / groups));
+  dim3 g(gx, groups);
+  *n_parts = gx;
+  const frag_t* Wf = c->Wf[head];
+  if (nb == 1) {
+    if (argmax_only) launch32<1, true>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+    else launch32<1, false>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+  } else {
+    if (argmax_only) launch32<2, true>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+    else launch32<2, false>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace eh

@@ -81,6 +81,10 @@ hipError_t decode_prepare(eh_ctx* ctx);
 // ctx->partials[*n_parts][R_pad].  Heads with a bias vector are not supported.
 hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
                        int* n_parts, hipStream_t s);
+// Same for bf16 with blocks of 32 rows: ctx->yf must hold the rows in the 32 x 16
+// operand order (ln_pack_kernel<DtBf16, 32>), partials are [*n_parts][n_rows rounded up to 32].
+hipError_t gemm32_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
+                         int* n_parts, hipStream_t s);
 // Enqueues the decode kernel.
 hipError_t decode_launch(const eh_ctx* ctx, const DecodeParams& p, hipStream_t s);
 

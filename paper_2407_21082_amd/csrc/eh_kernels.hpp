@@ -123,7 +123,12 @@ __device__ __forceinline__ void wave_layernorm(const void* row, int d, int n_chu
   }
 }
 
-template <typename DT>
+// RB = rows per activation block: 16 (fragments of 16 rows x KPF k, the operand
+// order of the 16x16 matrix instructions) or 32 (bf16 only: fragments of 32 rows
+// x 16 k for v_mfma_f32_32x32x16_bf16; lane l of fragment (block, k16) holds row
+// l%32, k = 16*k16 + 8*(l/32) .. +8).  R_pad is a multiple of RB; rows between
+// the live rows and R_pad are zero-filled.
+template <typename DT, int RB>
 __global__ __launch_bounds__(256) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
                                                       const int* __restrict__ row_idx,
                                                       const int* __restrict__ n_rows_dev, int n_rows,
@@ -131,15 +136,20 @@ __global__ __launch_bounds__(256) void ln_pack_kernel(const void* __restrict__ h
                                                       const float* __restrict__ gamma,
                                                       const float* __restrict__ beta, float eps,
                                                       frag_t* __restrict__ yf) {
+  static_assert(RB == 16 || (RB == 32 && DT::EPL == 8), "row block");
   const int lane = threadIdx.x & 63;
   const int p = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (p >= R_pad) return;
   int n_live = n_rows;
   if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
-  const int nb = p >> 4, n = p & 15;
+  const int nb = p / RB, n = p % RB;
   const int n_chunks = KS * 4;
-  frag_t* dst = yf + (int64_t)nb * KS * kWave;
-  auto put = [&](int c, const frag_t& v) { dst[(c >> 2) * kWave + (c & 3) * 16 + n] = v; };
+  // a block holds KS*4 chunks of 16 bytes per row either way
+  frag_t* dst = yf + (int64_t)nb * KS * kWave * (RB / 16);
+  auto put = [&](int c, const frag_t& v) {
+    if (RB == 16) dst[(c >> 2) * kWave + (c & 3) * 16 + n] = v;
+    else dst[(c >> 1) * kWave + (c & 1) * 32 + n] = v;
+  };
   if (p >= n_live) {
     for (int c = lane; c < n_chunks; c += kWave) put(c, mk_frag(0, 0, 0, 0));
     return;
