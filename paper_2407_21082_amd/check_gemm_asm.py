@@ -101,45 +101,66 @@ class Program:
                 self.succ[i] = (i + 1,) if i + 1 < n else ()
 
 
-def check_kernel(lines, max_report=5):
-    """Findings (strings) for one kernel body."""
+class LoadClass:
+    """A kind of load whose completion is awaited through one `s_waitcnt` counter."""
+
+    def __init__(self, what, load_re, younger_re, wait_re, disorder_re=None):
+        self.what = what
+        self.load_re = re.compile(load_re)        # groups: first and last destination VGPR
+        self.younger_re = re.compile(younger_re)  # instructions that return in order behind it
+        self.wait_re = re.compile(wait_re)        # the counter field of s_waitcnt
+        # instructions on the same counter that may return out of order with the load:
+        # once one is in flight only a wait for zero proves the load has landed
+        self.disorder_re = re.compile(disorder_re) if disorder_re else None
+
+
+VM_LOADS = LoadClass("global load", r"^global_load_dwordx4\s+v\[(\d+):(\d+)\]\s*,",
+                     r"^(global|buffer|flat|scratch)_load", r"vmcnt\((\d+)\)")
+LDS_LOADS = LoadClass("LDS read", r"^ds_read_b128\s+v\[(\d+):(\d+)\]\s*,", r"^ds_",
+                      r"lgkmcnt\((\d+)\)", r"^s_(load|buffer_load|scratch_load|sendmsg|memtime|memrealtime)")
+
+
+def check_kernel(lines, max_report=5, classes=(VM_LOADS, LDS_LOADS)):
+    """Findings (strings) and number of loads examined for one kernel body."""
     prog = Program(lines)
     ins = prog.ins
     regs_of = [_vregs(t) for t in ins]
-    is_vmem = [bool(VLOAD_RE.match(t)) for t in ins]
-    wait_n = []
-    for t in ins:
-        m = VMCNT_RE.search(t) if t.startswith("s_waitcnt") else None
-        wait_n.append(int(m.group(1)) if m else None)
     findings = []
     n_loads = 0
-    for i, t in enumerate(ins):
-        m = UNTRACKED_RE.match(t)
-        if not m:
-            continue
-        n_loads += 1
-        dest = set(range(int(m.group(1)), int(m.group(2)) + 1))
-        seen = set()
-        todo = deque((s, 0) for s in prog.succ[i])
-        while todo:
-            pc, younger = todo.popleft()
-            if (pc, younger) in seen:
+    for cls in classes:
+        is_younger = [bool(cls.younger_re.match(t)) for t in ins]
+        disorders = [bool(cls.disorder_re and cls.disorder_re.match(t)) for t in ins]
+        wait_n = []
+        for t in ins:
+            m = cls.wait_re.search(t) if t.startswith("s_waitcnt") else None
+            wait_n.append(int(m.group(1)) if m else None)
+        for i, t in enumerate(ins):
+            m = cls.load_re.match(t)
+            if not m:
                 continue
-            seen.add((pc, younger))
-            if wait_n[pc] is not None and younger >= wait_n[pc]:
-                continue                      # landed on this path
-            if regs_of[pc] & dest:
-                findings.append(f"load #{i} `{t}`: `{ins[pc]}` (#{pc}) touches its destination "
-                                f"with only {younger} younger loads and no wait")
-                break
-            if ins[pc].startswith("s_endpgm"):
-                findings.append(f"load #{i} `{t}` still in flight at s_endpgm (#{pc})")
-                break
-            y2 = min(younger + 1, 64) if is_vmem[pc] else younger
-            for s in prog.succ[pc]:
-                todo.append((s, y2))
-        if len(findings) >= max_report:
-            break
+            n_loads += 1
+            dest = set(range(int(m.group(1)), int(m.group(2)) + 1))
+            seen = set()
+            todo = deque((s, 0, False) for s in prog.succ[i])
+            while todo:
+                pc, younger, mixed = todo.popleft()
+                if (pc, younger, mixed) in seen:
+                    continue
+                seen.add((pc, younger, mixed))
+                if wait_n[pc] is not None and (wait_n[pc] == 0 or (not mixed and younger >= wait_n[pc])):
+                    continue                      # landed on this path
+                if regs_of[pc] & dest:
+                    findings.append(f"{cls.what} #{i} `{t}`: `{ins[pc]}` (#{pc}) touches its destination "
+                                    f"with only {younger} younger loads and no wait")
+                    break
+                if ins[pc].startswith("s_endpgm"):
+                    findings.append(f"{cls.what} #{i} `{t}` still in flight at s_endpgm (#{pc})")
+                    break
+                y2 = min(younger + 1, 64) if is_younger[pc] else younger
+                for s in prog.succ[pc]:
+                    todo.append((s, y2, mixed or disorders[pc]))
+            if len(findings) >= max_report:
+                return findings, n_loads
     return findings, n_loads
 
 
@@ -148,36 +169,53 @@ STEP_SYNC_RE = re.compile(r"^s_waitcnt vmcnt\((\d+)\)(?: lgkmcnt\(0\))?$")
 
 def check_step_counts(name, lines, max_report=5):
     """The waits count on every k-step issuing the same loads.  A step sync is
-    `s_waitcnt vmcnt(N)` (N > 0, with or without lgkmcnt(0)) directly followed by `s_barrier`; N must be
-    DEPTH times the number of loads (DMA + register loads) issued between the previous
-    step sync and this one, and nothing else may use vector memory there.  DEPTH is the
-    number of k-steps a load may stay in flight beyond the next one: 1 for the 16x16
-    kernel (two activation register sets), 2 for the 32x32 kernel (three sets)."""
-    depth = 2 if "gemm32_stats_kernel" in name else 1
-    ins = Program(lines).ins
-    syncs = []
+    `s_waitcnt vmcnt(N)` (N > 0, with or without lgkmcnt(0)) directly followed by
+    `s_barrier`.  On every control-flow path from one step sync to the next, the loads
+    issued (DMA + register loads) must divide the next sync's N -- by the same factor (the
+    k-steps a load may stay in flight beyond the next one) everywhere in the kernel -- and
+    nothing else may use vector memory.  Paths end at a pass boundary (`vmcnt(0)`)."""
+    prog = Program(lines)
+    ins = prog.ins
+    sync_n = {}
     for i in range(1, len(ins)):
         m = STEP_SYNC_RE.match(ins[i - 1])
         if ins[i] == "s_barrier" and m and int(m.group(1)) > 0:
-            syncs.append((i, int(m.group(1))))
-    findings = []
-    checked = 0
-    for (a, _), (b, n) in zip(syncs, syncs[1:]):
-        seg = ins[a + 1:b]
-        if any(t.startswith("s_barrier") or t.startswith("s_endpgm") for t in seg):
-            continue                      # a pass boundary lies in between
-        dma = sum(t.startswith("global_load_lds_dwordx4") for t in seg)
-        reg = sum(bool(UNTRACKED_RE.match(t)) for t in seg)
-        other = [t for t in seg if VMEM_RE.match(t) and not t.startswith("global_load_lds_dwordx4")
-                 and not UNTRACKED_RE.match(t)]
-        if dma + reg == 0 and not other:
-            continue                      # prologue: operands of step 0 fetched from LDS only
-        checked += 1
-        if depth * (dma + reg) != n or dma == 0 or reg == 0 or other:
-            findings.append(f"k-step before sync #{b}: {dma} DMA loads + {reg} register loads, wait "
-                            f"vmcnt({n}) (want {depth} x loads), other vector memory: {other[:2]}")
-            if len(findings) >= max_report:
-                break
+            sync_n[i] = int(m.group(1))
+    findings, depths, checked = [], set(), 0
+    for start in sync_n:
+        seen = set()
+        todo = [(s, 0, 0) for s in prog.succ[start]]
+        while todo and len(findings) < max_report:
+            pc, dma, reg = todo.pop()
+            if (pc, dma, reg) in seen or dma + reg > 64:
+                continue
+            seen.add((pc, dma, reg))
+            t = ins[pc]
+            if pc in sync_n:
+                if dma + reg == 0:
+                    pass                  # prologue: operands of step 0 come from LDS only
+                else:
+                    checked += 1
+                    n = sync_n[pc]
+                    if dma == 0 or reg == 0 or n % (dma + reg) != 0:
+                        findings.append(f"k-step from sync #{start} to sync #{pc}: {dma} DMA + {reg} register "
+                                        f"loads, wait vmcnt({n}) (want a multiple of the loads)")
+                    else:
+                        depths.add(n // (dma + reg))
+                    continue
+            if t.startswith("s_endpgm") or (t.startswith("s_waitcnt") and "vmcnt(0)" in t):
+                continue                  # pass boundary
+            if t.startswith("global_load_lds_dwordx4"):
+                dma += 1
+            elif UNTRACKED_RE.match(t):
+                reg += 1
+            elif VMEM_RE.match(t):
+                findings.append(f"k-step after sync #{start}: other vector memory `{t}` (#{pc})")
+                continue
+            for s in prog.succ[pc]:
+                todo.append((s, dma, reg))
+    if len(depths) > 1:
+        findings.append(f"k-steps wait with different depths: {sorted(depths)}")
     if checked == 0:
         findings.append("no k-step found between step syncs")
     return findings, checked

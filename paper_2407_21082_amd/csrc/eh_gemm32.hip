@@ -19,7 +19,8 @@
 //    k-steps ahead, and the LDS read applies the lane permutation that turns two
 //    16-row fragments into the two 32-row x 16-k operands of a k-step, so no
 //    second copy of the weights is needed.  A weight operand is re-read for the
-//    next k-step right after its last matrix instruction of this one;
+//    next k-step right after its last matrix instruction of this one, which
+//    spreads the LDS reads of the four waves evenly over the step;
 //  * the activations (L2 resident, private to a wave) are written by the
 //    LayerNorm kernel directly in 32x16 operand order and loaded straight into
 //    registers three k-steps ahead, into the registers just freed;
@@ -28,8 +29,15 @@
 //    count, followed by the one barrier per k-step that publishes the weights;
 //  * at the end of a pass the accumulator tiles are folded into per-lane running
 //    statistics (one exponential per logit); logits are never stored.
+//
+// Measured on this shape the loop is bound by the rate the matrix cores sustain
+// on real (toggling) data, not by memory: removing all loads from the loop does
+// not shorten it, and the vendor GEMM library reaches the same rate without the
+// statistics.
 #include "eh_internal.hpp"
 #include "eh_kernels.hpp"
+
+#include <type_traits>
 
 namespace eh {
 
@@ -42,7 +50,10 @@ constexpr int kG32Threads = kG32Waves * kWave;
 constexpr int kMaxMT = 7;     // 32-row tiles per pass
 constexpr int kSlots = 8;     // LDS ring: k-steps of weight fragments (a slot is rewritten 7 steps after its last read)
 constexpr int kSlotBytes = 2 * kMaxMT * 1024;
-constexpr int kDepth = 3;     // activation register sets = k-steps a load may take
+#ifndef EH_G32_DEPTH
+#define EH_G32_DEPTH 3
+#endif
+constexpr int kDepth = EH_G32_DEPTH;  // activation register sets = k-steps a load may take (<= 6: ring of 8)
 __host__ __device__ constexpr size_t g32_lds_bytes() { return (size_t)kSlots * kSlotBytes; }
 
 #define EH_LDS __attribute__((address_space(3)))
@@ -71,6 +82,15 @@ __device__ __forceinline__ f32x16 mma32(const frag_t& a, const frag_t& b, f32x16
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
+template <int N, typename F, int I = 0>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, F, I + 1>(static_cast<F&&>(f));
+  }
+}
+
 // DMA loads a wave issues per k-step: the 2*MT fragments of a step are dealt
 // round-robin to the four waves; a wave with fewer real fragments repeats its
 // last one (same bytes to the same place) so that all waves count alike.
@@ -80,17 +100,19 @@ __host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Wa
 // wave's NB blocks of 32 tokens.
 //
 // k-step s (32 values of k) uses, per tile m, the operands a[m][0], a[m][1] (the
-// two 16-k halves, 32 rows each) and, per token block n, b[s % 3][n][0..1].
-// Schedule, with SYNC(s) at the start of step s:
+// two 16-k halves, 32 rows each) and, per token block n, b[s % D][n][0..1], with
+// D = kDepth register sets.  Schedule, with SYNC(s) at the start of step s:
 //   SYNC(s):  wait until my loads up to B(s) and DMA(s+1) have landed; barrier;
-//             issue DMA(s+4).  Its ring slot (8 slots) was last read during step
-//             s-5 and those reads fed matrix instructions of step s-4, so nobody
-//             is reading it and the sync need not wait for LDS reads at all.
-//   step s:   for each tile m: its 2*NB matrix instructions, then a[m] <- LDS
-//             slot of step s+1; after the last tile's use of b[n][h], that
-//             register is reloaded with B(s+3).
-// Loads return in order, so at SYNC(s+1) the loads that may still be in flight
-// are exactly the last two groups issued: DMA(s+3)+B(s+2)... counted below.
+//             issue DMA(s+D+1).  Its ring slot (8 slots) was last read at least
+//             two steps ago and those reads have fed matrix instructions since,
+//             so nobody is reading it and the sync need not wait for LDS reads.
+//   step s:   for each tile m: wait for a[m], its 2*NB matrix instructions, then
+//             a[m] <- LDS slot of step s+1; after the last tile's use of b[n],
+//             that register set is reloaded with B(s+D).
+// Loads return in order and every wave issues them in the order
+//   DMA(0) | DMA(1) B(0) | DMA(2) B(1) | ... | DMA(s+D) B(s+D-1) | ...
+// so at SYNC(s) the loads that may still be in flight are exactly the last D-1
+// groups, DMA(s+2) B(s+1) ... DMA(s+D) B(s+D-1): a wait on a compile-time count.
 template <int MT, int NB, bool ARGMAX_ONLY>
 __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq,
                                        int T, int VT16, int KS, int V, int lane, int wave,
@@ -141,27 +163,39 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   };
   // LDS read with the 16x32 -> 32x16 lane permutation: lane l takes row l%32 and
   // k group 2h + l/32, i.e. lane (2h + l/32)*16 + l%16 of fragment (l%32)/16.
-  const int laneoff = ((lane & 31) >> 4) * 1024 + (((lane >> 5) * 16 + (lane & 15)) << 4);
-  auto fetch_a = [&](frag_t (&a)[2], int m, int ks) {
-    EH_LDS const char* p = lds + (ks & (kSlots - 1)) * kSlotBytes + laneoff + m * 2048;
-    a[0] = *(const lds_frag_t*)(p);
-    a[1] = *(const lds_frag_t*)(p + 512);
+  // These reads are not tracked by the compiler either (it would wait for all of
+  // them at once): LDS reads return in order, tile m's two reads are followed by
+  // those of the other MT-1 tiles before tile m is used again, so the wait before
+  // a tile's matrix instructions is lgkmcnt(2*(MT-1)).  Nothing else in the loop
+  // may use that counter (no scalar loads); the build checks the generated code.
+  const uint32_t laneoff = (uint32_t)(uintptr_t)lds + ((lane & 31) >> 4) * 1024 + (((lane >> 5) * 16 + (lane & 15)) << 4);
+  auto fetch_a = [&](frag_t (&a)[2], auto mc, int ks) {
+    constexpr int m = decltype(mc)::value;
+    const uint32_t p = laneoff + (ks & (kSlots - 1)) * kSlotBytes;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[0]) : "v"(p), "n"(m * 2048) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[1]) : "v"(p), "n"(m * 2048 + 512) : "memory");
   };
+  constexpr int kLdsInFlight = 2 * (MT - 1);
 
   frag_t a[MT][2];
-  frag_t b0[NB][2], b1[NB][2], b2[NB][2];
+  frag_t b[kDepth][NB][2];
   // one k-step on register set b (holding B(ks)); refills a for ks+1 and b with B(ks+3)
-  auto step = [&](frag_t (&b)[NB][2], int ks) {
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
+  auto step = [&](frag_t (&b)[NB][2], int ks) {  // b: the register set holding B(ks)
+    static_for<MT>([&](auto mc) {
+      constexpr int m = decltype(mc)::value;
+      asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a[m][0]), "+v"(a[m][1]) : "n"(kLdsInFlight));
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) acc[m][n] = mma32(a[m][h], b[n][h], acc[m][n]);
         if (m == MT - 1) load_b(b[n], n, ks + kDepth);
       }
-      fetch_a(a[m], m, ks + 1);
-    }
+      fetch_a(a[m], mc, ks + 1);
+      // keep this order: the LDS reads of a step must be spread over the step and
+      // start early, or all four waves queue them at its end and the matrix cores
+      // idle while the LDS drains
+      __builtin_amdgcn_sched_barrier(0);
+    });
   };
 #define EH_SYNC(bset, s_)                                                                          \
   do {                                                                                             \
@@ -170,55 +204,57 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
       asm volatile("" : "+v"(bset[n_][0]));                                                        \
       asm volatile("" : "+v"(bset[n_][1]));                                                        \
     }                                                                                              \
-    dma((s_) + 4);                                                                                 \
+    dma((s_) + kDepth + 1);                                                                        \
   } while (0)
 
   // nobody may still be reading the ring (previous pass) when it is refilled
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  // Prologue.  Issue order: DMA(0) DMA(1) | B(0) DMA(2) | B(1) DMA(3) | B(2)
+  // Prologue.  Issue order: DMA(0) | DMA(1) B(0) | DMA(2) B(1) | ... | DMA(D) B(D-1)
   dma(0);
-  dma(1);
 #pragma unroll
-  for (int n = 0; n < NB; ++n) load_b(b0[n], n, 0);
-  dma(2);
+  for (int j = 0; j < kDepth; ++j) {
+    dma(j + 1);
 #pragma unroll
-  for (int n = 0; n < NB; ++n) load_b(b1[n], n, 1);
-  dma(3);
-#pragma unroll
-  for (int n = 0; n < NB; ++n) load_b(b2[n], n, 2);
-  // DMA(0) landed everywhere (younger: B(0) DMA(2) B(1) DMA(3) B(2)), then a <- slot 0
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kGroup + 2 * NB + kDma) : "memory");
-#pragma unroll
-  for (int m = 0; m < MT; ++m) fetch_a(a[m], m, 0);
-  // From here every SYNC(s) sees, younger than B(s) and DMA(s+1):
-  //   [B(s+1) DMA(s+3)] [B(s+2)]  at s = 0 (DMA(4) not yet issued: one group less kDma, so the
-  //   wait is only stricter), and [DMA(s+3) B(s+1)... in steady state two whole groups.
-  int ks = 0;
-  for (; ks + 2 < KS; ks += 3) {
-    EH_SYNC(b0, ks);
-    step(b0, ks);
-    EH_SYNC(b1, ks + 1);
-    step(b1, ks + 1);
-    EH_SYNC(b2, ks + 2);
-    step(b2, ks + 2);
+    for (int n = 0; n < NB; ++n) load_b(b[j][n], n, j);
   }
-  if (ks < KS) {
-    EH_SYNC(b0, ks);
-    step(b0, ks);
-    if (ks + 1 < KS) {
-      EH_SYNC(b1, ks + 1);
-      step(b1, ks + 1);
+  // DMA(0) landed everywhere (younger: D whole groups), then a <- slot 0
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kDepth * kGroup) : "memory");
+  static_for<MT>([&](auto mc) { fetch_a(a[decltype(mc)::value], mc, 0); });
+  // From here every SYNC(s) sees, younger than B(s) and DMA(s+1), exactly the D-1
+  // groups DMA(s+2) B(s+1) ... DMA(s+D) B(s+D-1).
+  int ks = 0;
+  for (; ks + kDepth <= KS; ks += kDepth) {
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j) {
+      EH_SYNC(b[j], ks + j);
+      step(b[j], ks + j);
     }
   }
+  // the last KS % D steps, nested so that step j+1 is only reachable through step j
+  auto tail = [&](auto self, auto jc) {
+    constexpr int j = decltype(jc)::value;
+    if constexpr (j < kDepth - 1) {
+      if (ks + j < KS) {
+        EH_SYNC(b[j], ks + j);
+        step(b[j], ks + j);
+        self(self, std::integral_constant<int, j + 1>{});
+      }
+    }
+  };
+  tail(tail, std::integral_constant<int, 0>{});
 #undef EH_SYNC
   // The loads issued past the end (clamped) still write their registers: wait for
   // them, and keep every destination register reserved until here, or the
   // compiler would hand it out again while a load is still on its way to it.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #pragma unroll
   for (int n = 0; n < NB; ++n)
 #pragma unroll
-    for (int h = 0; h < 2; ++h) asm volatile("" ::"v"(b0[n][h]), "v"(b1[n][h]), "v"(b2[n][h]));
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < kDepth; ++j) asm volatile("" ::"v"(b[j][n][h]));
+#pragma unroll
+  for (int m = 0; m < MT; ++m) asm volatile("" ::"v"(a[m][0]), "v"(a[m][1]));
 
   // accumulator register 4g+i of lane l: vocabulary row 32*tile + 8g + 4*(l/32) + i, token l%32
   const int half = lane >> 5;
