@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of known size (1 GiB read + 1 GiB written each), "
                          "to scale rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="only time the vendor GEMM library (torch.matmul, bf16) on the workload's "
+                         "projection shape: context for the MFMA roofline fraction, not part of the path")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -105,6 +108,29 @@ def main():
                                                "bytes_read": n, "bytes_written": n, "copies": 10}}))
         return
     w = G.CONFIGS[args.workload]
+    if args.library_gemm:
+        R = max(w.rows, 16)
+        y = torch.randn(R, w.d, device=dev, dtype=torch.bfloat16)
+        Ws = [torch.randn(w.V, w.d, device=dev, dtype=torch.bfloat16) * 0.02 for _ in range(6)]
+        o = torch.empty(R, w.V, device=dev, dtype=torch.bfloat16)
+        for Wl in Ws:
+            torch.matmul(y, Wl.t(), out=o)
+        torch.cuda.synchronize()
+        n = 0
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(4):
+            for Wl in Ws:
+                torch.matmul(y, Wl.t(), out=o)
+                n += 1
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / n
+        print(json.dumps({"library_gemm": {"shape": [R, w.d, w.V], "dtype": "bf16", "us_per_gemm": us,
+                                           "tflops": 2.0 * R * w.d * w.V / us * 1e-6,
+                                           "note": "logits written as bf16, no LayerNorm, no statistics"}}))
+        return
     t_setup = time.time()
     heads = G.make_heads(w, dev)
     esz = 2 if w.dtype == "bf16" else 4
@@ -227,8 +253,121 @@ def main():
         out.update(ms_per_step=dt / args.steps * 1e3)
         cpu = None
         B.eh_destroy(ctx)
+    elif args.workload == "c3_dynexit":
+        # 64 decode rows through 32 heads; a row leaves at its first H < tau and the
+        # survivors are compacted between heads.  Thresholds: the 10/40/70 % exit schedule,
+        # set from this library's own entropies of every head on every row (a bench input,
+        # not a parity reference).
+        hid = G.make_hidden(w, heads, dev)
+        R = w.rows
+        ctx0 = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")] * w.n_heads, max_rows=R)
+        Hall = torch.zeros((w.n_heads, R), device=dev)
+        for l in range(w.n_heads):
+            B.eh_eval(ctx0, l, hid.h[l], R, Hall[l], None, None)
+        torch.cuda.synchronize()
+        B.eh_destroy(ctx0)
+        tau = G.tau_for_schedule(Hall.cpu().numpy(), w.n_heads)
+        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=R)
+        ex = torch.full((R,), -1, dtype=torch.int32, device=dev)
+        tok = torch.full((R,), -1, dtype=torch.int32, device=dev)
+        nev = torch.zeros(1, dtype=torch.int64, device=dev)
+
+        def step():
+            B.eh_cascade(ctx, hid.h, R, ex, tok, None, nev)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        nev.zero_()
+        torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(args.steps):
+            step()
+        ev1.record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ev_s = ev0.elapsed_time(ev1) * 1e-3
+        B.eh_check(ctx)
+        evals = int(nev.item())
+        value = evals / dt
+        exl = ex.cpu().numpy()
+        heads_run = int(exl.max()) + 1                       # heads that still had a live row
+        launches = args.steps * heads_run
+        # dominant kernel: the batched projection of one head on the live rows; it streams the
+        # head's weights once whatever the number of live rows (HBM-bound: <= 64 flop per byte)
+        bytes_per_launch = w.d * w.V * esz + (evals / launches) * (w.d * esz + 12)
+        avg_s = ev_s / launches
+        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "kernel": "eh::gemm32_stats_kernel<1,false> (one launch = one head on the live rows)",
+                "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
+        cfg = {"workload": "c3_dynexit: d=2560 V=50304 32 heads x 64 rows bf16, rows exit at first H<tau, "
+                           "compaction between heads",
+               "mean_evals_per_cascade": evals / args.steps,
+               "exited_by_layer_8_16_24": [float((exl < l).mean()) for l in (8, 16, 24)]}
+        out.update(ms_per_step=dt / args.steps * 1e3)
+        cpu = None
+        B.eh_destroy(ctx)
+    elif args.workload == "c4_verify":
+        # 16 rows x (8 drafts + 1): argmax of the final head at 144 positions and the accepted
+        # prefix per row.  Four copies of the final head are used in turn so that the 257.6 MB
+        # weight stream comes from HBM, not from the last-level cache.
+        Bsz, k = 16, 8
+        fin = w.n_heads - 1
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1234)
+        draft = torch.randint(0, w.V, (Bsz, k), generator=gen, device=dev)
+        case = G.make_verify_case(w, heads, draft, dev)
+        n_copies = 4
+        ctxs = []
+        for c in range(n_copies):
+            Wc = heads.W[fin].clone()
+            ctxs.append(B.eh_create([Wc], [heads.gamma[fin]], [heads.beta[fin]], [float("inf")],
+                                    max_rows=Bsz * (k + 1)))
+            del Wc
+        acc = torch.full((Bsz,), -1, dtype=torch.int32, device=dev)
+        nxt = torch.full((Bsz,), -1, dtype=torch.int32, device=dev)
+        d32 = draft.to(torch.int32).contiguous()
+        calls_per_step = 8
+
+        def step():
+            for i in range(calls_per_step):
+                B.dssd_verify(ctxs[i % n_copies], case.f_final, d32, None, acc, nxt, None)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(args.steps):
+            step()
+        ev1.record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ev_s = ev0.elapsed_time(ev1) * 1e-3
+        launches = args.steps * calls_per_step
+        evals = launches * Bsz * (k + 1)
+        value = evals / dt
+        bytes_per_launch = w.d * w.V * esz + Bsz * (k + 1) * (w.d * esz + 4)
+        avg_s = ev_s / launches
+        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "kernel": "eh::gemm32_stats_kernel<2,true> (one launch = one verification, 144 positions)",
+                "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
+        cfg = {"workload": "c4_verify: d=2560 V=50304 final head, 16 rows x (8 drafts + 1) bf16, "
+                           f"{calls_per_step} verifications per bench step over {n_copies} weight copies",
+               "mean_accepted": float(acc.float().mean().item())}
+        out.update(ms_per_step=dt / args.steps * 1e3)
+        cpu = None
+        for c in ctxs:
+            B.eh_destroy(c)
     else:
-        raise SystemExit("workload not wired into bench.py yet: " + args.workload)
+        raise SystemExit("unknown workload: " + args.workload)
 
     line = {"metric": "exit_head_evals_per_sec", "value": value, "unit": "evals/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": out["ms_per_step"],

@@ -100,7 +100,7 @@ eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const
   const int RB = (batched && bf) ? 32 : 16;
   const int R_pad = (n_rows + RB - 1) / RB * RB;
   {
-    dim3 g((R_pad + 3) / 4), b(256);
+    dim3 g(R_pad), b(64);
     if (bf && RB == 32)
       hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
                          n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);

@@ -43,18 +43,28 @@ __global__ __launch_bounds__(256) void repack_w_kernel(const void* __restrict__ 
 template <typename DT>
 __device__ __forceinline__ void load_elems(const void* row, int k0, float (&x)[DT::EPL]);
 
+// 16 bytes of a row -> its EPL elements as float
+template <typename DT>
+__device__ __forceinline__ void decode_elems(const frag_t& v, float (&x)[DT::EPL]);
 template <>
-__device__ __forceinline__ void load_elems<DtBf16>(const void* row, int k0, float (&x)[8]) {
-  const frag_t v = *(const frag_t*)((const char*)row + (int64_t)k0 * 2);
+__device__ __forceinline__ void decode_elems<DtBf16>(const frag_t& v, float (&x)[8]) {
   x[0] = bf16_bits_to_f32(v.x & 0xffffu); x[1] = bf16_bits_to_f32(v.x >> 16);
   x[2] = bf16_bits_to_f32(v.y & 0xffffu); x[3] = bf16_bits_to_f32(v.y >> 16);
   x[4] = bf16_bits_to_f32(v.z & 0xffffu); x[5] = bf16_bits_to_f32(v.z >> 16);
   x[6] = bf16_bits_to_f32(v.w & 0xffffu); x[7] = bf16_bits_to_f32(v.w >> 16);
 }
 template <>
+__device__ __forceinline__ void decode_elems<DtF32>(const frag_t& v, float (&x)[4]) {
+  x[0] = __uint_as_float(v.x); x[1] = __uint_as_float(v.y);
+  x[2] = __uint_as_float(v.z); x[3] = __uint_as_float(v.w);
+}
+template <>
+__device__ __forceinline__ void load_elems<DtBf16>(const void* row, int k0, float (&x)[8]) {
+  decode_elems<DtBf16>(*(const frag_t*)((const char*)row + (int64_t)k0 * 2), x);
+}
+template <>
 __device__ __forceinline__ void load_elems<DtF32>(const void* row, int k0, float (&x)[4]) {
-  const float4 v = *(const float4*)((const char*)row + (int64_t)k0 * 4);
-  x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  decode_elems<DtF32>(*(const frag_t*)((const char*)row + (int64_t)k0 * 4), x);
 }
 
 template <typename DT>
@@ -123,22 +133,86 @@ __device__ __forceinline__ void wave_layernorm(const void* row, int d, int n_chu
   }
 }
 
+// Same arithmetic, in the same order, for rows of at most kLnCache*64 chunks: the row is read
+// from memory once and kept in registers for the three sweeps (mean, variance, output).
+constexpr int kLnCache = 8;
+template <typename DT, typename OutFn>
+__device__ __forceinline__ void wave_layernorm_cached(const void* row, int d, int n_chunks,
+                                                      const float* __restrict__ gamma,
+                                                      const float* __restrict__ beta, float eps, int lane,
+                                                      OutFn out) {
+  const int live_chunks = d / DT::EPL;
+  frag_t raw[kLnCache];
+#pragma unroll
+  for (int j = 0; j < kLnCache; ++j) {
+    const int c = lane + j * kWave;
+    raw[j] = mk_frag(0, 0, 0, 0);
+    if (c < live_chunks) raw[j] = *(const frag_t*)((const char*)row + (int64_t)c * 16);
+  }
+  double s = 0.0;
+#pragma unroll
+  for (int j = 0; j < kLnCache; ++j) {
+    if (lane + j * kWave < live_chunks) {
+      float x[DT::EPL];
+      decode_elems<DT>(raw[j], x);
+#pragma unroll
+      for (int i = 0; i < DT::EPL; ++i) s += (double)x[i];
+    }
+  }
+  const double mu = wave_sum(s) / (double)d;
+  double v = 0.0;
+#pragma unroll
+  for (int j = 0; j < kLnCache; ++j) {
+    if (lane + j * kWave < live_chunks) {
+      float x[DT::EPL];
+      decode_elems<DT>(raw[j], x);
+#pragma unroll
+      for (int i = 0; i < DT::EPL; ++i) {
+        const double cdev = (double)x[i] - mu;
+        v += cdev * cdev;
+      }
+    }
+  }
+  const double var = wave_sum(v) / (double)d;
+  const double rstd = 1.0 / sqrt(var + (double)eps);
+#pragma unroll
+  for (int j = 0; j < kLnCache; ++j) {
+    const int c = lane + j * kWave;
+    if (c < n_chunks) {
+      frag_t o = mk_frag(0, 0, 0, 0);
+      if (c < live_chunks) {
+        float x[DT::EPL];
+        decode_elems<DT>(raw[j], x);
+        double y[DT::EPL];
+#pragma unroll
+        for (int i = 0; i < DT::EPL; ++i) {
+          const int k = c * DT::EPL + i;
+          y[i] = (double)gamma[k] * (((double)x[i] - mu) * rstd) + (double)beta[k];
+        }
+        o = pack_elems<DT>(y);
+      }
+      out(c, o);
+    }
+  }
+}
+
+// One wave (= one workgroup) per row.
 // RB = rows per activation block: 16 (fragments of 16 rows x KPF k, the operand
 // order of the 16x16 matrix instructions) or 32 (bf16 only: fragments of 32 rows
 // x 16 k for v_mfma_f32_32x32x16_bf16; lane l of fragment (block, k16) holds row
 // l%32, k = 16*k16 + 8*(l/32) .. +8).  R_pad is a multiple of RB; rows between
 // the live rows and R_pad are zero-filled.
 template <typename DT, int RB>
-__global__ __launch_bounds__(256) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
-                                                      const int* __restrict__ row_idx,
-                                                      const int* __restrict__ n_rows_dev, int n_rows,
-                                                      int R_pad, int d, int KS,
-                                                      const float* __restrict__ gamma,
-                                                      const float* __restrict__ beta, float eps,
-                                                      frag_t* __restrict__ yf) {
+__global__ __launch_bounds__(64) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
+                                                     const int* __restrict__ row_idx,
+                                                     const int* __restrict__ n_rows_dev, int n_rows,
+                                                     int R_pad, int d, int KS,
+                                                     const float* __restrict__ gamma,
+                                                     const float* __restrict__ beta, float eps,
+                                                     frag_t* __restrict__ yf) {
   static_assert(RB == 16 || (RB == 32 && DT::EPL == 8), "row block");
-  const int lane = threadIdx.x & 63;
-  const int p = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int lane = threadIdx.x;
+  const int p = blockIdx.x;
   if (p >= R_pad) return;
   int n_live = n_rows;
   if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
@@ -156,7 +230,8 @@ __global__ __launch_bounds__(256) void ln_pack_kernel(const void* __restrict__ h
   }
   const int64_t r = row_idx ? row_idx[p] : p;
   const void* row = (const char*)h + r * row_stride * DT::ESZ;
-  wave_layernorm<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+  if (n_chunks <= kLnCache * kWave) wave_layernorm_cached<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+  else wave_layernorm<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
 }
 
 // ---------------------------------------------------------------------------
