@@ -66,16 +66,19 @@ def split_kernels(asm: str) -> dict:
 class Program:
     def __init__(self, lines):
         self.ins = []        # instruction text (mnemonic + operands, comments stripped)
+        self.note = []       # the comment that followed it on its line ("" if none)
         self.label_at = {}   # label -> index of the next instruction
         for line in lines:
             m = LABEL_RE.match(line)
             if m:
                 self.label_at[m.group(1)] = len(self.ins)
                 continue
-            t = line.split(";")[0].strip()
+            t, _, note = line.partition(";")
+            t = t.strip()
             if not t or t.startswith("."):
                 continue
             self.ins.append(t)
+            self.note.append(note.strip())
         n = len(self.ins)
         self.succ = [None] * n
         for i, t in enumerate(self.ins):
@@ -168,18 +171,18 @@ STEP_SYNC_RE = re.compile(r"^s_waitcnt vmcnt\((\d+)\)(?: lgkmcnt\(0\))?$")
 
 
 def check_step_counts(name, lines, max_report=5):
-    """The waits count on every k-step issuing the same loads.  A step sync is
-    `s_waitcnt vmcnt(N)` (N > 0, with or without lgkmcnt(0)) directly followed by
-    `s_barrier`.  On every control-flow path from one step sync to the next, the loads
+    """The waits count on every k-step issuing the same loads.  A step sync is a
+    `s_waitcnt vmcnt(N)` with N > 0 that the kernel source marks with the comment
+    `; step-sync` (the compiler's own waits are not step syncs).  On every control-flow path from one step sync to the next, the loads
     issued (DMA + register loads) must divide the next sync's N -- by the same factor (the
     k-steps a load may stay in flight beyond the next one) everywhere in the kernel -- and
     nothing else may use vector memory.  Paths end at a pass boundary (`vmcnt(0)`)."""
     prog = Program(lines)
     ins = prog.ins
     sync_n = {}
-    for i in range(1, len(ins)):
-        m = STEP_SYNC_RE.match(ins[i - 1])
-        if ins[i] == "s_barrier" and m and int(m.group(1)) > 0:
+    for i, t in enumerate(ins):
+        m = STEP_SYNC_RE.match(t)
+        if m and int(m.group(1)) > 0 and "step-sync" in prog.note[i]:
             sync_n[i] = int(m.group(1))
     findings, depths, checked = [], set(), 0
     for start in sync_n:

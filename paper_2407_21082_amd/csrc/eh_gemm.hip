@@ -108,7 +108,7 @@ __device__ __forceinline__ void gemm_pass(const frag_t* __restrict__ Wf, const f
   // free for everybody and is refilled with step s+3.
 #define EH_SYNC(bset, s_)                                                                          \
   do {                                                                                             \
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(kInFlight) : "memory");       \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0) ; step-sync\n\ts_barrier" ::"n"(kInFlight) : "memory");       \
     _Pragma("unroll") for (int n_ = 0; n_ < NB; ++n_) asm volatile("" : "+v"(bset[n_]));           \
     dma((s_) + 3);                                                                                 \
   } while (0)

@@ -101,18 +101,20 @@ __host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Wa
 //
 // k-step s (32 values of k) uses, per tile m, the operands a[m][0], a[m][1] (the
 // two 16-k halves, 32 rows each) and, per token block n, b[s % D][n][0..1], with
-// D = kDepth register sets.  Schedule, with SYNC(s) at the start of step s:
-//   SYNC(s):  wait until my loads up to B(s) and DMA(s+1) have landed; barrier;
-//             issue DMA(s+D+1).  Its ring slot (8 slots) was last read at least
-//             two steps ago and those reads have fed matrix instructions since,
-//             so nobody is reading it and the sync need not wait for LDS reads.
-//   step s:   for each tile m: wait for a[m], its 2*NB matrix instructions, then
-//             a[m] <- LDS slot of step s+1; after the last tile's use of b[n],
-//             that register set is reloaded with B(s+D).
+// D = kDepth register sets.  Step s:
+//   wait until my loads up to B(s) and my share of DMA(s+1) have landed;
+//   tile 0's 2*NB matrix instructions; barrier (now every wave's share of DMA(s+1)
+//   is in LDS); then for each tile m: [its matrix instructions,] a[m] <- LDS slot of
+//   step s+1, and one piece of DMA(s+D+1); after the last tile's use of b[n] that
+//   register set is reloaded with B(s+D).  The ring slot DMA(s+D+1) goes to (8
+//   slots) was last read at least two steps ago and those reads have fed matrix
+//   instructions since, so nobody is reading it.
 // Loads return in order and every wave issues them in the order
 //   DMA(0) | DMA(1) B(0) | DMA(2) B(1) | ... | DMA(s+D) B(s+D-1) | ...
-// so at SYNC(s) the loads that may still be in flight are exactly the last D-1
-// groups, DMA(s+2) B(s+1) ... DMA(s+D) B(s+D-1): a wait on a compile-time count.
+// (inside a step the pieces of its DMA and its B loads interleave, which does not
+// change the counts), so at the wait that opens step s the loads that may still be in
+// flight are exactly the last D-1 groups, DMA(s+2) B(s+1) ... DMA(s+D) B(s+D-1): a
+// wait on a compile-time count.
 template <int MT, int NB, bool ARGMAX_ONLY>
 __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq,
                                        int T, int VT16, int KS, int V, int lane, int wave,
@@ -146,14 +148,15 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
     wsrc[i] = ((long long)t16 * KS) << 10;
     wdst[i] = f * 1024;
   }
-  auto dma = [&](int ks) {  // weight fragments of k-step ks into their ring slot
+  // weight fragments of k-step ks into their ring slot: this wave's i-th fragment, or all of them
+  auto dma_part = [&](auto ic, int ks) {
+    constexpr int i = decltype(ic)::value;
     const int k = min(ks, lastk);
     EH_LDS char* slot = lds + (ks & (kSlots - 1)) * kSlotBytes;
-#pragma unroll
-    for (int i = 0; i < kDma; ++i)
-      __builtin_amdgcn_global_load_lds((const EH_GLOBAL void*)(wbase + wsrc[i] + ((long long)k << 10) + lane16),
-                                       (EH_LDS void*)(slot + wdst[i]), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const EH_GLOBAL void*)(wbase + wsrc[i] + ((long long)k << 10) + lane16),
+                                     (EH_LDS void*)(slot + wdst[i]), 16, 0, 0);
   };
+  auto dma = [&](int ks) { static_for<kDma>([&](auto ic) { dma_part(ic, ks); }); };
   // activations: block n, k-step ks, half h -> fragment (n, 2*ks + h) of 2*KS per block
   const EH_GLOBAL char* ybase = uniform_ptr(yq);
   auto load_b = [&](frag_t (&dst)[2], int n, int ks) {
@@ -179,8 +182,20 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
 
   frag_t a[MT][2];
   frag_t b[kDepth][NB][2];
-  // one k-step on register set b (holding B(ks)); refills a for ks+1 and b with B(ks+3)
-  auto step = [&](frag_t (&b)[NB][2], int ks) {  // b: the register set holding B(ks)
+  // One k-step on register set b.  The step opens with the wait that proves this wave's
+  // loads up to B(ks) and its share of DMA(ks+1) have landed; tile 0 then runs at once
+  // (its weights are in registers already), and the barrier that publishes DMA(ks+1)
+  // to the other waves comes behind tile 0's matrix instructions, as do, spread over the
+  // tiles, the LDS reads for step ks+1 and the pieces of DMA(ks+D+1): a single wave issues
+  // about one instruction per four cycles, so everything that is not a matrix instruction
+  // has to sit between matrix instructions or the matrix core idles while it is issued.
+  auto step = [&](frag_t (&b)[NB][2], int ks) {
+    asm volatile("s_waitcnt vmcnt(%0) ; step-sync" ::"n"(kInFlight) : "memory");
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+      asm volatile("" : "+v"(b[n][0]));
+      asm volatile("" : "+v"(b[n][1]));
+    }
     static_for<MT>([&](auto mc) {
       constexpr int m = decltype(mc)::value;
       asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a[m][0]), "+v"(a[m][1]) : "n"(kLdsInFlight));
@@ -190,22 +205,19 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
         for (int h = 0; h < 2; ++h) acc[m][n] = mma32(a[m][h], b[n][h], acc[m][n]);
         if (m == MT - 1) load_b(b[n], n, ks + kDepth);
       }
+      if constexpr (m == 0) {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_barrier" ::: "memory");
+      }
       fetch_a(a[m], mc, ks + 1);
-      // keep this order: the LDS reads of a step must be spread over the step and
-      // start early, or all four waves queue them at its end and the matrix cores
-      // idle while the LDS drains
+      // DMA piece i travels with tile min(i, MT-1)
+      static_for<kDma>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr ((i < MT - 1 ? i : MT - 1) == m) dma_part(ic, ks + kDepth + 1);
+      });
       __builtin_amdgcn_sched_barrier(0);
     });
   };
-#define EH_SYNC(bset, s_)                                                                          \
-  do {                                                                                             \
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kInFlight) : "memory");                  \
-    _Pragma("unroll") for (int n_ = 0; n_ < NB; ++n_) {                                            \
-      asm volatile("" : "+v"(bset[n_][0]));                                                        \
-      asm volatile("" : "+v"(bset[n_][1]));                                                        \
-    }                                                                                              \
-    dma((s_) + kDepth + 1);                                                                        \
-  } while (0)
 
   // nobody may still be reading the ring (previous pass) when it is refilled
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -220,29 +232,24 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   // DMA(0) landed everywhere (younger: D whole groups), then a <- slot 0
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kDepth * kGroup) : "memory");
   static_for<MT>([&](auto mc) { fetch_a(a[decltype(mc)::value], mc, 0); });
-  // From here every SYNC(s) sees, younger than B(s) and DMA(s+1), exactly the D-1
-  // groups DMA(s+2) B(s+1) ... DMA(s+D) B(s+D-1).
+  // From here the wait that opens step s sees, younger than B(s) and DMA(s+1), exactly
+  // the D-1 groups DMA(s+2) B(s+1) ... DMA(s+D) B(s+D-1).
   int ks = 0;
   for (; ks + kDepth <= KS; ks += kDepth) {
 #pragma unroll
-    for (int j = 0; j < kDepth; ++j) {
-      EH_SYNC(b[j], ks + j);
-      step(b[j], ks + j);
-    }
+    for (int j = 0; j < kDepth; ++j) step(b[j], ks + j);
   }
   // the last KS % D steps, nested so that step j+1 is only reachable through step j
   auto tail = [&](auto self, auto jc) {
     constexpr int j = decltype(jc)::value;
     if constexpr (j < kDepth - 1) {
       if (ks + j < KS) {
-        EH_SYNC(b[j], ks + j);
         step(b[j], ks + j);
         self(self, std::integral_constant<int, j + 1>{});
       }
     }
   };
   tail(tail, std::integral_constant<int, 0>{});
-#undef EH_SYNC
   // The loads issued past the end (clamped) still write their registers: wait for
   // them, and keep every destination register reserved until here, or the
   // compiler would hand it out again while a load is still on its way to it.

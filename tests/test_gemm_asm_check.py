@@ -12,20 +12,20 @@ def kernel(body: str) -> str:
 
 
 STEP_OK = """
-\ts_waitcnt vmcnt(3) lgkmcnt(0)
+\ts_waitcnt vmcnt(3) lgkmcnt(0) ; step-sync
 \ts_barrier
 .LBB0_1:
 \tglobal_load_lds_dwordx4 v[2:3], off
 \tglobal_load_lds_dwordx4 v[4:5], off
 \tv_mfma_f32_16x16x32_bf16 a[0:3], v[20:23], v[8:11], a[0:3]
 \tglobal_load_dwordx4 v[8:11], v[6:7], off
-\ts_waitcnt vmcnt(3) lgkmcnt(0)
+\ts_waitcnt vmcnt(3) lgkmcnt(0) ; step-sync
 \ts_barrier
 \tglobal_load_lds_dwordx4 v[2:3], off
 \tglobal_load_lds_dwordx4 v[4:5], off
 \tv_mfma_f32_16x16x32_bf16 a[0:3], v[20:23], v[12:15], a[0:3]
 \tglobal_load_dwordx4 v[12:15], v[6:7], off
-\ts_waitcnt vmcnt(3) lgkmcnt(0)
+\ts_waitcnt vmcnt(3) lgkmcnt(0) ; step-sync
 \ts_barrier
 \ts_cbranch_scc1 .LBB0_1
 \ts_waitcnt vmcnt(0)
