@@ -113,9 +113,9 @@ eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const
   }
   int n_parts = kStreamGrid;
   if (batched && bf) {
-    EH_HIP(c, gemm32_launch(c, head, n_rows_dev, n_rows, AO, &n_parts, s));
+    EH_HIP(c, gemm32_launch(c, head, n_rows_dev, n_rows, AO, c->yf, c->partials, &n_parts, s));
   } else if (batched) {
-    EH_HIP(c, gemm_launch(c, head, n_rows_dev, n_rows, AO, &n_parts, s));
+    EH_HIP(c, gemm_launch(c, head, n_rows_dev, n_rows, AO, c->yf, c->partials, &n_parts, s));
   } else {
     const int NBtot = R_pad / 16;
     for (int nb0 = 0; nb0 < NBtot; nb0 += kMaxNB) {
@@ -125,7 +125,7 @@ eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const
     }
   }
   hipLaunchKernelGGL(finalize_kernel, dim3(n_rows), dim3(64), 0, s, c->partials, n_parts, R_pad,
-                     n_rows_dev, n_rows, AO ? nullptr : H, AO ? nullptr : lse, argmax);
+                     n_rows_dev, n_rows, AO ? nullptr : H, AO ? nullptr : lse, argmax, (int64_t)0, (int64_t)0);
   EH_HIP(c, hipGetLastError());
   return EH_OK;
 }
@@ -319,6 +319,64 @@ eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride
   }
   return run_head<false>(ctx, head, h, h_row_stride, row_idx, n_rows_dev, n_rows, H, lse, argmax,
                          (hipStream_t)stream);
+}
+
+eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const void* h_layers,
+                        int64_t layer_stride, int64_t row_stride, int32_t n_rows, float* H, float* lse,
+                        int32_t* argmax, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (n_heads_eval < 0 || head0 < 0 || head0 + n_heads_eval > ctx->n_heads)
+    return fail(ctx, EH_ERR_RANGE, "heads out of range");
+  if (n_rows == 0 || n_heads_eval == 0) return EH_OK;
+  if (!h_layers) return fail(ctx, EH_ERR_NULL, "h_layers is NULL");
+  eh_status st = check_rows(ctx, h_layers, row_stride, n_rows);
+  if (st != EH_OK) return st;
+  const int esz = ctx->dtype == EH_BF16 ? 2 : 4;
+  if ((layer_stride * esz) % 16 != 0) return fail(ctx, EH_ERR_SHAPE, "hidden rows must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const bool batched = ctx->dtype == EH_BF16 && ctx->bias.empty() && ctx->use_gemm && n_rows > 16;
+  if (!batched) {
+    // shapes the many-heads kernels do not cover: one head after the other
+    for (int l = 0; l < n_heads_eval; ++l) {
+      st = eh_eval(ctx, head0 + l, (const char*)h_layers + (int64_t)l * layer_stride * esz, row_stride,
+                   nullptr, nullptr, n_rows, H ? H + (int64_t)l * n_rows : nullptr,
+                   lse ? lse + (int64_t)l * n_rows : nullptr,
+                   argmax ? argmax + (int64_t)l * n_rows : nullptr, stream);
+      if (st != EH_OK) return st;
+    }
+    return EH_OK;
+  }
+  DeviceGuard guard(ctx->device);
+  // per head: activations for max_rows rows (plus the zero blocks the kernel may read past
+  // them) and one set of partial statistics
+  const size_t y_stride = (size_t)(ctx->R_pad_max / 16 + 32) * ctx->KS * kWave;
+  const size_t part_stride = (size_t)kStreamGrid * ctx->R_pad_max;
+  if (ctx->mh_heads < n_heads_eval) {
+    // grow-only workspace kept by the context; the old one may still be in use on a stream
+    EH_HIP(ctx, hipDeviceSynchronize());
+    eh::frag_t* y = nullptr;
+    eh::Stats* pt = nullptr;
+    hipError_t e = dev_alloc(ctx, &y, y_stride * n_heads_eval);
+    if (e == hipSuccess) e = dev_alloc(ctx, &pt, part_stride * n_heads_eval);
+    if (e == hipSuccess) e = hipMemset(y, 0, y_stride * n_heads_eval * sizeof(frag_t));
+    EH_HIP(ctx, e);
+    ctx->mh_yf = y;
+    ctx->mh_partials = pt;
+    ctx->mh_heads = n_heads_eval;
+  }
+  const int R_pad = (n_rows + 31) & ~31;
+  hipLaunchKernelGGL((ln_pack_heads_kernel<DtBf16, 32>), dim3(R_pad, n_heads_eval), dim3(64), 0, s, h_layers,
+                     layer_stride, row_stride, n_rows, R_pad, ctx->d, ctx->KS,
+                     (const float* const*)(ctx->d_gamma + head0), (const float* const*)(ctx->d_beta + head0),
+                     ctx->eps, ctx->mh_yf, (int64_t)y_stride);
+  int n_parts = 0;
+  for (int l = 0; l < n_heads_eval; ++l)
+    EH_HIP(ctx, gemm32_launch(ctx, head0 + l, nullptr, n_rows, false, ctx->mh_yf + (size_t)l * y_stride,
+                              ctx->mh_partials + (size_t)l * part_stride, &n_parts, s));
+  hipLaunchKernelGGL(finalize_kernel, dim3(n_rows, n_heads_eval), dim3(64), 0, s, ctx->mh_partials, n_parts,
+                     R_pad, (const int*)nullptr, n_rows, H, lse, argmax, (int64_t)part_stride, (int64_t)n_rows);
+  EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
 }
 
 eh_status eh_exit_decide(eh_ctx* ctx, int32_t head, const float* H, const int32_t* argmax,

@@ -237,7 +237,7 @@ static int pick_nb(int blocks) {
 }
 
 hipError_t gemm_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
-                       int* n_parts, hipStream_t s) {
+                       const frag_t* yf, Stats* partials, int* n_parts, hipStream_t s) {
   const int R_pad = (n_rows + 15) & ~15;
   const int blocks = R_pad / 16;
   const int nb = pick_nb(blocks);
@@ -247,8 +247,8 @@ hipError_t gemm_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_r
   *n_parts = gx;
   const frag_t* Wf = c->Wf[head];
   if (c->dtype != EH_F32) return hipErrorInvalidValue;  // bf16 has its own kernel (32x32x16 instructions)
-  if (argmax_only) launch_nb<DtF32, true>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
-  else launch_nb<DtF32, false>(nb, g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+  if (argmax_only) launch_nb<DtF32, true>(nb, g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
+  else launch_nb<DtF32, false>(nb, g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
   return hipGetLastError();
 }
 

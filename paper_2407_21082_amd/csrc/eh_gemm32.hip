@@ -348,7 +348,7 @@ void launch32(dim3 g, hipStream_t s, const frag_t* Wf, const frag_t* yq, int VT1
 }  // namespace
 
 hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
-                         int* n_parts, hipStream_t s) {
+                         const frag_t* yf, Stats* partials, int* n_parts, hipStream_t s) {
   const int R_pad = (n_rows + 31) & ~31;
   const int blocks = R_pad / 32;
   const int nb = blocks <= kG32Waves ? 1 : 2;
@@ -360,11 +360,11 @@ hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n
   *n_parts = gx;
   const frag_t* Wf = c->Wf[head];
   if (nb == 1) {
-    if (argmax_only) launch32<1, true>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
-    else launch32<1, false>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+    if (argmax_only) launch32<1, true>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
+    else launch32<1, false>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
   } else {
-    if (argmax_only) launch32<2, true>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
-    else launch32<2, false>(g, s, Wf, c->yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, c->partials);
+    if (argmax_only) launch32<2, true>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
+    else launch32<2, false>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
   }
   return hipGetLastError();
 }

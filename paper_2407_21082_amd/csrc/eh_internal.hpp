@@ -26,6 +26,11 @@ struct eh_ctx {
   float* d_tau = nullptr;
   eh::frag_t* yf = nullptr;     // [R_pad_max/16][KS][64] activations in fragment order
   eh::Stats* partials = nullptr;  // [kStreamGrid][R_pad_max]
+  // workspace of eh_eval_heads, allocated by its first call: one activation buffer and one
+  // set of partials per head
+  eh::frag_t* mh_yf = nullptr;
+  eh::Stats* mh_partials = nullptr;
+  int mh_heads = 0;
   float* ws_H = nullptr;        // [max_rows] internal outputs (cascade, verify)
   float* ws_lse = nullptr;
   int* ws_argmax = nullptr;
@@ -76,15 +81,15 @@ struct DecodeParams {
 // Sets up the decode kernel for this context (grid, LDS size, function
 // attributes).  Leaves ctx->decode_grid = 0 if the shape does not fit.
 hipError_t decode_prepare(eh_ctx* ctx);
-// Enqueues the batched projection + statistics kernel for one head on the rows
-// already laid out in ctx->yf; per-workgroup partial statistics go to
-// ctx->partials[*n_parts][R_pad].  Heads with a bias vector are not supported.
+// Enqueues the batched projection + statistics kernel (fp32) for one head on the rows
+// laid out in yf (fragments of 16 rows); per-workgroup partial statistics go to
+// partials[*n_parts][n_rows rounded up to 16].  Heads with a bias vector are not supported.
 hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
-                       int* n_parts, hipStream_t s);
-// Same for bf16 with blocks of 32 rows: ctx->yf must hold the rows in the 32 x 16
-// operand order (ln_pack_kernel<DtBf16, 32>), partials are [*n_parts][n_rows rounded up to 32].
+                       const eh::frag_t* yf, eh::Stats* partials, int* n_parts, hipStream_t s);
+// Same for bf16 with blocks of 32 rows: yf must hold the rows in the 32 x 16 operand
+// order (ln_pack_kernel<DtBf16, 32>), partials are [*n_parts][n_rows rounded up to 32].
 hipError_t gemm32_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
-                         int* n_parts, hipStream_t s);
+                         const eh::frag_t* yf, eh::Stats* partials, int* n_parts, hipStream_t s);
 // Enqueues the decode kernel.
 hipError_t decode_launch(const eh_ctx* ctx, const DecodeParams& p, hipStream_t s);
 

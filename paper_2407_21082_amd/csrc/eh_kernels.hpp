@@ -203,19 +203,13 @@ __device__ __forceinline__ void wave_layernorm_cached(const void* row, int d, in
 // l%32, k = 16*k16 + 8*(l/32) .. +8).  R_pad is a multiple of RB; rows between
 // the live rows and R_pad are zero-filled.
 template <typename DT, int RB>
-__global__ __launch_bounds__(64) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
-                                                     const int* __restrict__ row_idx,
-                                                     const int* __restrict__ n_rows_dev, int n_rows,
-                                                     int R_pad, int d, int KS,
-                                                     const float* __restrict__ gamma,
-                                                     const float* __restrict__ beta, float eps,
-                                                     frag_t* __restrict__ yf) {
+__device__ __forceinline__ void ln_pack_row(const void* __restrict__ h, int64_t row_stride,
+                                            const int* __restrict__ row_idx, int n_live, int R_pad, int d,
+                                            int KS, const float* __restrict__ gamma,
+                                            const float* __restrict__ beta, float eps,
+                                            frag_t* __restrict__ yf, int p, int lane) {
   static_assert(RB == 16 || (RB == 32 && DT::EPL == 8), "row block");
-  const int lane = threadIdx.x;
-  const int p = blockIdx.x;
   if (p >= R_pad) return;
-  int n_live = n_rows;
-  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
   const int nb = p / RB, n = p % RB;
   const int n_chunks = KS * 4;
   // a block holds KS*4 chunks of 16 bytes per row either way
@@ -232,6 +226,37 @@ __global__ __launch_bounds__(64) void ln_pack_kernel(const void* __restrict__ h,
   const void* row = (const char*)h + r * row_stride * DT::ESZ;
   if (n_chunks <= kLnCache * kWave) wave_layernorm_cached<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
   else wave_layernorm<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+}
+
+template <typename DT, int RB>
+__global__ __launch_bounds__(64) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
+                                                     const int* __restrict__ row_idx,
+                                                     const int* __restrict__ n_rows_dev, int n_rows,
+                                                     int R_pad, int d, int KS,
+                                                     const float* __restrict__ gamma,
+                                                     const float* __restrict__ beta, float eps,
+                                                     frag_t* __restrict__ yf) {
+  int n_live = n_rows;
+  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  ln_pack_row<DT, RB>(h, row_stride, row_idx, n_live, R_pad, d, KS, gamma, beta, eps, yf, blockIdx.x,
+                      threadIdx.x);
+}
+
+// The same for several heads at once: blockIdx.y = head (relative to the first),
+// whose hidden states start layer_stride elements after the previous head's and
+// whose output goes y_stride fragments after it.
+template <typename DT, int RB>
+__global__ __launch_bounds__(64) void ln_pack_heads_kernel(const void* __restrict__ h_layers,
+                                                           int64_t layer_stride, int64_t row_stride,
+                                                           int n_rows, int R_pad, int d, int KS,
+                                                           const float* const* __restrict__ gamma_tab,
+                                                           const float* const* __restrict__ beta_tab,
+                                                           float eps, frag_t* __restrict__ yf,
+                                                           int64_t y_stride) {
+  const int l = blockIdx.y;
+  const void* h = (const char*)h_layers + (int64_t)l * layer_stride * DT::ESZ;
+  ln_pack_row<DT, RB>(h, row_stride, nullptr, n_rows, R_pad, d, KS, gamma_tab[l], beta_tab[l], eps,
+                      yf + (int64_t)l * y_stride, blockIdx.x, threadIdx.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -334,25 +359,30 @@ __device__ __forceinline__ void stats_finalize(const Stats& s, float& H, float& 
   lse = (float)(kLn2d * ((double)s.m + l2));
 }
 
+// blockIdx.y = head (relative): partials advance by part_stride records per head,
+// outputs by out_stride elements (both 0 for a single head).
 static __global__ __launch_bounds__(64) void finalize_kernel(const Stats* __restrict__ partials, int n_parts,
                                                       int R_pad, const int* __restrict__ n_rows_dev,
                                                       int n_rows, float* __restrict__ H,
-                                                      float* __restrict__ lse, int* __restrict__ argmax) {
+                                                      float* __restrict__ lse, int* __restrict__ argmax,
+                                                      int64_t part_stride, int64_t out_stride) {
   const int p = blockIdx.x, lane = threadIdx.x;
   int n_live = n_rows;
   if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
   if (p >= n_live) return;
+  partials += (int64_t)blockIdx.y * part_stride;
+  const int64_t o = (int64_t)blockIdx.y * out_stride + p;
   Stats s;
   stats_init(s);
   for (int g = lane; g < n_parts; g += kWave) s = stats_merge(s, partials[(int64_t)g * R_pad + p]);
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) s = stats_merge(s, stats_shfl_xor(s, o));
+  for (int x = 32; x > 0; x >>= 1) s = stats_merge(s, stats_shfl_xor(s, x));
   if (lane == 0) {
     float h, l;
     stats_finalize(s, h, l);
-    if (H) H[p] = h;
-    if (lse) lse[p] = l;
-    if (argmax) argmax[p] = s.ib;
+    if (H) H[o] = h;
+    if (lse) lse[o] = l;
+    if (argmax) argmax[o] = s.ib;
   }
 }
 

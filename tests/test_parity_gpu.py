@@ -144,6 +144,32 @@ def test_nan_row_is_defined_behaviour(B):
     B.eh_destroy(ctx)
 
 
+def test_eval_heads_equals_eval_per_head(B):
+    """The many-heads entry point against the oracle on one head and, bit for bit, against
+    eh_eval on every head (same kernels on the same data); also its one-head-at-a-time
+    fallback (fp32, and bf16 with at most 16 rows) and a second, smaller call on the same
+    context (the workspace is reused)."""
+    for dtype, rows in (("bf16", 100), ("bf16", 37), ("bf16", 9), ("f32", 40)):
+        w = G.scaled(G.CONFIGS["c2_calib"], d=256, V=3000, n_heads=4, rows=rows, dtype=dtype)
+        heads = G.make_heads(w, DEV)
+        hid = G.make_hidden(w, heads, DEV)
+        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=100)
+        n = 3
+        H = torch.full((n, rows), float("nan"), device=DEV)
+        lse = torch.full((n, rows), float("nan"), device=DEV)
+        am = torch.full((n, rows), -1, dtype=torch.int32, device=DEV)
+        B.eh_eval_heads(ctx, 1, n, hid.h[1:], rows, H, lse, am)
+        torch.cuda.synchronize()
+        for l in range(n):
+            H1, l1, a1 = _outs(rows)
+            B.eh_eval(ctx, 1 + l, hid.h[1 + l], rows, H1, l1, a1)
+            torch.cuda.synchronize()
+            assert torch.equal(H[l], H1) and torch.equal(lse[l], l1) and torch.equal(am[l], a1), (dtype, rows, l)
+        orc = P.oracle_head(hid.h[2], heads.gamma[2], heads.beta[2], heads.W[2], dtype == "bf16")
+        P.compare_head(f"heads/{dtype}/{rows}", H[1], lse[1], am[1], orc, [])
+        B.eh_destroy(ctx)
+
+
 def test_determinism(B):
     w = G.scaled(G.CONFIGS["c1_decode"], n_heads=2, rows=8)
     heads = G.make_heads(w, DEV)
