@@ -66,6 +66,22 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
 }
+// fp64 -> bf16 with a single round to nearest even.  Going through fp32 with two
+// roundings to nearest would be wrong whenever the fp32 value lands exactly on a bf16
+// tie (once in about 2^16 values): the first step therefore rounds to odd (truncate
+// toward zero, set the last bit if anything was lost), which leaves the second,
+// nearest-even rounding to 8 bits exact because fp32 carries 16 bits more than bf16.
+__device__ __forceinline__ uint32_t f64_to_bf16_bits(double y) {
+  float f = (float)y;
+  const double fd = (double)f;
+  if (fd != y && fd == fd) {  // inexact, not NaN
+    uint32_t u = __float_as_uint(f);
+    if (fabs(fd) > fabs(y)) u -= 1u;  // one step toward zero (sign-magnitude encoding)
+    u |= 1u;
+    f = __uint_as_float(u);
+  }
+  return f32_to_bf16_bits(f);
+}
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -73,7 +73,7 @@ template <>
 __device__ __forceinline__ frag_t pack_elems<DtBf16>(const double (&y)[8]) {
   uint32_t b[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) b[i] = f32_to_bf16_bits((float)y[i]);
+  for (int i = 0; i < 8; ++i) b[i] = f64_to_bf16_bits(y[i]);
   return mk_frag(b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16));
 }
 template <>

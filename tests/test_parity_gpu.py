@@ -42,7 +42,7 @@ def _eval_all(B, ctx, heads, hid, R, bf16, name, log, rows=None):
 # --------------------------------------------------------------- small shapes
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("V,d,R", [(1000, 200, 1), (1000, 200, 5), (4099 - 3, 96, 17), (777, 512, 37),
-                                    (2048, 256, 161), (16, 32, 16), (50, 8, 3)])
+                                    (2048, 256, 161), (16, 32, 16), (50, 8, 3), (1500, 160, 1000), (33, 64, 33)])
 def test_small_ragged_shapes(B, dtype, V, d, R):
     if dtype == "f32" and d % 4:
         pytest.skip("d must hold whole 16-byte groups")
@@ -87,6 +87,18 @@ def test_gather_and_device_row_count(B):
     orc = P.oracle_head(hid.h[0][sel], heads.gamma[0], heads.beta[0], heads.W[0], True)
     P.compare_head("gather", H[:9], lse[:9], am[:9], orc, [])
     assert torch.isnan(H[9:]).all() and (am[9:] == -7).all()     # dead positions untouched
+    # the same through the batched kernel (more than 16 positions): 40 positions, 25 live
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(5)
+    idx = torch.randint(0, 40, (40,), generator=gen).to(torch.int32).to(DEV)
+    n_dev = torch.tensor([25], dtype=torch.int32, device=DEV)
+    H, lse, am = _outs(40)
+    B.eh_eval(ctx, 0, hid.h[0], 40, H, lse, am, row_idx=idx, n_rows_dev=n_dev)
+    torch.cuda.synchronize()
+    sel = idx[:25].long()
+    orc = P.oracle_head(hid.h[0][sel], heads.gamma[0], heads.beta[0], heads.W[0], True)
+    P.compare_head("gather40", H[:25], lse[:25], am[:25], orc, [])
+    assert torch.isnan(H[25:]).all() and (am[25:] == -7).all()
     B.eh_destroy(ctx)
 
 
