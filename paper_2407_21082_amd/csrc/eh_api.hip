@@ -424,6 +424,50 @@ eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride, in
     const int64_t n = (int64_t)ctx->n_heads * n_rows;
     hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, H_out, n, NAN);
   }
+  if (ctx->bias.empty() && ctx->use_gemm) {
+    // Two launches per head: the batched projection, then one kernel that merges the partial
+    // statistics, applies the exit rule, appends the rows that go on to the next head's list
+    // and writes their LayerNorm for the next head.  Three live-row counters rotate: head l
+    // reads counter l%3, fills (l+1)%3 and clears (l+2)%3.
+    const bool bf = ctx->dtype == EH_BF16;
+    const int RB = bf ? 32 : 16;
+    const int R_pad = (n_rows + RB - 1) / RB * RB;
+    int* cnt = ctx->n_active[0];
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, cnt, (int64_t)3, 0);
+    {
+      dim3 g(R_pad), b(64);
+      if (bf)
+        hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, h_layers, row_stride, (const int*)nullptr,
+                           (const int*)nullptr, n_rows, R_pad, ctx->d, ctx->KS, ctx->gamma[0], ctx->beta[0],
+                           ctx->eps, ctx->yf);
+      else
+        hipLaunchKernelGGL((ln_pack_kernel<DtF32, 16>), g, b, 0, s, h_layers, row_stride, (const int*)nullptr,
+                           (const int*)nullptr, n_rows, R_pad, ctx->d, ctx->KS, ctx->gamma[0], ctx->beta[0],
+                           ctx->eps, ctx->yf);
+    }
+    for (int l = 0; l < ctx->n_heads; ++l) {
+      const int last = l == ctx->n_heads - 1 ? 1 : 0;
+      const int* idx = l == 0 ? nullptr : ctx->active[l & 1];
+      const int* live = l == 0 ? nullptr : cnt + l % 3;
+      int n_parts = 0;
+      if (bf) EH_HIP(ctx, gemm32_launch(ctx, l, live, n_rows, false, ctx->yf, ctx->partials, &n_parts, s));
+      else EH_HIP(ctx, gemm_launch(ctx, l, live, n_rows, false, ctx->yf, ctx->partials, &n_parts, s));
+      const void* hn = last ? nullptr : (const char*)h_layers + (int64_t)(l + 1) * layer_stride * esz;
+      const float* gn = last ? nullptr : ctx->gamma[l + 1];
+      const float* bn = last ? nullptr : ctx->beta[l + 1];
+      float* Hl = H_out ? H_out + (int64_t)l * n_rows : nullptr;
+#define EH_POST(DT, RBV)                                                                              \
+  hipLaunchKernelGGL((cascade_post_kernel<DT, RBV>), dim3(n_rows), dim3(64), 0, s, ctx->partials, n_parts, \
+                     R_pad, idx, live, n_rows, ctx->tau[l], last, l, exit_layer, token, Hl,            \
+                     (unsigned long long*)n_evals_out, ctx->active[(l + 1) & 1], cnt + (l + 1) % 3,    \
+                     cnt + (l + 2) % 3, hn, row_stride, ctx->d, ctx->KS, gn, bn, ctx->eps, ctx->yf)
+      if (bf) EH_POST(DtBf16, 32);
+      else EH_POST(DtF32, 16);
+#undef EH_POST
+    }
+    EH_HIP(ctx, hipGetLastError());
+    return EH_OK;
+  }
   for (int l = 0; l < ctx->n_heads; ++l) {
     const int* idx = l == 0 ? nullptr : ctx->active[(l - 1) & 1];
     const int* cnt = l == 0 ? nullptr : ctx->n_active[(l - 1) & 1];

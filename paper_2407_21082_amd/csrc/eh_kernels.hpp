@@ -202,30 +202,42 @@ __device__ __forceinline__ void wave_layernorm_cached(const void* row, int d, in
 // x 16 k for v_mfma_f32_32x32x16_bf16; lane l of fragment (block, k16) holds row
 // l%32, k = 16*k16 + 8*(l/32) .. +8).  R_pad is a multiple of RB; rows between
 // the live rows and R_pad are zero-filled.
+// Writes 16-byte chunk c of the row at position p of the activation workspace.
+template <int RB>
+__device__ __forceinline__ void put_chunk(frag_t* __restrict__ yf, int KS, int p, int c, const frag_t& v) {
+  const int nb = p / RB, n = p % RB;
+  // a block holds KS*4 chunks of 16 bytes per row either way
+  frag_t* dst = yf + (int64_t)nb * KS * kWave * (RB / 16);
+  if (RB == 16) dst[(c >> 2) * kWave + (c & 3) * 16 + n] = v;
+  else dst[(c >> 1) * kWave + (c & 1) * 32 + n] = v;
+}
+
+// LayerNorm of the row at `row` into position p (one wave).
+template <typename DT, int RB>
+__device__ __forceinline__ void ln_write_row(const void* __restrict__ row, int d, int KS,
+                                             const float* __restrict__ gamma,
+                                             const float* __restrict__ beta, float eps,
+                                             frag_t* __restrict__ yf, int p, int lane) {
+  static_assert(RB == 16 || (RB == 32 && DT::EPL == 8), "row block");
+  const int n_chunks = KS * 4;
+  auto put = [&](int c, const frag_t& v) { put_chunk<RB>(yf, KS, p, c, v); };
+  if (n_chunks <= kLnCache * kWave) wave_layernorm_cached<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+  else wave_layernorm<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+}
+
 template <typename DT, int RB>
 __device__ __forceinline__ void ln_pack_row(const void* __restrict__ h, int64_t row_stride,
                                             const int* __restrict__ row_idx, int n_live, int R_pad, int d,
                                             int KS, const float* __restrict__ gamma,
                                             const float* __restrict__ beta, float eps,
                                             frag_t* __restrict__ yf, int p, int lane) {
-  static_assert(RB == 16 || (RB == 32 && DT::EPL == 8), "row block");
   if (p >= R_pad) return;
-  const int nb = p / RB, n = p % RB;
-  const int n_chunks = KS * 4;
-  // a block holds KS*4 chunks of 16 bytes per row either way
-  frag_t* dst = yf + (int64_t)nb * KS * kWave * (RB / 16);
-  auto put = [&](int c, const frag_t& v) {
-    if (RB == 16) dst[(c >> 2) * kWave + (c & 3) * 16 + n] = v;
-    else dst[(c >> 1) * kWave + (c & 1) * 32 + n] = v;
-  };
   if (p >= n_live) {
-    for (int c = lane; c < n_chunks; c += kWave) put(c, mk_frag(0, 0, 0, 0));
+    for (int c = lane; c < KS * 4; c += kWave) put_chunk<RB>(yf, KS, p, c, mk_frag(0, 0, 0, 0));
     return;
   }
   const int64_t r = row_idx ? row_idx[p] : p;
-  const void* row = (const char*)h + r * row_stride * DT::ESZ;
-  if (n_chunks <= kLnCache * kWave) wave_layernorm_cached<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
-  else wave_layernorm<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+  ln_write_row<DT, RB>((const char*)h + r * row_stride * DT::ESZ, d, KS, gamma, beta, eps, yf, p, lane);
 }
 
 template <typename DT, int RB>
@@ -384,6 +396,58 @@ static __global__ __launch_bounds__(64) void finalize_kernel(const Stats* __rest
     if (lse) lse[o] = l;
     if (argmax) argmax[o] = s.ib;
   }
+}
+
+// ---------------------------------------------------------------------------
+// Cascade step behind a head's projection (Sections 3.4.1, 3.4.2), one wave per
+// position p of the head's active list: merge the partial statistics of the row,
+// apply the exit rule, and for a row that goes on append it to the next head's
+// active list and write its LayerNorm for the next head straight into the
+// activation workspace at the position it got.  Positions are handed out by an
+// atomic counter, so the next list is not in row order (nothing depends on the
+// order: rows are independent and every output is indexed by the row).  Positions
+// beyond the next head's live count keep whatever an earlier head left there; the
+// projection never lets a token column influence another.
+// ---------------------------------------------------------------------------
+template <typename DT, int RB>
+__global__ __launch_bounds__(64) void cascade_post_kernel(
+    const Stats* __restrict__ partials, int n_parts, int R_pad, const int* __restrict__ row_idx,
+    const int* __restrict__ n_rows_dev, int n_rows, float tau, int is_last, int head,
+    int* __restrict__ exit_layer,
+    int* __restrict__ token, float* __restrict__ H_out, unsigned long long* __restrict__ n_evals,
+    int* __restrict__ active_next, int* __restrict__ n_active_next, int* __restrict__ clear,
+    const void* __restrict__ h_next, int64_t row_stride, int d, int KS,
+    const float* __restrict__ gamma_next, const float* __restrict__ beta_next, float eps,
+    frag_t* __restrict__ yf) {
+  const int p = blockIdx.x, lane = threadIdx.x;
+  if (p == 0 && lane == 0 && clear) *clear = 0;  // the counter of the head after next
+  int n_live = n_rows;
+  if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  if (p >= n_live) return;
+  const int r = row_idx ? row_idx[p] : p;
+  Stats s;
+  stats_init(s);
+  for (int g = lane; g < n_parts; g += kWave) s = stats_merge(s, partials[(int64_t)g * R_pad + p]);
+#pragma unroll
+  for (int x = 32; x > 0; x >>= 1) s = stats_merge(s, stats_shfl_xor(s, x));
+  int pos = -1;
+  if (lane == 0) {
+    float H, l;
+    stats_finalize(s, H, l);
+    if (H_out) H_out[r] = H;
+    if (n_evals) atomicAdd(n_evals, 1ull);
+    if (is_last || H < tau) {  // NaN never passes the test
+      exit_layer[r] = head;
+      token[r] = s.ib;
+    } else {
+      pos = atomicAdd(n_active_next, 1);
+      active_next[pos] = r;
+    }
+  }
+  pos = __shfl(pos, 0);
+  if (pos < 0) return;
+  ln_write_row<DT, RB>((const char*)h_next + (int64_t)r * row_stride * DT::ESZ, d, KS, gamma_next, beta_next,
+                       eps, yf, pos, lane);
 }
 
 // ---------------------------------------------------------------------------
