@@ -26,6 +26,11 @@ What each function follows (arXiv 2407.21082):
   accepted prefix is committed and the first mismatch is replaced by the
   full-model token.
 
+* ``calibrate_threshold``: Section 3.4.1, "Calibration of Confidence Thresholds":
+  correctness t_j from eq. (2), the joint sort by confidence, the smallest index
+  whose suffix holds a proportion of correct predictions of at least epsilon,
+  and tau = the confidence value at that index, with entropy as the metric.
+
 Readings taken where the paper is silent (LayerNorm epsilon, biased variance,
 where bf16 rounding happens, strict inequality, alignment of draft and target
 positions) are listed in the repository's design notes; the ones that matter
@@ -275,3 +280,47 @@ def dssd_verify(f_final, draft, gamma, beta, W, draft_len=None, eps=1e-5, bf16=F
         accepted[b] = accepted_prefix(draft[b], target[b], L)
         nxt[b] = target[b, accepted[b]]
     return accepted, nxt, target, gap
+
+
+# ----------------------------------------------------------------------------
+# Threshold calibration (Section 3.4.1, "Calibration of Confidence Thresholds")
+# ----------------------------------------------------------------------------
+def correctness(pred_head, pred_model) -> np.ndarray:
+    """eq. (2): t_j = 1 where the head's prediction equals the underlying
+    model's prediction for the same token, else 0."""
+    return (np.asarray(pred_head) == np.asarray(pred_model)).astype(np.int64)
+
+
+def calibrate_threshold(H, t, epsilon: float):
+    """Entropy threshold of one head for the confidence level epsilon.
+
+    The confidence is c = -H (a prediction is the more confident the lower its
+    entropy).  Following Section 3.4.1 literally: take every calibration sample
+    j in turn as the candidate threshold, look at ALL samples whose confidence
+    is at least c_j (entropy at most H_j), and compute the proportion of
+    correct predictions among them; among the candidates whose proportion is at
+    least epsilon take the one that comes first in ascending order of
+    confidence, i.e. the largest entropy.  tau is that sample's entropy.
+
+    Readings: (i) the suffix of a candidate holds every sample with confidence
+    "higher (or equal)", so samples tied with the candidate are all in it and
+    the result does not depend on how ties are ordered; (ii) if no candidate
+    qualifies the head never exits: tau = -inf; (iii) a NaN entropy is no
+    candidate and belongs to no suffix (such a row never passes the exit test);
+    (iv) the proportion test is `correct >= epsilon * size` in float64.
+
+    Quadratic on purpose (two nested sweeps, no sort, no running sums).
+    Returns (tau, n) with n the number of samples with H <= tau.
+    """
+    H = np.asarray(H, dtype=np.float64)
+    t = np.asarray(t)
+    best_H, best_n = -np.inf, 0
+    for j in range(H.shape[0]):
+        if np.isnan(H[j]):
+            continue
+        inside = H <= H[j]                       # NaN compares false: never inside
+        size = int(np.count_nonzero(inside))
+        correct = int(np.count_nonzero(t[inside]))
+        if float(correct) >= float(epsilon) * float(size) and H[j] > best_H:
+            best_H, best_n = float(H[j]), size
+    return best_H, best_n

@@ -347,3 +347,112 @@ def test_dssd_verify_planted_targets():
     np.testing.assert_array_equal(nxt, [tgt[0, 0], tgt[1, 2], tgt[2, 3], tgt[3, 4], tgt[4, 2], tgt[5, 0]])
     acc2, _, _, _ = O.dssd_verify(f, draft, g, b, W)
     np.testing.assert_array_equal(acc2, [0, 2, 3, 4, 4, 4])
+
+
+# ------------------------------------------------------------------ threshold calibration
+def _calibrate_by_sorting(H, t, eps):
+    """The paper's procedure step by step (Section 3.4.1): sort jointly by ascending
+    confidence c = -H, take suffix proportions with running sums, pick the smallest index
+    that qualifies.  Only equal to the definition when no two entropies tie."""
+    H = np.asarray(H, dtype=np.float64)
+    order = np.argsort(-H, kind="stable")            # ascending confidence = descending entropy
+    Hs, ts = H[order], np.asarray(t)[order]
+    M = len(Hs)
+    suffix_correct = np.cumsum(ts[::-1])[::-1]
+    for j in range(M):
+        if suffix_correct[j] >= eps * (M - j):
+            return float(Hs[j]), M - j
+    return -np.inf, 0
+
+
+def test_calibration_worked_example():
+    # entropies descending: 2.0(wrong) 1.0(wrong) 0.5(wrong) 0.5(right) 0.1(right)
+    # proportions of correct from each value on: 2/5, 2/4, 2/3 (both 0.5 tied), 1/1
+    H = [0.1, 0.5, 0.5, 1.0, 2.0]
+    t = [1, 1, 0, 0, 0]
+    assert O.calibrate_threshold(H, t, 0.0) == (2.0, 5)
+    assert O.calibrate_threshold(H, t, 0.4) == (2.0, 5)
+    assert O.calibrate_threshold(H, t, 0.5) == (1.0, 4)
+    assert O.calibrate_threshold(H, t, 0.625) == (0.5, 3)
+    assert O.calibrate_threshold(H, t, 0.75) == (0.1, 1)
+    assert O.calibrate_threshold(H, t, 1.0) == (0.1, 1)
+
+
+def test_calibration_degenerate_sets():
+    rng = np.random.default_rng(3)
+    H = rng.uniform(0.0, 5.0, size=40)
+    for eps in (0.0, 0.3, 1.0):
+        assert O.calibrate_threshold(H, np.ones(40, dtype=int), eps) == (float(H.max()), 40)
+    assert O.calibrate_threshold(H, np.zeros(40, dtype=int), 0.0) == (float(H.max()), 40)
+    for eps in (1e-9, 0.5, 1.0):
+        assert O.calibrate_threshold(H, np.zeros(40, dtype=int), eps) == (-np.inf, 0)
+    assert O.calibrate_threshold([], [], 0.5) == (-np.inf, 0)
+
+
+def test_calibration_matches_the_sorting_procedure_without_ties():
+    rng = np.random.default_rng(11)
+    for trial in range(60):
+        M = int(rng.integers(1, 80))
+        H = rng.permutation(M).astype(np.float64) * 0.07 + 0.01        # distinct
+        t = (rng.random(M) < (0.9 - 0.1 * H / H.max() * 8).clip(0.05, 0.95)).astype(int)
+        for eps in (0.0, 0.25, 0.5, 0.7, 0.9, 1.0):
+            assert O.calibrate_threshold(H, t, eps) == _calibrate_by_sorting(H, t, eps), (trial, eps)
+
+
+def test_calibration_guarantee_minimality_monotonicity_permutation():
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        M = int(rng.integers(2, 60))
+        H = np.round(rng.uniform(0, 3, size=M), 1)                      # many ties
+        t = (rng.random(M) < np.exp(-H)).astype(int)
+        prev = np.inf
+        for eps in (0.0, 0.2, 0.4, 0.6, 0.8, 1.0):
+            tau, n = O.calibrate_threshold(H, t, eps)
+            assert tau <= prev                                           # stricter level, lower threshold
+            prev = tau
+            if tau == -np.inf:
+                assert n == 0
+                assert all(t[H <= v].sum() < eps * (H <= v).sum() for v in np.unique(H))
+                continue
+            kept = H <= tau
+            assert n == kept.sum() and t[kept].sum() >= eps * n          # the guarantee
+            for v in np.unique(H[H > tau]):                              # nothing larger qualifies
+                assert t[H <= v].sum() < eps * (H <= v).sum()
+            perm = rng.permutation(M)
+            assert O.calibrate_threshold(H[perm], t[perm], eps) == (tau, n)
+
+
+def test_calibration_ties_do_not_depend_on_their_order():
+    # three samples tie at 1.0: right, wrong, wrong.  Taken as a whole 1/3 of them are right.
+    # An index-based suffix could start between them (after the wrong ones) and see 1/1.
+    H = np.array([1.0, 1.0, 1.0, 2.0])
+    for t in ([1, 0, 0, 0], [0, 1, 0, 0], [0, 0, 1, 0]):
+        assert O.calibrate_threshold(H, t, 0.5) == (-np.inf, 0)
+        assert O.calibrate_threshold(H, t, 1 / 3) == (1.0, 3)
+        assert O.calibrate_threshold(H, t, 0.25) == (2.0, 4)
+
+
+def test_calibration_ignores_nan_entropies():
+    H = np.array([np.nan, 0.2, 0.9, np.nan, 0.4])
+    t = np.array([1, 1, 0, 1, 1])
+    assert O.calibrate_threshold(H, t, 0.6) == (0.9, 3)                   # 2 of the 3 finite ones
+    assert O.calibrate_threshold(H, t, 0.7) == (0.4, 2)
+    assert O.calibrate_threshold([np.nan, np.nan], [1, 1], 0.0) == (-np.inf, 0)
+
+
+def test_calibration_exhaustive_small():
+    from fractions import Fraction
+    values = (0.25, 0.5, 0.5, 1.5, 1.5, 3.0)                             # fixed entropies with ties
+    for t in itertools.product((0, 1), repeat=len(values)):
+        for eps in (Fraction(0), Fraction(1, 4), Fraction(1, 2), Fraction(3, 4), Fraction(1)):
+            want = (-np.inf, 0)
+            for v in sorted(set(values), reverse=True):
+                inside = [tj for hj, tj in zip(values, t) if hj <= v]
+                if Fraction(sum(inside), len(inside)) >= eps:
+                    want = (v, len(inside))
+                    break
+            assert O.calibrate_threshold(values, t, float(eps)) == want
+
+
+def test_correctness_indicator():
+    np.testing.assert_array_equal(O.correctness([3, 1, 4, 1], [3, 1, 5, 9]), [1, 1, 0, 0])
