@@ -183,6 +183,31 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft,
                       int32_t* next_token, int32_t* target, void* stream);
 
 /*
+ * Threshold calibration of one head (Section 3.4.1, "Calibration of Confidence
+ * Thresholds"), entropy as the confidence metric: the M calibration tokens are
+ * ordered by ascending confidence (descending entropy); for a level epsilon the
+ * threshold is the entropy of the first token in that order such that, among all
+ * tokens at least as confident, the proportion whose prediction equals the
+ * model's (eq. (2)) is at least epsilon.  Tokens with equal entropy are taken as
+ * a whole; NaN entropies are ignored; if no token qualifies tau = -inf (the head
+ * never exits).  The value returned is the paper's tau, to be used as
+ * "exit if H <= tau"; eh_exit_decide tests H < tau, so pass nextafterf(tau, +inf)
+ * there to let the boundary token exit as well.
+ *
+ * H            device [M] float, e.g. one row of eh_eval_heads' output
+ * pred, ref    device [M] int32: the head's and the full model's argmax
+ * M            0 <= M < 2^31
+ * eps          host [n_eps] double, each in [0, 1]; 0 <= n_eps <= 64
+ * tau_out      device [n_eps] float
+ * n_exit_out   NULL or device [n_eps] int64: tokens with H <= tau
+ * Allocates about 20 * M bytes of scratch memory for the call and synchronises
+ * `stream` before returning.
+ */
+eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const int32_t* ref, int64_t M,
+                       const double* eps, int32_t n_eps, float* tau_out, int64_t* n_exit_out,
+                       void* stream);
+
+/*
  * Waits for `stream` and reports failures that only the device can see: the
  * persistent decode kernel (used for calls with at most 16 rows) waits for other
  * workgroups with a bounded spin, and a timeout there sets a sticky flag in the

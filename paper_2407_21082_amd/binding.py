@@ -24,7 +24,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
 
 # every symbol include/eh.h declares
 EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_exit_decide", "eh_cascade", "dssd_verify",
-           "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
+           "eh_calibrate", "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
 
 
 class EhError(RuntimeError):
@@ -56,6 +56,7 @@ def _load() -> C.CDLL:
     lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, f32, vp]
     lib.eh_cascade.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.eh_calibrate.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double), i32, vp, vp, vp]
     lib.eh_check.argtypes = [vp, vp]
     lib.eh_decode_trace.argtypes = [vp, i32, vp, i32]
     lib.eh_decode_trace.restype = C.c_int
@@ -178,6 +179,15 @@ def eh_cascade(ctx: EhContext, h_layers: torch.Tensor, n_rows: int, exit_layer: 
     _check(lib.eh_cascade(ctx.handle, _ptr(h_layers), h_layers.stride(0), h_layers.stride(1), n_rows,
                           _ptr(exit_layer), _ptr(token), _ptr(H_out), _ptr(n_evals_out),
                           _stream(stream)), ctx.handle)
+
+
+def eh_calibrate(ctx: EhContext, H: torch.Tensor, pred: torch.Tensor, ref: torch.Tensor, eps,
+                 tau_out: torch.Tensor, n_exit_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """H, pred, ref: device [M]; eps: sequence of floats in [0, 1]; tau_out: device [len(eps)] float32;
+    n_exit_out: device [len(eps)] int64 or None."""
+    arr = (C.c_double * len(eps))(*[float(e) for e in eps])
+    _check(lib.eh_calibrate(ctx.handle, _ptr(H), _ptr(pred), _ptr(ref), H.numel(), arr, len(eps),
+                            _ptr(tau_out), _ptr(n_exit_out), _stream(stream)), ctx.handle)
 
 
 def eh_check(ctx: EhContext, stream=None) -> None:

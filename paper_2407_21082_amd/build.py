@@ -18,7 +18,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libeh.so")
 PROBE = os.path.join(PKG, "mfma_probe")   # stand-alone matrix-core rate probe (csrc/mfma_probe.hip)
-SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip", "eh_gemm32.hip"]
+SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip", "eh_gemm32.hip", "eh_calib.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -508,6 +508,28 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, co
   return EH_OK;
 }
 
+eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const int32_t* ref, int64_t M,
+                       const double* eps, int32_t n_eps, float* tau_out, int64_t* n_exit_out, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (n_eps < 0 || n_eps > 64) return fail(ctx, EH_ERR_RANGE, "n_eps outside [0, 64]");
+  if (M < 0 || M >= ((int64_t)1 << 31)) return fail(ctx, EH_ERR_SHAPE, "M outside [0, 2^31)");
+  if (n_eps == 0) return EH_OK;
+  if (!eps || !tau_out || (M > 0 && (!H || !pred || !ref))) return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
+  for (int i = 0; i < n_eps; ++i)
+    if (!(eps[i] >= 0.0 && eps[i] <= 1.0)) return fail(ctx, EH_ERR_RANGE, "epsilon outside [0, 1]");
+  DeviceGuard guard(ctx->device);
+  hipStream_t s = (hipStream_t)stream;
+  if (M == 0) {
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(1), dim3(64), 0, s, tau_out, (int64_t)n_eps, -INFINITY);
+    if (n_exit_out)
+      hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(128), 0, s, (int*)n_exit_out, (int64_t)2 * n_eps, 0);
+    EH_HIP(ctx, hipGetLastError());
+    return EH_OK;
+  }
+  EH_HIP(ctx, calibrate_run(H, pred, ref, M, eps, n_eps, tau_out, (long long*)n_exit_out, s));
+  return EH_OK;
+}
+
 eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n) {
   if (!ctx) return EH_ERR_NULL;
   if (!ctx->dec_trace) return fail(ctx, EH_ERR_RANGE, "this context has no decode kernel");

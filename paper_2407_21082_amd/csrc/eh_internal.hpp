@@ -90,6 +90,10 @@ hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n
 // order (ln_pack_kernel<DtBf16, 32>), partials are [*n_parts][n_rows rounded up to 32].
 hipError_t gemm32_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
                          const eh::frag_t* yf, eh::Stats* partials, int* n_parts, hipStream_t s);
+// Threshold calibration of one head (eh_calib.hip): device inputs, host eps, device outputs;
+// allocates its scratch memory and synchronises the stream before freeing it.
+hipError_t calibrate_run(const float* H, const int* pred, const int* ref, int64_t M, const double* eps,
+                         int n_eps, float* tau_out, long long* n_exit_out, hipStream_t s);
 // Enqueues the decode kernel.
 hipError_t decode_launch(const eh_ctx* ctx, const DecodeParams& p, hipStream_t s);
 

@@ -353,3 +353,79 @@ def test_c4_dssd_verify(B, big):
     np.testing.assert_array_equal(nxt.cpu().numpy(), nxt_t)
     print(f"c4: accepted {acc_o.tolist()} mean {acc_o.mean():.2f}; agreement {case.agree[:, :k].float().mean().item():.2f}")
     B.eh_destroy(ctx)
+
+
+# --------------------------------------------------------------- threshold calibration
+EPS_SWEEP = [0.5, 0.55, 0.6, 0.65, 0.7, 0.75, 0.8, 0.85, 0.9, 0.95, 1.0]
+
+
+def _calibrate(B, ctx, H, pred, ref, eps):
+    tau = torch.full((len(eps),), float("nan"), device=DEV)
+    n = torch.full((len(eps),), -1, dtype=torch.int64, device=DEV)
+    B.eh_calibrate(ctx, H, pred, ref, eps, tau, n)
+    torch.cuda.synchronize()
+    return tau.cpu().numpy(), n.cpu().numpy()
+
+
+@pytest.fixture(scope="module")
+def small_ctx(B):
+    w = G.Workload("calib", d=64, V=64, n_heads=1, rows=4, dtype="bf16", seed=1)
+    heads = G.make_heads(w, DEV)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")], max_rows=4)
+    yield ctx
+    B.eh_destroy(ctx)
+
+
+@pytest.mark.parametrize("M,ties,nan_every", [(1, False, 0), (2, True, 0), (257, False, 0), (1000, True, 0),
+                                              (2500, False, 7), (3000, True, 5)])
+def test_calibrate_matches_oracle(B, small_ctx, M, ties, nan_every):
+    """Bit-exact: the threshold is one of the input entropies and the count is an integer."""
+    H, pred, ref = G.make_calibration_case(M, DEV, seed=M, V=50, ties=ties, nan_every=nan_every)
+    eps = [0.0, 0.01] + EPS_SWEEP
+    tau, n = _calibrate(B, small_ctx, H, pred, ref, eps)
+    Hc = H.cpu().numpy().astype(np.float64)
+    t = O.correctness(pred.cpu().numpy(), ref.cpu().numpy())
+    for i, e in enumerate(eps):
+        want_tau, want_n = O.calibrate_threshold(Hc, t, e)
+        assert (tau[i] == np.float32(want_tau)) and int(n[i]) == want_n, (M, e, tau[i], want_tau, n[i], want_n)
+
+
+def test_calibrate_degenerate_inputs(B, small_ctx):
+    H = torch.tensor([0.5, 0.25, 2.0, 0.0, -0.0], device=DEV)
+    same = torch.zeros(5, dtype=torch.int32, device=DEV)
+    tau, n = _calibrate(B, small_ctx, H, same, same, [0.0, 1.0])          # all right
+    assert list(tau) == [2.0, 2.0] and list(n) == [5, 5]
+    tau, n = _calibrate(B, small_ctx, H, same, same + 1, [0.0, 0.5, 1.0])  # all wrong
+    assert tau[0] == 2.0 and n[0] == 5 and np.isneginf(tau[1:]).all() and list(n[1:]) == [0, 0]
+    right_at_zero = torch.tensor([1, 1, 1, 0, 0], dtype=torch.int32, device=DEV)
+    tau, n = _calibrate(B, small_ctx, H, same, right_at_zero, [1.0])       # +0 and -0 are one value
+    assert tau[0] == 0.0 and n[0] == 2
+    allnan = torch.full((9,), float("nan"), device=DEV)
+    nine = torch.zeros(9, dtype=torch.int32, device=DEV)
+    tau, n = _calibrate(B, small_ctx, allnan, nine, nine, [0.0, 0.5])
+    assert np.isneginf(tau).all() and list(n) == [0, 0]
+    tau, n = _calibrate(B, small_ctx, H[:0], same[:0], same[:0], [0.3])    # empty set
+    assert np.isneginf(tau).all() and list(n) == [0]
+
+
+def test_calibrate_large_set_properties(B, small_ctx):
+    """2^22 tokens, beyond what the quadratic oracle can do: the definition is evaluated by
+    exact counting instead (tokens and correct tokens at or below every distinct entropy
+    value, from sorted arrays), which gives the unique answer for every level."""
+    M = 1 << 22
+    H, pred, ref = G.make_calibration_case(M, DEV, seed=3, ties=True, nan_every=1001)
+    tau, n = _calibrate(B, small_ctx, H, pred, ref, EPS_SWEEP)
+    Hc = H.cpu().numpy().astype(np.float64)
+    t = O.correctness(pred.cpu().numpy(), ref.cpu().numpy())
+    ok = ~np.isnan(Hc)
+    vals, inv = np.unique(Hc[ok], return_inverse=True)                     # ascending entropy values
+    cnt = np.bincount(inv, minlength=len(vals)).cumsum()                   # tokens with H <= value
+    cor = np.bincount(inv, weights=t[ok], minlength=len(vals)).cumsum()    # correct ones among them
+    for i, e in enumerate(EPS_SWEEP):
+        good = cor >= e * cnt
+        if not good.any():
+            assert np.isneginf(tau[i]) and n[i] == 0
+            continue
+        k = np.nonzero(good)[0].max()                                      # largest qualifying value
+        assert tau[i] == np.float32(vals[k]) and n[i] == cnt[k], (e, tau[i], vals[k])
+    assert (np.diff(tau) <= 0).all()

@@ -240,6 +240,28 @@ def make_verify_case(w: Workload, heads: Heads, draft: torch.Tensor, device="cpu
     return VerifyCase(hid.h[0].reshape(B, k + 1, w.d).contiguous(), agree, planted)
 
 
+def make_calibration_case(M: int, device="cpu", seed: int = 0, V: int = V_PYTHIA, ties: bool = False,
+                          nan_every: int = 0):
+    """Synthetic calibration set of one head (Section 3.4.1): entropies H[M] (float32, spread
+    like a head's over text: a gamma-shaped bulk below ln V), the head's and the model's
+    predictions pred[M], ref[M] (int32), with agreement the likelier the lower the entropy.
+    ties=True quantises the entropies so that many tokens share a value; nan_every > 0 plants a
+    NaN entropy at every nan_every-th token."""
+    gen = _gen(device, 7919 * seed + 17)
+    u = torch.rand((3, M), generator=gen, device=device)
+    H = (-(torch.log(u[0].clamp_min(1e-12)) + torch.log(u[1].clamp_min(1e-12))) * 0.9).clamp(max=math.log(V))
+    if ties:
+        H = torch.round(H * 8) / 8
+    H = H.to(torch.float32)
+    p_agree = torch.exp(-0.9 * H)
+    ref = torch.randint(0, V, (M,), generator=gen, device=device, dtype=torch.int64)
+    other = (ref + 1 + torch.randint(0, V - 1, (M,), generator=gen, device=device, dtype=torch.int64)) % V
+    pred = torch.where(u[2] < p_agree, ref, other)
+    if nan_every > 0:
+        H[::nan_every] = float("nan")
+    return H.contiguous(), pred.to(torch.int32).contiguous(), ref.to(torch.int32).contiguous()
+
+
 # ---------------------------------------------------------------- conversions
 def to_f64_numpy(t: torch.Tensor):
     """The exact stored values of a tensor as a float64 numpy array (host)."""
