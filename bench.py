@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c1_decode",
-                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify"])
+                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify", "f1_calibrate"])
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per bench step (c1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -78,6 +78,76 @@ def oracle_threads():
         return os.cpu_count() or 1
 
 
+def bench_calibrate(args, torch, B, G, dev):
+    """Threshold calibration of one head (the step after config 2 in the paper's pipeline):
+    M = 2^24 calibration tokens, the paper's sweep of 11 confidence levels in one call."""
+    import numpy as np
+    M = 1 << 24
+    eps = [0.5 + 0.05 * i for i in range(11)]
+    t_setup = time.time()
+    w = G.Workload("calib", d=64, V=64, n_heads=1, rows=4, dtype="bf16", seed=1)
+    heads = G.make_heads(w, dev)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")], max_rows=4)
+    sets = [G.make_calibration_case(M, dev, seed=s, ties=False) for s in range(2)]
+    tau = torch.zeros(len(eps), device=dev)
+    n_exit = torch.zeros(len(eps), dtype=torch.int64, device=dev)
+
+    def step(i):
+        H, pred, ref = sets[i % len(sets)]
+        B.eh_calibrate(ctx, H, pred, ref, eps, tau, n_exit)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ev_s = ev0.elapsed_time(ev1) * 1e-3
+    value = args.steps * M / dt
+    # algorithmic bytes: each token's entropy and two predictions are read once (12 B); the
+    # 11 thresholds and counts written are negligible.  The call as a whole is timed (sort,
+    # scan, search and its own allocation and synchronisation).
+    bytes_per_launch = 12.0 * M
+    avg_s = ev_s / args.steps
+    roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+            "kernel": "eh_calibrate (key transform + rocPRIM radix sort of pairs + scan + search)",
+            "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": args.steps}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import eh_oracle as O
+        m = 12000                                  # the oracle is quadratic: a bounded sample
+        H, pred, ref = G.make_calibration_case(m, "cpu", seed=0)
+        Hc = H.numpy().astype(np.float64)
+        t = O.correctness(pred.numpy(), ref.numpy())
+        c0 = time.perf_counter()
+        n_lv = 0
+        for e in eps:
+            O.calibrate_threshold(Hc, t, e)
+            n_lv += 1
+            if time.perf_counter() - c0 > args.cpu_seconds:
+                break
+        cdt = time.perf_counter() - c0
+        cpu = {"value": m * n_lv / len(eps) / cdt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": f"{m} tokens, {n_lv} of {len(eps)} levels ({cdt:.1f} s); the oracle is the literal "
+                         "quadratic definition, so its rate falls with the size of the set"}
+    B.eh_destroy(ctx)
+    line = {"metric": "calibration_tokens_per_sec", "value": value, "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+            "data": "synthetic",
+            "config": {"workload": f"f1_calibrate: one head, M = {M} calibration tokens, {len(eps)} confidence "
+                                   "levels 0.5 ... 1.0 per call", "tau": [float(x) for x in tau.cpu()]},
+            "roofline": roof, "cpu_baseline": cpu, "setup_s": round(time.time() - t_setup, 1)}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -107,6 +177,8 @@ def main():
         print(json.dumps({"copy_calibration": {"kernel": "torch.add(uint8, 1) elementwise",
                                                "bytes_read": n, "bytes_written": n, "copies": 10}}))
         return
+    if args.workload == "f1_calibrate":
+        return bench_calibrate(args, torch, B, G, dev)
     w = G.CONFIGS[args.workload]
     if args.library_gemm:
         R = max(w.rows, 16)

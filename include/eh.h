@@ -200,8 +200,9 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft,
  * eps          host [n_eps] double, each in [0, 1]; 0 <= n_eps <= 64
  * tau_out      device [n_eps] float
  * n_exit_out   NULL or device [n_eps] int64: tokens with H <= tau
- * Allocates about 20 * M bytes of scratch memory for the call and synchronises
- * `stream` before returning.
+ * Asynchronous on `stream`.  Uses about 20 * M bytes of scratch memory that the
+ * context keeps until eh_destroy; a call with a larger M than any before grows it,
+ * which synchronises the device.
  */
 eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const int32_t* ref, int64_t M,
                        const double* eps, int32_t n_eps, float* tau_out, int64_t* n_exit_out,

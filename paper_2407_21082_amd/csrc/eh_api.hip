@@ -66,6 +66,8 @@ hipError_t dev_alloc(eh_ctx* ctx, T** p, size_t count) {
 void free_all(eh_ctx* ctx) {
   for (void* p : ctx->allocs) (void)hipFree(p);
   ctx->allocs.clear();
+  if (ctx->calib.buf) (void)hipFree(ctx->calib.buf);
+  ctx->calib = CalibScratch();
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -526,7 +528,7 @@ eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const i
     EH_HIP(ctx, hipGetLastError());
     return EH_OK;
   }
-  EH_HIP(ctx, calibrate_run(H, pred, ref, M, eps, n_eps, tau_out, (long long*)n_exit_out, s));
+  EH_HIP(ctx, calibrate_run(ctx->calib, H, pred, ref, M, eps, n_eps, tau_out, (long long*)n_exit_out, s));
   return EH_OK;
 }
 

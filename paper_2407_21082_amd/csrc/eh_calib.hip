@@ -65,11 +65,23 @@ __global__ void calib_init_kernel(unsigned* __restrict__ best, int n, unsigned M
   if ((int)threadIdx.x < n) best[threadIdx.x] = M;
 }
 
-// keys ascending, prefix = inclusive running count of correct tokens in that order
-__global__ __launch_bounds__(256) void calib_search_kernel(const uint32_t* __restrict__ keys,
-                                                           const uint32_t* __restrict__ prefix, int64_t M,
-                                                           EpsList eps, unsigned* __restrict__ best) {
+// keys ascending, prefix = inclusive running count of correct tokens in that order.
+// Workgroups of 1024 positions.  Only a position before the best one found so far can
+// improve it, and positions are visited roughly in ascending order: the workgroup reads
+// the current bests once (possibly stale, which only costs a redundant atomic) and skips
+// every level that is already settled before its first position.
+__global__ __launch_bounds__(1024) void calib_search_kernel(const uint32_t* __restrict__ keys,
+                                                            const uint32_t* __restrict__ prefix, int64_t M,
+                                                            EpsList eps, unsigned* __restrict__ best) {
+  __shared__ unsigned cur[kMaxEps];
+  __shared__ unsigned wg_min[kMaxEps];
+  if ((int)threadIdx.x < eps.n) {
+    cur[threadIdx.x] = __builtin_nontemporal_load(&best[threadIdx.x]);
+    wg_min[threadIdx.x] = 0xFFFFFFFFu;
+  }
+  __syncthreads();
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const unsigned wg_first = (unsigned)((int64_t)blockIdx.x * blockDim.x);
   const int lane = threadIdx.x & 63;
   bool cand = false;
   double sc = 0.0, n = 0.0;
@@ -82,12 +94,17 @@ __global__ __launch_bounds__(256) void calib_search_kernel(const uint32_t* __res
       n = (double)(M - j);
     }
   }
+  bool any = false;
   for (int e = 0; e < eps.n; ++e) {
-    unsigned m = (cand && sc >= eps.v[e] * n) ? (unsigned)j : 0xFFFFFFFFu;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = min(m, (unsigned)__shfl_xor((int)m, o));
-    if (lane == 0 && m != 0xFFFFFFFFu) atomicMin(&best[e], m);
+    if (cur[e] <= wg_first) continue;  // uniform over the workgroup
+    any = true;
+    // lanes hold ascending positions: the first lane that qualifies is the wave's minimum
+    const unsigned long long q = __ballot(cand && sc >= eps.v[e] * n);
+    if (lane == 0 && q) atomicMin(&wg_min[e], (unsigned)(j + __builtin_ctzll(q)));
   }
+  if (!any) return;  // uniform
+  __syncthreads();
+  if ((int)threadIdx.x < eps.n && wg_min[threadIdx.x] != 0xFFFFFFFFu) atomicMin(&best[threadIdx.x], wg_min[threadIdx.x]);
 }
 
 __global__ void calib_read_kernel(const uint32_t* __restrict__ keys, const unsigned* __restrict__ best, int n,
@@ -101,46 +118,50 @@ __global__ void calib_read_kernel(const uint32_t* __restrict__ keys, const unsig
 
 }  // namespace
 
-hipError_t calibrate_run(const float* H, const int* pred, const int* ref, int64_t M, const double* eps,
-                         int n_eps, float* tau_out, long long* n_exit_out, hipStream_t s) {
+hipError_t calibrate_run(CalibScratch& sc, const float* H, const int* pred, const int* ref, int64_t M,
+                         const double* eps, int n_eps, float* tau_out, long long* n_exit_out, hipStream_t s) {
   EpsList el;
   el.n = n_eps;
   for (int i = 0; i < n_eps; ++i) el.v[i] = eps[i];
-  uint32_t* buf = nullptr;   // keys_in, vals_in, keys_out, vals_out, prefix
-  unsigned* best = nullptr;
-  void* tmp = nullptr;
-  hipError_t e = hipMalloc(&buf, sizeof(uint32_t) * 5 * (size_t)M);
-  if (e != hipSuccess) return e;
-  e = hipMalloc(&best, sizeof(unsigned) * kMaxEps);
-  uint32_t *k0 = buf, *v0 = buf + M, *k1 = buf + 2 * M, *v1 = buf + 3 * M, *pf = buf + 4 * M;
   size_t tmp_sort = 0, tmp_scan = 0;
-  if (e == hipSuccess) e = rocprim::radix_sort_pairs(nullptr, tmp_sort, k0, k1, v0, v1, (size_t)M, 0u, 32u, s);
+  hipError_t e = rocprim::radix_sort_pairs(nullptr, tmp_sort, (uint32_t*)nullptr, (uint32_t*)nullptr,
+                                           (uint32_t*)nullptr, (uint32_t*)nullptr, (size_t)M, 0u, 32u, s);
   if (e == hipSuccess)
-    e = rocprim::inclusive_scan(nullptr, tmp_scan, v1, pf, (size_t)M, rocprim::plus<uint32_t>(), s);
-  const size_t tmp_bytes = tmp_sort > tmp_scan ? tmp_sort : tmp_scan;
-  if (e == hipSuccess) e = hipMalloc(&tmp, tmp_bytes ? tmp_bytes : 16);
-  if (e == hipSuccess) {
-    const unsigned grid = (unsigned)((M + 255) / 256);
-    hipLaunchKernelGGL(calib_keys_kernel, dim3(grid), dim3(256), 0, s, H, pred, ref, M, k0, v0);
-    size_t ts = tmp_bytes;
-    e = rocprim::radix_sort_pairs(tmp, ts, k0, k1, v0, v1, (size_t)M, 0u, 32u, s);
-    ts = tmp_bytes;
-    if (e == hipSuccess) e = rocprim::inclusive_scan(tmp, ts, v1, pf, (size_t)M, rocprim::plus<uint32_t>(), s);
-    if (e == hipSuccess) {
-      hipLaunchKernelGGL(calib_init_kernel, dim3(1), dim3(kMaxEps), 0, s, best, n_eps, (unsigned)M);
-      hipLaunchKernelGGL(calib_search_kernel, dim3(grid), dim3(256), 0, s, k1, pf, M, el, best);
-      hipLaunchKernelGGL(calib_read_kernel, dim3(1), dim3(kMaxEps), 0, s, k1, best, n_eps, (unsigned)M, tau_out,
-                         n_exit_out);
-      e = hipGetLastError();
-    }
+    e = rocprim::inclusive_scan(nullptr, tmp_scan, (uint32_t*)nullptr, (uint32_t*)nullptr, (size_t)M,
+                                rocprim::plus<uint32_t>(), s);
+  if (e != hipSuccess) return e;
+  const size_t tmp_bytes = ((tmp_sort > tmp_scan ? tmp_sort : tmp_scan) + 255) & ~(size_t)255;
+  // one buffer: keys_in, vals_in, keys_out, vals_out, prefix (M words each), bests, primitive scratch
+  const size_t words = 5 * (size_t)M + kMaxEps;
+  const size_t need = words * sizeof(uint32_t) + 256 + tmp_bytes;
+  if (sc.bytes < need) {
+    // grow only; an earlier call may still be using the old buffer on some stream
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) return e;
+    if (sc.buf) (void)hipFree(sc.buf);
+    sc.buf = nullptr;
+    sc.bytes = 0;
+    e = hipMalloc(&sc.buf, need);
+    if (e != hipSuccess) return e;
+    sc.bytes = need;
   }
-  // the scratch buffers are freed here, so the work has to be finished first
-  const hipError_t es = hipStreamSynchronize(s);
-  if (e == hipSuccess) e = es;
-  if (tmp) (void)hipFree(tmp);
-  if (best) (void)hipFree(best);
-  (void)hipFree(buf);
-  return e;
+  uint32_t* buf = (uint32_t*)sc.buf;
+  uint32_t *k0 = buf, *v0 = buf + M, *k1 = buf + 2 * M, *v1 = buf + 3 * M, *pf = buf + 4 * M;
+  unsigned* best = buf + 5 * M;
+  void* tmp = (char*)sc.buf + ((words * sizeof(uint32_t) + 255) & ~(size_t)255);
+  const unsigned grid = (unsigned)((M + 255) / 256);
+  hipLaunchKernelGGL(calib_keys_kernel, dim3(grid), dim3(256), 0, s, H, pred, ref, M, k0, v0);
+  size_t ts = tmp_bytes;
+  e = rocprim::radix_sort_pairs(tmp, ts, k0, k1, v0, v1, (size_t)M, 0u, 32u, s);
+  ts = tmp_bytes;
+  if (e == hipSuccess) e = rocprim::inclusive_scan(tmp, ts, v1, pf, (size_t)M, rocprim::plus<uint32_t>(), s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(calib_init_kernel, dim3(1), dim3(kMaxEps), 0, s, best, n_eps, (unsigned)M);
+  hipLaunchKernelGGL(calib_search_kernel, dim3((unsigned)((M + 1023) / 1024)), dim3(1024), 0, s, k1, pf, M, el,
+                     best);
+  hipLaunchKernelGGL(calib_read_kernel, dim3(1), dim3(kMaxEps), 0, s, k1, best, n_eps, (unsigned)M, tau_out,
+                     n_exit_out);
+  return hipGetLastError();
 }
 
 }  // namespace eh

@@ -9,6 +9,11 @@
 #include "eh.h"
 #include "eh_device.hpp"
 
+struct CalibScratch {
+  void* buf = nullptr;
+  size_t bytes = 0;
+};
+
 struct eh_ctx {
   int d = 0, V = 0, n_heads = 0, max_rows = 0, dtype = 0, device = 0;
   float eps = 1e-5f;
@@ -31,6 +36,7 @@ struct eh_ctx {
   eh::frag_t* mh_yf = nullptr;
   eh::Stats* mh_partials = nullptr;
   int mh_heads = 0;
+  CalibScratch calib;  // eh_calibrate's scratch, grown on demand
   float* ws_H = nullptr;        // [max_rows] internal outputs (cascade, verify)
   float* ws_lse = nullptr;
   int* ws_argmax = nullptr;
@@ -90,10 +96,11 @@ hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n
 // order (ln_pack_kernel<DtBf16, 32>), partials are [*n_parts][n_rows rounded up to 32].
 hipError_t gemm32_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
                          const eh::frag_t* yf, eh::Stats* partials, int* n_parts, hipStream_t s);
-// Threshold calibration of one head (eh_calib.hip): device inputs, host eps, device outputs;
-// allocates its scratch memory and synchronises the stream before freeing it.
-hipError_t calibrate_run(const float* H, const int* pred, const int* ref, int64_t M, const double* eps,
-                         int n_eps, float* tau_out, long long* n_exit_out, hipStream_t s);
+// Threshold calibration of one head (eh_calib.hip): device inputs, host eps, device outputs.
+// Asynchronous on s; its scratch memory (about 20 bytes per token) lives in `sc`, grows on
+// demand (which synchronises the device) and is freed by the owner of `sc`.
+hipError_t calibrate_run(CalibScratch& sc, const float* H, const int* pred, const int* ref, int64_t M,
+                         const double* eps, int n_eps, float* tau_out, long long* n_exit_out, hipStream_t s);
 // Enqueues the decode kernel.
 hipError_t decode_launch(const eh_ctx* ctx, const DecodeParams& p, hipStream_t s);
 
