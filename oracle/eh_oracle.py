@@ -26,6 +26,9 @@ What each function follows (arXiv 2407.21082):
   accepted prefix is committed and the first mismatch is replaced by the
   full-model token.
 
+* ``confidence_metrics``: Section 3.4.1: the two confidence metrics the paper
+  compares entropy with, the maximum probability and the difference between the
+  two largest probabilities ("breaking ties").
 * ``calibrate_threshold``: Section 3.4.1, "Calibration of Confidence Thresholds":
   correctness t_j from eq. (2), the joint sort by confidence, the smallest index
   whose suffix holds a proportion of correct predictions of at least epsilon,
@@ -177,6 +180,41 @@ def softmax_stats(z):
         else:
             gap[r] = np.inf
     return H, lse, am, gap
+
+
+def confidence_metrics(z):
+    """Maximum probability and top-2 probability difference of each row of logits
+    (Section 3.4.1, metrics (1) and (3)).
+
+    Straight from the definitions on the materialised distribution: p = softmax(z)
+    computed as exp(z - lse); the probabilities are sorted, max_prob is the largest
+    and margin the largest minus the second largest (a tie at the top gives 0; with
+    a single class the second largest probability is taken as 0).  A row with a NaN
+    or without a finite maximum gives NaN.  Returns (max_prob, margin).
+    """
+    z = np.asarray(z, dtype=np.float64)
+    if z.ndim == 1:
+        z = z[None, :]
+    R, V = z.shape
+    pmax = np.empty(R)
+    margin = np.empty(R)
+    for r in range(R):
+        zr = z[r]
+        m = zr.max()
+        if not np.isfinite(m):
+            pmax[r] = margin[r] = np.nan
+            continue
+        L = m + np.log(np.exp(zr - m).sum())
+        p = np.sort(np.exp(zr - L))
+        pmax[r] = p[-1]
+        margin[r] = p[-1] - (p[-2] if V > 1 else 0.0)
+    return pmax, margin
+
+
+def head_metrics(h, gamma, beta, W, eps=1e-5, bf16=False, bias=None):
+    """LayerNorm -> projection -> (max_prob, margin) for rows h [R, d]."""
+    y = layernorm(h, gamma, beta, eps, bf16_out=bf16)
+    return confidence_metrics(head_logits(y, W, bias))
 
 
 def head_eval(h, gamma, beta, W, eps=1e-5, bf16=False, bias=None):

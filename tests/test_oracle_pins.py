@@ -456,3 +456,65 @@ def test_calibration_exhaustive_small():
 
 def test_correctness_indicator():
     np.testing.assert_array_equal(O.correctness([3, 1, 4, 1], [3, 1, 5, 9]), [1, 1, 0, 0])
+
+
+# ------------------------------------------------------------------ the other two confidence metrics
+def test_metrics_closed_forms():
+    V = 37
+    pm, mg = O.confidence_metrics(np.full((1, V), 2.5))
+    assert abs(pm[0] - 1.0 / V) < 1e-15 and mg[0] == 0.0                  # uniform
+    # one logit a above the rest: p1 = e^a / (e^a + V - 1), p2 = 1 / (e^a + V - 1)
+    for a in (0.3, 2.0, 9.0):
+        z = np.zeros(V)
+        z[11] = a
+        pm, mg = O.confidence_metrics(z)
+        den = math.exp(a) + V - 1
+        assert abs(pm[0] - math.exp(a) / den) < 1e-14 and abs(mg[0] - (math.exp(a) - 1) / den) < 1e-14
+    # two-class case is the logistic function: p1 = sigma(|d|), margin = tanh(|d| / 2)
+    for dlt in (0.0, 0.7, -3.0):
+        pm, mg = O.confidence_metrics([0.0, dlt])
+        assert abs(pm[0] - 1.0 / (1.0 + math.exp(-abs(dlt)))) < 1e-15
+        assert abs(mg[0] - math.tanh(abs(dlt) / 2.0)) < 1e-15
+    pm, mg = O.confidence_metrics([[4.2]])                                # a single class
+    assert pm[0] == 1.0 and mg[0] == 1.0
+    pm, mg = O.confidence_metrics([3.0, 3.0, 1.0])                        # tie at the top
+    assert mg[0] == 0.0 and abs(pm[0] - 1.0 / (2.0 + math.exp(-2.0))) < 1e-15
+
+
+def test_metrics_invariances_and_bounds():
+    rng = np.random.default_rng(21)
+    z = rng.normal(size=(30, 50)) * rng.uniform(0.1, 6.0, size=(30, 1))
+    pm, mg = O.confidence_metrics(z)
+    pm2, mg2 = O.confidence_metrics(z + 123.456)                           # shift
+    np.testing.assert_allclose(pm2, pm, rtol=1e-12)
+    np.testing.assert_allclose(mg2, mg, rtol=1e-10, atol=1e-14)
+    perm = rng.permutation(50)
+    pm3, mg3 = O.confidence_metrics(z[:, perm])                            # permutation
+    np.testing.assert_allclose(pm3, pm, rtol=1e-13)
+    np.testing.assert_allclose(mg3, mg, rtol=1e-11, atol=1e-15)
+    assert ((pm >= 1.0 / 50 - 1e-15) & (pm <= 1.0)).all() and ((mg >= 0) & (mg <= pm)).all()
+    H, lse, am, gap = O.softmax_stats(z)
+    np.testing.assert_allclose(pm, np.exp(z[np.arange(30), am] - lse), rtol=1e-13)   # p of the argmax
+    np.testing.assert_allclose(mg, pm * (1.0 - np.exp(-gap)), rtol=1e-11)            # from the logit gap
+    assert (pm >= np.exp(-H) - 1e-12).all()                                # max p >= e^{-H}
+
+
+def test_metrics_against_scipy_and_pure_python():
+    from scipy.special import softmax
+    rng = np.random.default_rng(4)
+    z = rng.normal(size=(12, 9)) * 3.0
+    pm, mg = O.confidence_metrics(z)
+    p = softmax(z, axis=1)
+    top = np.sort(p, axis=1)
+    np.testing.assert_allclose(pm, top[:, -1], rtol=1e-13)
+    np.testing.assert_allclose(mg, top[:, -1] - top[:, -2], rtol=1e-11, atol=1e-15)
+    for r in range(3):                                                     # the formulas spelled out
+        e = [math.exp(v) for v in z[r]]
+        tot = sum(e)
+        pr = sorted(v / tot for v in e)
+        assert abs(pm[r] - pr[-1]) < 1e-14 and abs(mg[r] - (pr[-1] - pr[-2])) < 1e-14
+
+
+def test_metrics_nan_row():
+    pm, mg = O.confidence_metrics([[1.0, float("nan"), 0.0], [0.0, 1.0, 2.0]])
+    assert np.isnan(pm[0]) and np.isnan(mg[0]) and np.isfinite(pm[1])
