@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of known size (1 GiB read + 1 GiB written each), "
                          "to scale rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--metrics", action="store_true",
+                    help="c2_calib only: also produce the maximum probability and the top-2 probability "
+                         "difference of every (head, token) (eh_eval_heads_metrics)")
     ap.add_argument("--library-gemm", action="store_true",
                     help="only time the vendor GEMM library (torch.matmul, bf16) on the workload's "
                          "projection shape: context for the MFMA roofline fraction, not part of the path")
@@ -294,11 +297,16 @@ def main():
         Hb = torch.zeros((w.n_heads, R), device=dev)
         Lb = torch.zeros((w.n_heads, R), device=dev)
         Ab = torch.zeros((w.n_heads, R), dtype=torch.int32, device=dev)
+        Pb = torch.zeros((w.n_heads, R), device=dev)
+        Mb = torch.zeros((w.n_heads, R), device=dev)
 
         def step():
             # all heads in one call: one LayerNorm launch, one projection launch per head,
             # one launch for the final merges
-            B.eh_eval_heads(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab)
+            if args.metrics:
+                B.eh_eval_heads_metrics(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab, Pb, Mb)
+            else:
+                B.eh_eval_heads(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab)
 
         for _ in range(args.warmup):
             step()
@@ -325,7 +333,8 @@ def main():
                           "launch includes its 1/24 share of the LayerNorm and final-merge launches)",
                 "avg_launch_us": avg_s * 1e6,
                 "flops_per_launch": flops_per_launch, "launches": launches}
-        cfg = {"workload": "c2_calib: d=2048 V=50304 24 heads x 512 tokens bf16, all heads on all tokens"}
+        cfg = {"workload": "c2_calib: d=2048 V=50304 24 heads x 512 tokens bf16, all heads on all tokens"
+                           + (", with max-probability and top-2 difference" if args.metrics else "")}
         out.update(ms_per_step=dt / args.steps * 1e3)
         cpu = None
         B.eh_destroy(ctx)

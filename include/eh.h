@@ -125,6 +125,23 @@ eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const 
                         float* lse, int32_t* argmax, void* stream);
 
 /*
+ * eh_eval_heads plus the two other confidence metrics of Section 3.4.1
+ * ("Calibration of Confidence Thresholds": maximum probability and the difference
+ * between the two largest probabilities, "breaking ties"), for comparing them
+ * with the entropy on a calibration set.  bf16 heads without a bias vector only
+ * (EH_ERR_DTYPE otherwise); any 1 <= n_rows <= max_rows.
+ *
+ * max_prob, margin   device [n_heads_eval, n_rows] float, either may be NULL:
+ *               max_j p_j, and the largest minus the second largest probability
+ *               (0 on a tie at the top; the largest probability itself if V = 1)
+ * Everything else as in eh_eval_heads.
+ */
+eh_status eh_eval_heads_metrics(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const void* h_layers,
+                                int64_t layer_stride, int64_t row_stride, int32_t n_rows, float* H,
+                                float* lse, int32_t* argmax, float* max_prob, float* margin,
+                                void* stream);
+
+/*
  * Exit rule for one head (Section 3.4.2; entropy form of Section 4.3.1,
  * "Drafting phase") followed by compaction of the rows that go on.
  *

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
                 4: "EH_ERR_RANGE", 5: "EH_ERR_HIP", 6: "EH_ERR_WORKSPACE"}
 
 # every symbol include/eh.h declares
-EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_exit_decide", "eh_cascade", "dssd_verify",
+EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify",
            "eh_calibrate", "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
 
 
@@ -53,6 +53,7 @@ def _load() -> C.CDLL:
     lib.eh_destroy.argtypes = [vp]
     lib.eh_eval.argtypes = [vp, i32, vp, i64, vp, vp, i32, vp, vp, vp, vp]
     lib.eh_eval_heads.argtypes = [vp, i32, i32, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.eh_eval_heads_metrics.argtypes = [vp, i32, i32, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp]
     lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, f32, vp]
     lib.eh_cascade.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
@@ -160,6 +161,16 @@ def eh_eval_heads(ctx: EhContext, head0: int, n_heads_eval: int, h_layers: torch
     _check(lib.eh_eval_heads(ctx.handle, head0, n_heads_eval, _ptr(h_layers), h_layers.stride(0),
                              h_layers.stride(1), n_rows, _ptr(H), _ptr(lse), _ptr(argmax),
                              _stream(stream)), ctx.handle)
+
+
+def eh_eval_heads_metrics(ctx: EhContext, head0: int, n_heads_eval: int, h_layers: torch.Tensor, n_rows: int,
+                          H: Optional[torch.Tensor], lse: Optional[torch.Tensor],
+                          argmax: Optional[torch.Tensor], max_prob: Optional[torch.Tensor],
+                          margin: Optional[torch.Tensor], stream=None) -> None:
+    """eh_eval_heads plus max_prob and margin, each [n_heads_eval, n_rows] float32 or None."""
+    _check(lib.eh_eval_heads_metrics(ctx.handle, head0, n_heads_eval, _ptr(h_layers), h_layers.stride(0),
+                                     h_layers.stride(1), n_rows, _ptr(H), _ptr(lse), _ptr(argmax),
+                                     _ptr(max_prob), _ptr(margin), _stream(stream)), ctx.handle)
 
 
 def eh_exit_decide(ctx: EhContext, head: int, H: torch.Tensor, argmax: torch.Tensor, n_rows: int,

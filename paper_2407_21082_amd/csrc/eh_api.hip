@@ -115,7 +115,7 @@ eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const
   }
   int n_parts = kStreamGrid;
   if (batched && bf) {
-    EH_HIP(c, gemm32_launch(c, head, n_rows_dev, n_rows, AO, c->yf, c->partials, &n_parts, s));
+    EH_HIP(c, gemm32_launch(c, head, n_rows_dev, n_rows, AO, c->yf, c->partials, nullptr, &n_parts, s));
   } else if (batched) {
     EH_HIP(c, gemm_launch(c, head, n_rows_dev, n_rows, AO, c->yf, c->partials, &n_parts, s));
   } else {
@@ -323,12 +323,18 @@ eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride
                          (hipStream_t)stream);
 }
 
-eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const void* h_layers,
-                        int64_t layer_stride, int64_t row_stride, int32_t n_rows, float* H, float* lse,
-                        int32_t* argmax, void* stream) {
+namespace {
+
+// eh_eval_heads and eh_eval_heads_metrics.  `metrics`: also the maximum probability and the
+// difference of the two largest probabilities (either output may be NULL).
+eh_status eval_heads_impl(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const void* h_layers,
+                          int64_t layer_stride, int64_t row_stride, int32_t n_rows, float* H, float* lse,
+                          int32_t* argmax, bool metrics, float* max_prob, float* margin, void* stream) {
   if (!ctx) return EH_ERR_NULL;
   if (n_heads_eval < 0 || head0 < 0 || head0 + n_heads_eval > ctx->n_heads)
     return fail(ctx, EH_ERR_RANGE, "heads out of range");
+  if (metrics && (ctx->dtype != EH_BF16 || !ctx->bias.empty()))
+    return fail(ctx, EH_ERR_DTYPE, "the extra confidence metrics need bf16 heads without a bias vector");
   if (n_rows == 0 || n_heads_eval == 0) return EH_OK;
   if (!h_layers) return fail(ctx, EH_ERR_NULL, "h_layers is NULL");
   eh_status st = check_rows(ctx, h_layers, row_stride, n_rows);
@@ -336,7 +342,8 @@ eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const 
   const int esz = ctx->dtype == EH_BF16 ? 2 : 4;
   if ((layer_stride * esz) % 16 != 0) return fail(ctx, EH_ERR_SHAPE, "hidden rows must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
-  const bool batched = ctx->dtype == EH_BF16 && ctx->bias.empty() && ctx->use_gemm && n_rows > 16;
+  const bool batched =
+      ctx->dtype == EH_BF16 && ctx->bias.empty() && ((ctx->use_gemm && n_rows > 16) || metrics);
   if (!batched) {
     // shapes the many-heads kernels do not cover: one head after the other
     for (int l = 0; l < n_heads_eval; ++l) {
@@ -350,7 +357,7 @@ eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const 
   }
   DeviceGuard guard(ctx->device);
   // per head: activations for max_rows rows (plus the zero blocks the kernel may read past
-  // them) and one set of partial statistics
+  // them), one set of partial statistics and one of second largest logits
   const size_t y_stride = (size_t)(ctx->R_pad_max / 16 + 32) * ctx->KS * kWave;
   const size_t part_stride = (size_t)kStreamGrid * ctx->R_pad_max;
   if (ctx->mh_heads < n_heads_eval) {
@@ -358,12 +365,15 @@ eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const 
     EH_HIP(ctx, hipDeviceSynchronize());
     eh::frag_t* y = nullptr;
     eh::Stats* pt = nullptr;
+    float* sec = nullptr;
     hipError_t e = dev_alloc(ctx, &y, y_stride * n_heads_eval);
     if (e == hipSuccess) e = dev_alloc(ctx, &pt, part_stride * n_heads_eval);
+    if (e == hipSuccess) e = dev_alloc(ctx, &sec, part_stride * n_heads_eval);
     if (e == hipSuccess) e = hipMemset(y, 0, y_stride * n_heads_eval * sizeof(frag_t));
     EH_HIP(ctx, e);
     ctx->mh_yf = y;
     ctx->mh_partials = pt;
+    ctx->mh_second = sec;
     ctx->mh_heads = n_heads_eval;
   }
   const int R_pad = (n_rows + 31) & ~31;
@@ -374,11 +384,34 @@ eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const 
   int n_parts = 0;
   for (int l = 0; l < n_heads_eval; ++l)
     EH_HIP(ctx, gemm32_launch(ctx, head0 + l, nullptr, n_rows, false, ctx->mh_yf + (size_t)l * y_stride,
-                              ctx->mh_partials + (size_t)l * part_stride, &n_parts, s));
-  hipLaunchKernelGGL(finalize_kernel, dim3(n_rows, n_heads_eval), dim3(64), 0, s, ctx->mh_partials, n_parts,
-                     R_pad, (const int*)nullptr, n_rows, H, lse, argmax, (int64_t)part_stride, (int64_t)n_rows);
+                              ctx->mh_partials + (size_t)l * part_stride,
+                              metrics ? ctx->mh_second + (size_t)l * part_stride : nullptr, &n_parts, s));
+  if (metrics)
+    hipLaunchKernelGGL(finalize_metrics_kernel, dim3(n_rows, n_heads_eval), dim3(64), 0, s, ctx->mh_partials,
+                       ctx->mh_second, n_parts, R_pad, n_rows, H, lse, argmax, max_prob, margin,
+                       (int64_t)part_stride, (int64_t)n_rows);
+  else
+    hipLaunchKernelGGL(finalize_kernel, dim3(n_rows, n_heads_eval), dim3(64), 0, s, ctx->mh_partials, n_parts,
+                       R_pad, (const int*)nullptr, n_rows, H, lse, argmax, (int64_t)part_stride,
+                       (int64_t)n_rows);
   EH_HIP(ctx, hipGetLastError());
   return EH_OK;
+}
+
+}  // namespace
+
+eh_status eh_eval_heads(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const void* h_layers,
+                        int64_t layer_stride, int64_t row_stride, int32_t n_rows, float* H, float* lse,
+                        int32_t* argmax, void* stream) {
+  return eval_heads_impl(ctx, head0, n_heads_eval, h_layers, layer_stride, row_stride, n_rows, H, lse, argmax,
+                         false, nullptr, nullptr, stream);
+}
+
+eh_status eh_eval_heads_metrics(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const void* h_layers,
+                                int64_t layer_stride, int64_t row_stride, int32_t n_rows, float* H, float* lse,
+                                int32_t* argmax, float* max_prob, float* margin, void* stream) {
+  return eval_heads_impl(ctx, head0, n_heads_eval, h_layers, layer_stride, row_stride, n_rows, H, lse, argmax,
+                         true, max_prob, margin, stream);
 }
 
 eh_status eh_exit_decide(eh_ctx* ctx, int32_t head, const float* H, const int32_t* argmax,
@@ -452,7 +485,7 @@ eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride, in
       const int* idx = l == 0 ? nullptr : ctx->active[l & 1];
       const int* live = l == 0 ? nullptr : cnt + l % 3;
       int n_parts = 0;
-      if (bf) EH_HIP(ctx, gemm32_launch(ctx, l, live, n_rows, false, ctx->yf, ctx->partials, &n_parts, s));
+      if (bf) EH_HIP(ctx, gemm32_launch(ctx, l, live, n_rows, false, ctx->yf, ctx->partials, nullptr, &n_parts, s));
       else EH_HIP(ctx, gemm_launch(ctx, l, live, n_rows, false, ctx->yf, ctx->partials, &n_parts, s));
       const void* hn = last ? nullptr : (const char*)h_layers + (int64_t)(l + 1) * layer_stride * esz;
       const float* gn = last ? nullptr : ctx->gamma[l + 1];

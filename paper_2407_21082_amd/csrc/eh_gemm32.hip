@@ -54,7 +54,10 @@ constexpr int kSlotBytes = 2 * kMaxMT * 1024;
 #define EH_G32_DEPTH 3
 #endif
 constexpr int kDepth = EH_G32_DEPTH;  // activation register sets = k-steps a load may take (<= 6: ring of 8)
-__host__ __device__ constexpr size_t g32_lds_bytes() { return (size_t)kSlots * kSlotBytes; }
+// the weight ring, then 16 bytes per thread: the two largest logits of its (at most 2) token blocks
+// between passes (registers are too scarce to keep them live across the k loop)
+__host__ __device__ constexpr size_t g32_ring_bytes() { return (size_t)kSlots * kSlotBytes; }
+__host__ __device__ constexpr size_t g32_lds_bytes() { return g32_ring_bytes() + kG32Threads * 16; }
 
 #define EH_LDS __attribute__((address_space(3)))
 #define EH_GLOBAL __attribute__((address_space(1)))
@@ -115,7 +118,9 @@ __host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Wa
 // change the counts), so at the wait that opens step s the loads that may still be in
 // flight are exactly the last D-1 groups, DMA(s+2) B(s+1) ... DMA(s+D) B(s+D-1): a
 // wait on a compile-time count.
-template <int MT, int NB, bool ARGMAX_ONLY>
+// TOP2: also track the two largest logits of every token (z1 >= z2, with multiplicity) for the
+// "difference of the two largest probabilities" confidence metric (Section 3.4.1).
+template <int MT, int NB, bool ARGMAX_ONLY, bool TOP2>
 __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq,
                                        int T, int VT16, int KS, int V, int lane, int wave,
                                        EH_LDS char* lds, Stats (&st)[NB]) {
@@ -265,6 +270,12 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
 
   // accumulator register 4g+i of lane l: vocabulary row 32*tile + 8g + 4*(l/32) + i, token l%32
   const int half = lane >> 5;
+  float z1[NB], z2[NB];
+  EH_LDS float* top2 = (EH_LDS float*)(lds + g32_ring_bytes()) + threadIdx.x * 4;
+  if constexpr (TOP2) {
+#pragma unroll
+    for (int n = 0; n < NB; ++n) { z1[n] = top2[2 * n]; z2[n] = top2[2 * n + 1]; }
+  }
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
 #pragma unroll
@@ -274,19 +285,32 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
       for (int n = 0; n < NB; ++n) {
         const f32x4 z = {acc[m][n][4 * g], acc[m][n][4 * g + 1], acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]};
         stats_push4<ARGMAX_ONLY>(st[n], z, row0, V);
+        if constexpr (TOP2) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float zi = (row0 + i < V) ? z[i] : -INFINITY;
+            z2[n] = fmaxf(z2[n], fminf(zi, z1[n]));
+            z1[n] = fmaxf(z1[n], zi);
+          }
+        }
       }
       // keep the instruction scheduler from pulling all accumulators into
       // vector registers at once (it would spill inside the k loop's tail)
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  if constexpr (TOP2) {
+#pragma unroll
+    for (int n = 0; n < NB; ++n) { top2[2 * n] = z1[n]; top2[2 * n + 1] = z2[n]; }
+  }
 }
 
 // grid.x = workgroups over the vocabulary, grid.y = groups of 4*NB blocks of 32 tokens
-template <int NB, bool ARGMAX_ONLY>
+template <int NB, bool ARGMAX_ONLY, bool TOP2>
 __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
     const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq, int VT16, int KS, int V,
-    const int* __restrict__ n_rows_dev, int n_rows, int R_pad, Stats* __restrict__ partials) {
+    const int* __restrict__ n_rows_dev, int n_rows, int R_pad, Stats* __restrict__ partials,
+    float* __restrict__ second) {
   extern __shared__ __attribute__((aligned(16))) char g32_smem[];
   EH_LDS char* lds = (EH_LDS char*)g32_smem;
   const int lane = threadIdx.x & 63;
@@ -306,6 +330,11 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
   Stats st[NB];
 #pragma unroll
   for (int n = 0; n < NB; ++n) stats_init(st[n]);
+  EH_LDS float* top2 = (EH_LDS float*)(lds + g32_ring_bytes()) + threadIdx.x * 4;
+  if constexpr (TOP2) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) top2[i] = -INFINITY;
+  }
   const frag_t* ybase = yq + (long long)nb_first * 2 * KS * kWave;
   for (int t = T0; t < T1;) {
     const int left = T1 - t;
@@ -313,13 +342,13 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
     const int passes = (left + kMaxMT - 1) / kMaxMT;
     const int mt = (left + passes - 1) / passes;
     switch (mt) {
-      case 7: pass32<7, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 6: pass32<6, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 5: pass32<5, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 4: pass32<4, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 3: pass32<3, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 2: pass32<2, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      default: pass32<1, NB, ARGMAX_ONLY>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 7: pass32<7, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 6: pass32<6, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 5: pass32<5, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 4: pass32<4, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 3: pass32<3, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 2: pass32<2, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      default: pass32<1, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
     }
     t += mt;
   }
@@ -327,28 +356,34 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
 #pragma unroll
   for (int n = 0; n < NB; ++n) {
     st[n] = stats_merge(st[n], stats_shfl_xor(st[n], 32));
+    if constexpr (TOP2) {
+      const float a1 = top2[2 * n], a2 = top2[2 * n + 1];
+      const float o1 = __shfl_xor(a1, 32), o2 = __shfl_xor(a2, 32);
+      const float u2 = fmaxf(fminf(a1, o1), fmaxf(a2, o2));  // second largest of the union
+      if (lane < 32 && n < nb_live) second[(long long)blockIdx.x * R_pad + (nb_first + n) * 32 + lane] = u2;
+    }
     if (lane < 32 && n < nb_live)
       partials[(long long)blockIdx.x * R_pad + (nb_first + n) * 32 + lane] = st[n];
   }
 }
 
-template <int NB, bool AO>
+template <int NB, bool AO, bool TOP2>
 void launch32(dim3 g, hipStream_t s, const frag_t* Wf, const frag_t* yq, int VT16, int KS, int V,
-              const int* n_rows_dev, int n_rows, int R_pad, Stats* partials) {
+              const int* n_rows_dev, int n_rows, int R_pad, Stats* partials, float* second) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm32_stats_kernel<NB, AO>,
+    (void)hipFuncSetAttribute((const void*)gemm32_stats_kernel<NB, AO, TOP2>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g32_lds_bytes());
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm32_stats_kernel<NB, AO>), g, dim3(kG32Threads), g32_lds_bytes(), s, Wf, yq,
-                     VT16, KS, V, n_rows_dev, n_rows, R_pad, partials);
+  hipLaunchKernelGGL((gemm32_stats_kernel<NB, AO, TOP2>), g, dim3(kG32Threads), g32_lds_bytes(), s, Wf, yq,
+                     VT16, KS, V, n_rows_dev, n_rows, R_pad, partials, second);
 }
 
 }  // namespace
 
 hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
-                         const frag_t* yf, Stats* partials, int* n_parts, hipStream_t s) {
+                         const frag_t* yf, Stats* partials, float* second, int* n_parts, hipStream_t s) {
   const int R_pad = (n_rows + 31) & ~31;
   const int blocks = R_pad / 32;
   const int nb = blocks <= kG32Waves ? 1 : 2;
@@ -359,13 +394,20 @@ hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n
   dim3 g(gx, groups);
   *n_parts = gx;
   const frag_t* Wf = c->Wf[head];
-  if (nb == 1) {
-    if (argmax_only) launch32<1, true>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
-    else launch32<1, false>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
+#define EH_L32(NB_, AO_, T2_) \
+  launch32<NB_, AO_, T2_>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials, second)
+  if (second) {  // entropy statistics plus the second largest logit
+    if (argmax_only) return hipErrorInvalidValue;
+    if (nb == 1) EH_L32(1, false, true);
+    else EH_L32(2, false, true);
+  } else if (nb == 1) {
+    if (argmax_only) EH_L32(1, true, false);
+    else EH_L32(1, false, false);
   } else {
-    if (argmax_only) launch32<2, true>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
-    else launch32<2, false>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials);
+    if (argmax_only) EH_L32(2, true, false);
+    else EH_L32(2, false, false);
   }
+#undef EH_L32
   return hipGetLastError();
 }
 

@@ -35,6 +35,7 @@ struct eh_ctx {
   // set of partials per head
   eh::frag_t* mh_yf = nullptr;
   eh::Stats* mh_partials = nullptr;
+  float* mh_second = nullptr;  // second largest logits, same shape as mh_partials
   int mh_heads = 0;
   CalibScratch calib;  // eh_calibrate's scratch, grown on demand
   float* ws_H = nullptr;        // [max_rows] internal outputs (cascade, verify)
@@ -94,8 +95,11 @@ hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n
                        const eh::frag_t* yf, eh::Stats* partials, int* n_parts, hipStream_t s);
 // Same for bf16 with blocks of 32 rows: yf must hold the rows in the 32 x 16 operand
 // order (ln_pack_kernel<DtBf16, 32>), partials are [*n_parts][n_rows rounded up to 32].
+// `second`: NULL, or [*n_parts][rows rounded up to 32] floats that receive, per workgroup and
+// row, the second largest logit (counting multiplicity) of the workgroup's vocabulary slice.
 hipError_t gemm32_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
-                         const eh::frag_t* yf, eh::Stats* partials, int* n_parts, hipStream_t s);
+                         const eh::frag_t* yf, eh::Stats* partials, float* second, int* n_parts,
+                         hipStream_t s);
 // Threshold calibration of one head (eh_calib.hip): device inputs, host eps, device outputs.
 // Asynchronous on s; its scratch memory (about 20 bytes per token) lives in `sc`, grows on
 // demand (which synchronises the device) and is freed by the owner of `sc`.

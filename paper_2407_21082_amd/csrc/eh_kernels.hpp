@@ -398,6 +398,46 @@ static __global__ __launch_bounds__(64) void finalize_kernel(const Stats* __rest
   }
 }
 
+// Final merge with the other two confidence metrics of Section 3.4.1: besides the
+// statistics, the second largest logit z2 (with multiplicity) is merged over the
+// workgroups' slices -- second of a union = max(min(z1a, z1b), max(z2a, z2b)) -- and
+//   max_prob = p(argmax) = 1 / S        (S sums 2^(t - m) with m the largest t: its own term is 1)
+//   margin   = p1 - p2 = (1 - e^(z2 - z1)) / S.
+static __global__ __launch_bounds__(64) void finalize_metrics_kernel(
+    const Stats* __restrict__ partials, const float* __restrict__ second, int n_parts, int R_pad, int n_rows,
+    float* __restrict__ H, float* __restrict__ lse, int* __restrict__ argmax, float* __restrict__ max_prob,
+    float* __restrict__ margin, int64_t part_stride, int64_t out_stride) {
+  const int p = blockIdx.x, lane = threadIdx.x;
+  if (p >= n_rows) return;
+  partials += (int64_t)blockIdx.y * part_stride;
+  second += (int64_t)blockIdx.y * part_stride;
+  const int64_t o = (int64_t)blockIdx.y * out_stride + p;
+  Stats s;
+  stats_init(s);
+  float z2 = -INFINITY;
+  for (int g = lane; g < n_parts; g += kWave) {
+    const Stats q = partials[(int64_t)g * R_pad + p];
+    z2 = fmaxf(fminf(s.zb, q.zb), fmaxf(z2, second[(int64_t)g * R_pad + p]));
+    s = stats_merge(s, q);
+  }
+#pragma unroll
+  for (int x = 32; x > 0; x >>= 1) {
+    const Stats q = stats_shfl_xor(s, x);
+    z2 = fmaxf(fminf(s.zb, q.zb), fmaxf(z2, __shfl_xor(z2, x)));
+    s = stats_merge(s, q);
+  }
+  if (lane == 0) {
+    float h, l;
+    stats_finalize(s, h, l);
+    if (H) H[o] = h;
+    if (lse) lse[o] = l;
+    if (argmax) argmax[o] = s.ib;
+    const float p1 = 1.0f / s.S;  // NaN statistics give NaN metrics
+    if (max_prob) max_prob[o] = p1;
+    if (margin) margin[o] = p1 * (1.0f - fast_exp2((z2 - s.zb) * kLog2e));
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Cascade step behind a head's projection (Sections 3.4.1, 3.4.2), one wave per
 // position p of the head's active list: merge the partial statistics of the row,

@@ -429,3 +429,68 @@ def test_calibrate_large_set_properties(B, small_ctx):
         k = np.nonzero(good)[0].max()                                      # largest qualifying value
         assert tau[i] == np.float32(vals[k]) and n[i] == cnt[k], (e, tau[i], vals[k])
     assert (np.diff(tau) <= 0).all()
+
+
+# --------------------------------------------------------------- the other two confidence metrics
+TOL_P = 2e-4   # a probability moves by at most p(1-p) <= 1/4 of a logit error; logits carry fp32
+               # accumulation error well under 8e-4 at these sizes
+
+
+@pytest.mark.parametrize("V,d,R", [(1000, 128, 5), (777, 512, 37), (3000, 256, 161), (1500, 160, 700), (1, 64, 3)])
+def test_eval_heads_metrics(B, V, d, R):
+    w = G.Workload("metrics", d=d, V=V, n_heads=3, rows=R, dtype="bf16", seed=V + d + R)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    n = 3
+    H = torch.full((n, R), float("nan"), device=DEV)
+    lse = torch.full((n, R), float("nan"), device=DEV)
+    am = torch.full((n, R), -1, dtype=torch.int32, device=DEV)
+    pm = torch.full((n, R), float("nan"), device=DEV)
+    mg = torch.full((n, R), float("nan"), device=DEV)
+    B.eh_eval_heads_metrics(ctx, 0, n, hid.h, R, H, lse, am, pm, mg)
+    torch.cuda.synchronize()
+    f64 = G.to_f64_numpy
+    for l in range(n):
+        orc = P.oracle_head(hid.h[l], heads.gamma[l], heads.beta[l], heads.W[l], True)
+        P.compare_head(f"metrics/head{l}", H[l], lse[l], am[l], orc, [])
+        pm_o, mg_o = O.head_metrics(f64(hid.h[l]), f64(heads.gamma[l]), f64(heads.beta[l]), f64(heads.W[l]),
+                                    1e-5, True)
+        dp = np.abs(pm[l].double().cpu().numpy() - pm_o).max()
+        dm = np.abs(mg[l].double().cpu().numpy() - mg_o).max()
+        assert dp <= TOL_P and dm <= TOL_P, (l, dp, dm)
+    if R > 16:   # the statistics are those of eh_eval_heads, bit for bit
+        H2 = torch.zeros_like(H)
+        l2 = torch.zeros_like(lse)
+        a2 = torch.zeros_like(am)
+        B.eh_eval_heads(ctx, 0, n, hid.h, R, H2, l2, a2)
+        torch.cuda.synchronize()
+        assert torch.equal(H, H2) and torch.equal(lse, l2) and torch.equal(am, a2)
+    B.eh_destroy(ctx)
+
+
+def test_eval_heads_metrics_tie_at_the_top_and_refusals(B):
+    # two identical vocabulary rows that win: the margin is exactly 0
+    w = G.Workload("tie", d=64, V=200, n_heads=1, rows=40, dtype="bf16", seed=5)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    f64 = G.to_f64_numpy
+    z = O.head_logits(O.layernorm(f64(hid.h[0]), f64(heads.gamma[0]), f64(heads.beta[0]), 1e-5, True), f64(heads.W[0]))
+    win = int(np.bincount(z.argmax(axis=1)).argmax())           # the most frequent winner
+    Wt = heads.W[0].clone()
+    Wt[(win + 97) % 200] = Wt[win]
+    ctx = B.eh_create([Wt], heads.gamma, heads.beta, [float("inf")], max_rows=40)
+    pm = torch.zeros((1, 40), device=DEV)
+    mg = torch.ones((1, 40), device=DEV)
+    am = torch.zeros((1, 40), dtype=torch.int32, device=DEV)
+    B.eh_eval_heads_metrics(ctx, 0, 1, hid.h, 40, None, None, am, pm, mg)
+    torch.cuda.synchronize()
+    rows = np.nonzero(z.argmax(axis=1) == win)[0]
+    assert len(rows) > 0 and (mg[0, rows] == 0).all() and (am[0, rows].cpu().numpy() == min(win, (win + 97) % 200)).all()
+    B.eh_destroy(ctx)
+    w32 = G.scaled(w, dtype="f32")
+    h32 = G.make_heads(w32, DEV)
+    ctx = B.eh_create(h32.W, h32.gamma, h32.beta, [float("inf")], max_rows=40)
+    with pytest.raises(B.EhError):
+        B.eh_eval_heads_metrics(ctx, 0, 1, G.make_hidden(w32, h32, DEV).h, 40, None, None, None, pm, mg)
+    B.eh_destroy(ctx)
