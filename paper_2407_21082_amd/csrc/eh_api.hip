@@ -533,6 +533,30 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, co
   if (st != EH_OK) return st;
   DeviceGuard guard(ctx->device);
   hipStream_t s = (hipStream_t)stream;
+  const bool bf = ctx->dtype == EH_BF16;
+  if (ctx->bias.empty() && ctx->use_gemm && rows > 16 && (size_t)(k + 1) * sizeof(int) <= 48 * 1024) {
+    // three launches: LayerNorm, argmax-only projection, then one kernel that merges the
+    // partial argmaxes of a row's k+1 positions and walks the prefix
+    const int RB = bf ? 32 : 16;
+    const int R_pad = (int)((rows + RB - 1) / RB * RB);
+    const int fin = ctx->n_heads - 1;
+    dim3 g(R_pad), b(64);
+    if (bf)
+      hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, f_final, (int64_t)ctx->d, (const int*)nullptr,
+                         (const int*)nullptr, (int)rows, R_pad, ctx->d, ctx->KS, ctx->gamma[fin], ctx->beta[fin],
+                         ctx->eps, ctx->yf);
+    else
+      hipLaunchKernelGGL((ln_pack_kernel<DtF32, 16>), g, b, 0, s, f_final, (int64_t)ctx->d, (const int*)nullptr,
+                         (const int*)nullptr, (int)rows, R_pad, ctx->d, ctx->KS, ctx->gamma[fin], ctx->beta[fin],
+                         ctx->eps, ctx->yf);
+    int n_parts = 0;
+    if (bf) EH_HIP(ctx, gemm32_launch(ctx, fin, nullptr, (int)rows, true, ctx->yf, ctx->partials, nullptr, &n_parts, s));
+    else EH_HIP(ctx, gemm_launch(ctx, fin, nullptr, (int)rows, true, ctx->yf, ctx->partials, &n_parts, s));
+    hipLaunchKernelGGL(verify_post_kernel, dim3(B), dim3(256), (size_t)(k + 1) * sizeof(int), s, ctx->partials,
+                       n_parts, R_pad, draft, draft_len, k, target, accepted, next_token);
+    EH_HIP(ctx, hipGetLastError());
+    return EH_OK;
+  }
   int* tgt = target ? target : ctx->ws_argmax;
   st = run_head<true>(ctx, ctx->n_heads - 1, f_final, ctx->d, nullptr, nullptr, (int)rows, nullptr,
                       nullptr, tgt, s);

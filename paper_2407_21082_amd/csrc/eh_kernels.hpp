@@ -560,6 +560,45 @@ static __global__ void verify_compare_kernel(const int* __restrict__ draft, cons
   next_token[b] = target[(int64_t)b * (k + 1) + n];
 }
 
+// The same behind the batched projection in one launch: workgroup b merges the partial
+// argmax records of row b's k+1 positions (one wave per position, four at a time), then
+// its first thread walks the prefix.  `target` (nullable) receives the merged argmaxes.
+static __global__ __launch_bounds__(256) void verify_post_kernel(
+    const Stats* __restrict__ partials, int n_parts, int R_pad, const int* __restrict__ draft,
+    const int* __restrict__ draft_len, int k, int* __restrict__ target, int* __restrict__ accepted,
+    int* __restrict__ next_token) {
+  extern __shared__ int verify_tgt[];  // k + 1 entries
+  const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int j = wave; j <= k; j += 4) {
+    const int p = b * (k + 1) + j;
+    float zb = -INFINITY;
+    int ib = 0x7fffffff;
+    for (int g = lane; g < n_parts; g += kWave) {
+      const Stats q = partials[(int64_t)g * R_pad + p];
+      if (q.zb > zb || (q.zb == zb && q.ib < ib)) { zb = q.zb; ib = q.ib; }
+    }
+#pragma unroll
+    for (int x = 32; x > 0; x >>= 1) {
+      const float oz = __shfl_xor(zb, x);
+      const int oi = __shfl_xor(ib, x);
+      if (oz > zb || (oz == zb && oi < ib)) { zb = oz; ib = oi; }
+    }
+    if (lane == 0) {
+      verify_tgt[j] = ib;
+      if (target) target[p] = ib;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int len = k;
+    if (draft_len) len = min(max(draft_len[b], 0), k);
+    int n = 0;
+    while (n < len && draft[(int64_t)b * k + n] == verify_tgt[n]) ++n;
+    accepted[b] = n;
+    next_token[b] = verify_tgt[n];
+  }
+}
+
 static __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

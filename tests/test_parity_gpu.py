@@ -494,3 +494,36 @@ def test_eval_heads_metrics_tie_at_the_top_and_refusals(B):
     with pytest.raises(B.EhError):
         B.eh_eval_heads_metrics(ctx, 0, 1, G.make_hidden(w32, h32, DEV).h, 40, None, None, None, pm, mg)
     B.eh_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("Bsz,k", [(5, 4), (3, 2), (7, 9)])
+def test_dssd_verify_small(B, dtype, Bsz, k):
+    """Verification on small shapes: with and without draft lengths, with and without the
+    target output, through the decode kernel (at most 16 positions) and the batched one."""
+    w = G.Workload("verify", d=128, V=900, n_heads=2, rows=Bsz * (k + 1), dtype=dtype, seed=Bsz * 10 + k)
+    heads = G.make_heads(w, DEV)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(k)
+    draft = torch.randint(0, w.V, (Bsz, k), generator=gen).to(DEV)
+    case = G.make_verify_case(w, heads, draft, DEV)
+    dlen = torch.randint(0, k + 1, (Bsz,), generator=gen).to(torch.int32).to(DEV)
+    fin = w.n_heads - 1
+    f64 = G.to_f64_numpy
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [0.0, float("inf")], max_rows=Bsz * (k + 1))
+    for use_len in (False, True):
+        acc_o, nxt_o, tgt_o, gap_o = O.dssd_verify(f64(case.f_final), draft.cpu().numpy(), f64(heads.gamma[fin]),
+                                                   f64(heads.beta[fin]), f64(heads.W[fin]),
+                                                   dlen.cpu().numpy() if use_len else None, 1e-5, dtype == "bf16")
+        assert gap_o.min() > 1e-3
+        acc = torch.full((Bsz,), -1, dtype=torch.int32, device=DEV)
+        nxt = torch.full((Bsz,), -1, dtype=torch.int32, device=DEV)
+        tgt = torch.full((Bsz, k + 1), -1, dtype=torch.int32, device=DEV)
+        B.dssd_verify(ctx, case.f_final, draft.to(torch.int32).contiguous(), dlen if use_len else None, acc, nxt,
+                      tgt if use_len else None)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
+        np.testing.assert_array_equal(nxt.cpu().numpy(), nxt_o)
+        if use_len:
+            np.testing.assert_array_equal(tgt.cpu().numpy(), tgt_o)
+    B.eh_destroy(ctx)
