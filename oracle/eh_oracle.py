@@ -26,6 +26,10 @@ What each function follows (arXiv 2407.21082):
   accepted prefix is committed and the first mismatch is replaced by the
   full-model token.
 
+* ``dssd_draft``: Section 4.3.1, "Drafting phase": position by position the first
+  exit head whose entropy is under its threshold supplies the token, which is
+  appended to the draft buffer, until the buffer is full, an end-of-sequence
+  token has been drafted, or no exit head is confident (fallback to the model).
 * ``confidence_metrics``: Section 3.4.1: the two confidence metrics the paper
   compares entropy with, the maximum probability and the difference between the
   two largest probabilities ("breaking ties").
@@ -318,6 +322,53 @@ def dssd_verify(f_final, draft, gamma, beta, W, draft_len=None, eps=1e-5, bf16=F
         accepted[b] = accepted_prefix(draft[b], target[b], L)
         nxt[b] = target[b, accepted[b]]
     return accepted, nxt, target, gap
+
+
+def dssd_draft(H_by_position, token_by_position, tau, limit: int, eos_token: int):
+    """Drafting phase of DSSD (Section 4.3.1) given, for every position the backbone
+    can reach, the entropies H[t][l] and predictions token[t][l] of all heads
+    (l = n_heads-1 is the full model's own head, which is no exit head).
+
+    Walks the positions in order.  At position t the exit heads are tried from the
+    shallowest to the deepest; the first with H < tau_l drafts its token: it is
+    appended to the buffer.  Drafting stops (i) when the buffer holds `limit`
+    tokens, (ii) right after an end-of-sequence token was appended, (iii) at a
+    position where no exit head is confident: nothing is appended and the full
+    model's prediction there is reported as the fallback token.  A NaN entropy is
+    never under a threshold.  If the positions run out first the draft simply ends.
+
+    Returns dict(draft, exit_layer (per drafted token), reason, fallback_token,
+    n_evals) with reason in {"limit", "eos", "fallback", "exhausted"}; n_evals
+    counts (position, head) evaluations with heads tried in order and the model's
+    head evaluated at a fallback position.
+    """
+    n_heads = len(tau)
+    draft, layers = [], []
+    n_evals = 0
+    reason, fallback = "exhausted", -1
+    if limit <= 0:
+        return dict(draft=draft, exit_layer=layers, reason="limit", fallback_token=-1, n_evals=0)
+    for t in range(len(H_by_position)):
+        chosen = None
+        for l in range(n_heads - 1):
+            n_evals += 1
+            if H_by_position[t][l] < tau[l]:
+                chosen = l
+                break
+        if chosen is None:
+            n_evals += 1                          # the model's own head answers
+            reason, fallback = "fallback", int(token_by_position[t][n_heads - 1])
+            break
+        tok = int(token_by_position[t][chosen])
+        draft.append(tok)
+        layers.append(chosen)
+        if tok == eos_token:
+            reason = "eos"
+            break
+        if len(draft) == limit:
+            reason = "limit"
+            break
+    return dict(draft=draft, exit_layer=layers, reason=reason, fallback_token=fallback, n_evals=n_evals)
 
 
 # ----------------------------------------------------------------------------

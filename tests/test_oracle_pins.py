@@ -518,3 +518,59 @@ def test_metrics_against_scipy_and_pure_python():
 def test_metrics_nan_row():
     pm, mg = O.confidence_metrics([[1.0, float("nan"), 0.0], [0.0, 1.0, 2.0]])
     assert np.isnan(pm[0]) and np.isnan(mg[0]) and np.isfinite(pm[1])
+
+
+# ------------------------------------------------------------------ DSSD drafting
+def test_dssd_draft_against_closed_form_exhaustively():
+    """Every pattern of (exit layer, token) over 4 positions, 3 heads, tokens {0, 1=EOS}: the
+    draft is the prefix of length min(limit, first fallback position, first drafted EOS + 1)."""
+    n_heads, tau = 3, [1.0, 1.0, float("inf")]
+    for limit in (1, 2, 3, 5):
+        for exits in itertools.product(range(n_heads), repeat=4):
+            for toks in itertools.product((0, 1), repeat=4):
+                # entropies that make head `exits[t]` the first confident one (2 = none confident)
+                H = [[0.5 if l >= e else 2.0 for l in range(n_heads)] for e in exits]
+                T = [[7 if l != min(e, n_heads - 1) else tk for l in range(n_heads)] for e, tk in zip(exits, toks)]
+                got = O.dssd_draft(H, T, tau, limit, eos_token=1)
+                i_fb = next((t for t, e in enumerate(exits) if e == n_heads - 1), 99)
+                i_eos = next((t for t, (e, tk) in enumerate(zip(exits, toks)) if t < i_fb and tk == 1), 99)
+                L = min(limit, i_fb, i_eos + 1, 4)
+                assert got["draft"] == list(toks[:L]) and got["exit_layer"] == list(exits[:L])
+                want = ("eos" if L == i_eos + 1 else "limit" if L == limit else
+                        "fallback" if L == i_fb else "exhausted")
+                assert got["reason"] == want, (limit, exits, toks, got)
+                assert got["fallback_token"] == (toks[i_fb] if want == "fallback" else -1)
+                evals = sum(e + 1 for e in exits[:L]) + (n_heads if want == "fallback" else 0)
+                assert got["n_evals"] == evals
+
+
+def test_dssd_draft_special_cases():
+    tau = [1.0, float("inf")]
+    assert O.dssd_draft([[0.1, 0.1]], [[5, 6]], tau, 0, 9)["draft"] == []                 # no room
+    r = O.dssd_draft([[float("nan"), 0.1]], [[5, 6]], tau, 4, 9)                           # NaN is not confident
+    assert r["reason"] == "fallback" and r["fallback_token"] == 6 and r["draft"] == []
+    r = O.dssd_draft([[1.0, 0.0]], [[5, 6]], tau, 4, 9)                                    # strict inequality
+    assert r["reason"] == "fallback"
+    r = O.dssd_draft([[0.2, 0.0]] * 3, [[5, 6]] * 3, tau, 8, 9)                            # positions run out
+    assert r["draft"] == [5, 5, 5] and r["reason"] == "exhausted"
+
+
+def test_dssd_draft_consistent_with_exit_rule_and_cascade():
+    """Position by position the drafted (layer, token) is what exit_rule / cascade give."""
+    rng = np.random.default_rng(12)
+    d, V, n_heads, T = 16, 40, 4, 10
+    Ws = [rng.normal(size=(V, d)) / math.sqrt(d) for _ in range(n_heads)]
+    g = [np.ones(d)] * n_heads
+    b = [np.zeros(d)] * n_heads
+    h = rng.normal(size=(T, n_heads, d)) * rng.uniform(0.5, 6.0, size=(T, 1, 1))
+    stats = [[O.head_eval(h[t, l][None, :], g[l], b[l], Ws[l]) for l in range(n_heads)] for t in range(T)]
+    H = [[float(stats[t][l][0][0]) for l in range(n_heads)] for t in range(T)]
+    tok = [[int(stats[t][l][2][0]) for l in range(n_heads)] for t in range(T)]
+    tau = [float(np.median([H[t][l] for t in range(T)])) for l in range(n_heads - 1)] + [float("inf")]
+    r = O.dssd_draft(H, tok, tau, limit=T, eos_token=-5)
+    for t, (lay, tk) in enumerate(zip(r["exit_layer"], r["draft"])):
+        assert lay == O.exit_rule(H[t], tau) and lay < n_heads - 1
+        c = O.cascade([h[t, l][None, :] for l in range(n_heads)], g, b, Ws, tau)
+        assert int(c["exit_layer"][0]) == lay and int(c["token"][0]) == tk
+    if r["reason"] == "fallback":
+        assert O.exit_rule(H[len(r["draft"])], tau) == n_heads - 1
