@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c1_decode",
-                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify", "f1_calibrate"])
+                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify", "f1_calibrate", "f3_draft"])
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per bench step (c1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -151,6 +151,105 @@ def bench_calibrate(args, torch, B, G, dev):
     print(json.dumps(line), flush=True)
 
 
+def bench_draft(args, torch, B, G, dev):
+    """DSSD drafting phase on the device (the controller around config 1's cascade): the decode
+    workload's positions in windows of `limit` = 32, one dssd_draft call per window."""
+    import numpy as np
+    w = G.CONFIGS["c1_decode"]
+    limit = 32
+    n_dec = args.decode_steps or w.steps
+    n_win = n_dec // limit
+    t_setup = time.time()
+    heads = G.make_heads(w, dev)
+    hid = G.make_hidden(w, heads, dev, rows=n_dec)               # [n_heads, n_dec, d]
+    tau = G.tau_linear(w)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=1)
+    hp = hid.h.permute(1, 0, 2)                                  # [position, head, d]
+    wins = [hp[i * limit:(i + 1) * limit] for i in range(n_win)]
+    draft = torch.zeros((n_win, limit), dtype=torch.int32, device=dev)
+    layers = torch.zeros((n_win, limit), dtype=torch.int32, device=dev)
+    ln = torch.zeros(n_win, dtype=torch.int32, device=dev)
+    reason = torch.zeros(n_win, dtype=torch.int32, device=dev)
+    fb = torch.zeros(n_win, dtype=torch.int32, device=dev)
+    nev = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def step():
+        for i in range(n_win):
+            B.dssd_draft(ctx, wins[i], limit, -1, draft[i], ln[i:i + 1], layers[i], reason[i:i + 1], fb[i:i + 1], nev)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    nev.zero_()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ev_s = ev0.elapsed_time(ev1) * 1e-3
+    B.eh_check(ctx)
+    evals = int(nev.item())
+    drafted = int(ln.sum().item())
+    fallbacks = int((reason == 2).sum().item())
+    live = (drafted + fallbacks) * args.steps                   # cascades that did work
+    esz = 2
+    bytes_per_eval = w.d * w.V * esz + w.d * esz + 12
+    # the cascades that run are the dominant kernel; the launches behind a stop return at once.
+    # The whole timed region (controllers and empty launches included) is charged to them.
+    bytes_per_launch = bytes_per_eval * evals / live
+    avg_s = ev_s / live
+    roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C1 * bytes_per_launch,
+            "kernel": "eh::decode_kernel<DtBf16> (one live launch = one drafted position's cascade)",
+            "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": live}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import eh_oracle as O
+        f64 = G.to_f64_numpy
+        W64 = [f64(Wl) for Wl in heads.W]
+        g64 = [f64(g) for g in heads.gamma]
+        b64 = [f64(b) for b in heads.beta]
+        c_evals, c_wins = 0, 0
+        c0 = time.perf_counter()
+        for i in range(n_win):
+            Ht, At = [], []
+            for t in range(i * limit, (i + 1) * limit):
+                hl = [f64(hid.h[l, t:t + 1]) for l in range(w.n_heads)]
+                r = O.cascade(hl, g64, b64, W64, tau, w.ln_eps, True)
+                e = int(r["exit_layer"][0])
+                # heads behind the exit are never consulted by the drafting rule: NaN = never confident
+                Ht.append([float(r["H"][l][0]) if l <= e else float("nan") for l in range(w.n_heads)])
+                At.append([int(r["token"][0]) if l == e else -1 for l in range(w.n_heads)])
+                if e == w.n_heads - 1:
+                    break
+            res = O.dssd_draft(Ht, At, tau, limit, -1)
+            c_evals += res["n_evals"]
+            c_wins += 1
+            if time.perf_counter() - c0 > args.cpu_seconds:
+                break
+        cdt = time.perf_counter() - c0
+        cpu = {"value": c_evals / cdt, "unit": "evals/s", "cores": oracle_threads(), "kind": "oracle",
+               "sample": f"first {c_wins} windows of the same workload ({c_evals} evaluations, {cdt:.1f} s; "
+                         "fp64 numpy cascade per position, then the drafting rule)"}
+    B.eh_destroy(ctx)
+    line = {"metric": "exit_head_evals_per_sec", "value": evals / dt, "unit": "evals/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"f3_draft: d=1024 V=50304 24 heads batch-1 bf16, {n_win} drafting windows of "
+                                   f"{limit} positions per bench step, draft until the buffer is full or no exit head "
+                                   "is confident",
+                       "windows": n_win, "limit": limit, "drafted_tokens_per_step": drafted,
+                       "fallback_windows": fallbacks, "drafted_tokens_per_sec": drafted * args.steps / dt,
+                       "mean_evals_per_live_position": evals / live},
+            "roofline": roof, "cpu_baseline": cpu, "setup_s": round(time.time() - t_setup, 1)}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -182,6 +281,8 @@ def main():
         return
     if args.workload == "f1_calibrate":
         return bench_calibrate(args, torch, B, G, dev)
+    if args.workload == "f3_draft":
+        return bench_draft(args, torch, B, G, dev)
     w = G.CONFIGS[args.workload]
     if args.library_gemm:
         R = max(w.rows, 16)

@@ -200,6 +200,40 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft,
                       int32_t* next_token, int32_t* target, void* stream);
 
 /*
+ * DSSD drafting phase (Section 4.3.1, "Drafting phase") for one sequence, without a
+ * host round trip: position after position the exit heads are tried from the
+ * shallowest to the deepest and the first with H < tau drafts its token, which is
+ * appended to the draft buffer; drafting stops when the buffer holds `limit` tokens
+ * (EH_DRAFT_LIMIT), right after an end-of-sequence token was appended
+ * (EH_DRAFT_EOS), at a position where no exit head is confident (EH_DRAFT_FALLBACK:
+ * nothing is appended, the last head's -- the model's own -- prediction there is
+ * reported), or when the positions run out (EH_DRAFT_EXHAUSTED).  The hidden
+ * states of every position are supplied by the caller (the backbone is not part of
+ * this library; in a real decoder position t depends on the token drafted at t-1,
+ * so a caller drafts with n_positions = 1 per backbone step, or with as many
+ * positions as its backbone has produced).  Once drafting has stopped the
+ * remaining launches of the call return at once on the device.
+ *
+ * h_positions   device; position t, head l: d elements (h_dtype) at element
+ *               t * pos_stride + l * layer_stride
+ * n_positions   positions available, >= 0; limit  buffer size, >= 0
+ * eos_token     token id that ends the draft (pass -1 for none)
+ * draft         device [limit] int32: the drafted tokens (first *draft_len valid)
+ * draft_len     device int32
+ * exit_layers   device [limit] int32: the head that drafted each token, -1 beyond
+ * stop_reason, fallback_token   device int32, nullable; fallback_token is -1 unless
+ *               the reason is EH_DRAFT_FALLBACK
+ * n_evals_out   NULL or device int64, incremented by the (position, head)
+ *               evaluations performed
+ * Needs the single-row kernel (heads without a bias vector); EH_ERR_DTYPE otherwise.
+ */
+enum { EH_DRAFT_LIMIT = 0, EH_DRAFT_EOS = 1, EH_DRAFT_FALLBACK = 2, EH_DRAFT_EXHAUSTED = 3 };
+eh_status dssd_draft(eh_ctx* ctx, const void* h_positions, int64_t pos_stride, int64_t layer_stride,
+                     int32_t n_positions, int32_t limit, int32_t eos_token, int32_t* draft,
+                     int32_t* draft_len, int32_t* exit_layers, int32_t* stop_reason,
+                     int32_t* fallback_token, int64_t* n_evals_out, void* stream);
+
+/*
  * Threshold calibration of one head (Section 3.4.1, "Calibration of Confidence
  * Thresholds"), entropy as the confidence metric: the M calibration tokens are
  * ordered by ascending confidence (descending entropy); for a level epsilon the

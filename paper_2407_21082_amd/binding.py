@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
                 4: "EH_ERR_RANGE", 5: "EH_ERR_HIP", 6: "EH_ERR_WORKSPACE"}
 
 # every symbol include/eh.h declares
-EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify",
+EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft",
            "eh_calibrate", "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
 
 
@@ -57,6 +57,7 @@ def _load() -> C.CDLL:
     lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, f32, vp]
     lib.eh_cascade.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.dssd_draft.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.eh_calibrate.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double), i32, vp, vp, vp]
     lib.eh_check.argtypes = [vp, vp]
     lib.eh_decode_trace.argtypes = [vp, i32, vp, i32]
@@ -65,7 +66,7 @@ def _load() -> C.CDLL:
     lib.eh_last_error.restype = C.c_char_p
     lib.eh_version.argtypes = []
     lib.eh_version.restype = C.c_char_p
-    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "eh_check"):
+    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "eh_check"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -190,6 +191,19 @@ def eh_cascade(ctx: EhContext, h_layers: torch.Tensor, n_rows: int, exit_layer: 
     _check(lib.eh_cascade(ctx.handle, _ptr(h_layers), h_layers.stride(0), h_layers.stride(1), n_rows,
                           _ptr(exit_layer), _ptr(token), _ptr(H_out), _ptr(n_evals_out),
                           _stream(stream)), ctx.handle)
+
+
+DRAFT_REASONS = {0: "limit", 1: "eos", 2: "fallback", 3: "exhausted"}
+
+
+def dssd_draft(ctx: EhContext, h_positions: torch.Tensor, limit: int, eos_token: int, draft: torch.Tensor,
+               draft_len: torch.Tensor, exit_layers: torch.Tensor, stop_reason: Optional[torch.Tensor] = None,
+               fallback_token: Optional[torch.Tensor] = None, n_evals_out: Optional[torch.Tensor] = None,
+               stream=None) -> None:
+    """h_positions: [n_positions, n_heads, d] (any strides on the first two axes)."""
+    _check(lib.dssd_draft(ctx.handle, _ptr(h_positions), h_positions.stride(0), h_positions.stride(1),
+                          h_positions.shape[0], limit, eos_token, _ptr(draft), _ptr(draft_len), _ptr(exit_layers),
+                          _ptr(stop_reason), _ptr(fallback_token), _ptr(n_evals_out), _stream(stream)), ctx.handle)
 
 
 def eh_calibrate(ctx: EhContext, H: torch.Tensor, pred: torch.Tensor, ref: torch.Tensor, eps,

@@ -567,6 +567,54 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, co
   return EH_OK;
 }
 
+eh_status dssd_draft(eh_ctx* ctx, const void* h_positions, int64_t pos_stride, int64_t layer_stride,
+                     int32_t n_positions, int32_t limit, int32_t eos_token, int32_t* draft, int32_t* draft_len,
+                     int32_t* exit_layers, int32_t* stop_reason, int32_t* fallback_token, int64_t* n_evals_out,
+                     void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (limit < 0 || n_positions < 0) return fail(ctx, EH_ERR_SHAPE, "limit and n_positions must be non-negative");
+  if (!draft_len || (limit > 0 && (!draft || !exit_layers))) return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
+  if (n_positions > 0 && limit > 0 && !h_positions) return fail(ctx, EH_ERR_NULL, "h_positions is NULL");
+  if (ctx->decode_grid <= 0)
+    return fail(ctx, EH_ERR_DTYPE, "drafting needs the single-row decode kernel (no bias vector, d within its limit)");
+  if (ctx->n_heads < 2) return fail(ctx, EH_ERR_RANGE, "drafting needs at least one exit head besides the model's");
+  const int esz = ctx->dtype == EH_BF16 ? 2 : 4;
+  const int steps = n_positions < limit ? n_positions : limit;
+  if (steps > 0) {
+    eh_status st = check_rows(ctx, h_positions, ctx->d, 1);
+    if (st != EH_OK) return st;
+    if ((layer_stride * esz) % 16 != 0 || (pos_stride * esz) % 16 != 0)
+      return fail(ctx, EH_ERR_SHAPE, "strides must keep rows 16-byte aligned");
+  }
+  DeviceGuard guard(ctx->device);
+  hipStream_t s = (hipStream_t)stream;
+  int* state = ctx->n_active[1];     // {live, length, reason, fallback token}
+  int* ex = ctx->active[0];          // the current position's exit layer and token
+  int* tk = ctx->active[1];
+  hipLaunchKernelGGL(draft_init_kernel, dim3(1), dim3(64), 0, s, state, limit, exit_layers);
+  for (int t = 0; t < steps; ++t) {
+    DecodeParams p = decode_base(ctx);
+    p.h = (const char*)h_positions + (int64_t)t * pos_stride * esz;
+    p.layer_stride = layer_stride;
+    p.row_stride = ctx->d;
+    p.n_rows = 1;
+    p.n_rows_dev = state;  // 1 while drafting, 0 once it has stopped: the launch then returns at once
+    p.l0 = 0;
+    p.l1 = ctx->n_heads;
+    p.decide = 1;
+    p.exit_layer = ex;
+    p.token = tk;
+    p.H_out = nullptr;
+    p.n_evals = (unsigned long long*)n_evals_out;
+    EH_HIP(ctx, decode_launch(ctx, p, s));
+    hipLaunchKernelGGL(draft_step_kernel, dim3(1), dim3(1), 0, s, state, ex, tk, ctx->n_heads - 1, limit, eos_token,
+                       draft, exit_layers);
+  }
+  hipLaunchKernelGGL(draft_finish_kernel, dim3(1), dim3(1), 0, s, state, draft_len, stop_reason, fallback_token);
+  EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
+}
+
 eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const int32_t* ref, int64_t M,
                        const double* eps, int32_t n_eps, float* tau_out, int64_t* n_exit_out, void* stream) {
   if (!ctx) return EH_ERR_NULL;

@@ -707,6 +707,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(const DecodeParams 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in an SGPR
   if (*(volatile int*)p.status != 0) return;  // a previous launch failed: do nothing
+  // no live row at all (the count lives on the device: e.g. a drafting loop that has stopped):
+  // every workgroup reads the same word, so the whole grid leaves together
+  if (p.n_rows_dev && *p.n_rows_dev <= 0) return;
   // zero both activation buffers (columns of rows that are not live stay zero)
   {
     lds_frag_t* y = sm.ybuf(0);

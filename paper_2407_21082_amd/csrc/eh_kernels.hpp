@@ -599,6 +599,53 @@ static __global__ __launch_bounds__(256) void verify_post_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// DSSD drafting controller (Section 4.3.1, "Drafting phase"): one thread, run
+// behind the cascade of a position.  state = {live, length, reason, fallback}:
+// `live` is the device-side row count of the next position's cascade (0 once
+// drafting has stopped, which turns the remaining launches into no-ops).
+// ---------------------------------------------------------------------------
+static __global__ void draft_init_kernel(int* __restrict__ state, int limit, int* __restrict__ exit_layers) {
+  if (threadIdx.x == 0) {
+    state[0] = limit > 0 ? 1 : 0;
+    state[1] = 0;
+    state[2] = limit > 0 ? -1 : 0;  // an empty buffer is full at once
+    state[3] = -1;
+  }
+  for (int i = threadIdx.x; i < limit; i += blockDim.x) exit_layers[i] = -1;
+}
+
+static __global__ void draft_step_kernel(int* __restrict__ state, const int* __restrict__ exit_layer,
+                                         const int* __restrict__ token, int last_head, int limit, int eos,
+                                         int* __restrict__ draft, int* __restrict__ exit_layers) {
+  if (state[0] == 0) return;
+  const int e = *exit_layer, tk = *token;
+  if (e >= last_head) {  // no exit head was confident: the model's own prediction is the fallback
+    state[0] = 0;
+    state[2] = 2;
+    state[3] = tk;
+    return;
+  }
+  const int n = state[1];
+  draft[n] = tk;
+  exit_layers[n] = e;
+  state[1] = n + 1;
+  if (tk == eos) {
+    state[0] = 0;
+    state[2] = 1;
+  } else if (n + 1 == limit) {
+    state[0] = 0;
+    state[2] = 0;
+  }
+}
+
+static __global__ void draft_finish_kernel(const int* __restrict__ state, int* __restrict__ draft_len,
+                                           int* __restrict__ stop_reason, int* __restrict__ fallback_token) {
+  *draft_len = state[1];
+  if (stop_reason) *stop_reason = state[2] < 0 ? 3 : state[2];  // still running: the positions ran out
+  if (fallback_token) *fallback_token = state[3];
+}
+
 static __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

@@ -527,3 +527,106 @@ def test_dssd_verify_small(B, dtype, Bsz, k):
         if use_len:
             np.testing.assert_array_equal(tgt.cpu().numpy(), tgt_o)
     B.eh_destroy(ctx)
+
+
+# --------------------------------------------------------------- DSSD drafting phase
+def _draft_case(dtype, seed, n_heads=4, n_pos=12, V=1000, d=256):
+    """A seeded drafting case whose oracle argmaxes are all clear of a tie (top-2 logit gap above
+    1e-3): the first seed from `seed` on that has none, so the comparison can be exact."""
+    for s in range(seed, seed + 16):
+        w = G.Workload("draft", d=d, V=V, n_heads=n_heads, rows=n_pos, dtype=dtype, seed=s)
+        heads = G.make_heads(w, DEV)
+        hid = G.make_hidden(w, heads, DEV)                  # [n_heads, n_pos, d]
+        full = P.oracle_all_heads(heads, hid.h, dtype == "bf16")
+        if full[3].min() > 1e-3:
+            return w, heads, hid, full
+    raise AssertionError("no tie-free case in 16 seeds")
+
+
+def _run_draft(B, heads, hid, tau, limit, eos, n_pos=None):
+    """One dssd_draft call; every output starts poisoned."""
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=1)
+    hp = hid.h.permute(1, 0, 2)                             # [position, head, d], a strided view
+    if n_pos is not None:
+        hp = hp[:n_pos]
+    draft = torch.full((max(limit, 1),), -7, dtype=torch.int32, device=DEV)
+    layers = torch.full((max(limit, 1),), -7, dtype=torch.int32, device=DEV)
+    ln = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    reason = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    fb = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    nev = torch.zeros(1, dtype=torch.int64, device=DEV)
+    B.dssd_draft(ctx, hp, limit, eos, draft, ln, layers, reason, fb, nev)
+    torch.cuda.synchronize()
+    B.eh_check(ctx)
+    B.eh_destroy(ctx)
+    n = int(ln.item())
+    return dict(draft=draft[:n].tolist(), exit_layer=layers[:n].tolist(), reason=B.DRAFT_REASONS[int(reason.item())],
+                fallback_token=int(fb.item()), n_evals=int(nev.item())), layers.tolist()
+
+
+def _safe_tau(H, q, margin=5e-3):
+    """Per-head thresholds near the q-quantile of the oracle's entropies, moved into the widest
+    gap nearby so that no entropy lies within `margin` of its head's threshold."""
+    tau = []
+    for l in range(H.shape[0]):
+        s = np.sort(H[l])
+        k = min(max(int(q * len(s)), 1), len(s) - 1)
+        best = max(range(max(1, k - 3), min(len(s), k + 4)), key=lambda i: s[i] - s[i - 1])
+        assert s[best] - s[best - 1] > 2 * margin
+        tau.append(float(0.5 * (s[best] + s[best - 1])))
+    return tau
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_dssd_draft_matches_oracle(B, dtype):
+    w, heads, hid, (H, _, am, gap) = _draft_case(dtype, seed=2024)
+    Ht, amt = H.T, am.T                                     # [position][head]
+    n_heads, n_pos = H.shape
+    seen = set()
+    for q in (0.3, 0.6, 0.85):
+        tau = _safe_tau(H, q)
+        for limit in (3, 8, 12, 20):
+            want = O.dssd_draft(Ht, amt, tau, limit, -1)
+            got, layers = _run_draft(B, heads, hid, tau, limit, -1)
+            assert got == want, (q, limit, got, want)
+            assert all(x == -1 for x in layers[len(want["draft"]):limit])
+            seen.add(want["reason"])
+            if want["draft"]:
+                # the same call with its own last drafted token as the end-of-sequence token
+                eos = want["draft"][-1]
+                want_e = O.dssd_draft(Ht, amt, tau, limit, eos)
+                got_e, _ = _run_draft(B, heads, hid, tau, limit, eos)
+                assert got_e == want_e and want_e["reason"] == "eos"
+                seen.add("eos")
+    assert {"limit", "fallback", "eos"} <= seen, seen
+    # every exit head always confident: the buffer fills, or the positions run out
+    always = [1e9] * n_heads
+    for limit, npos in ((5, None), (12, None), (20, None), (8, 4), (8, 0), (0, None)):
+        hsel = Ht if npos is None else Ht[:npos]
+        want = O.dssd_draft(hsel, amt, always, limit, -1)
+        got, _ = _run_draft(B, heads, hid, always, limit, -1, n_pos=npos)
+        assert got == want, (limit, npos, got, want)
+        seen.add(want["reason"])
+    assert "exhausted" in seen
+    # no exit head ever confident: the model's head answers at the first position
+    never = [-1.0] * n_heads
+    want = O.dssd_draft(Ht, amt, never, 8, -1)
+    got, _ = _run_draft(B, heads, hid, never, 8, -1)
+    assert got == want and want["reason"] == "fallback" and want["n_evals"] == n_heads and want["draft"] == []
+
+
+def test_dssd_draft_errors(B):
+    w, heads, hid, _ = _draft_case("bf16", seed=7, n_heads=2, n_pos=2, V=64, d=64)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [1.0, 1.0], max_rows=1)
+    i32 = lambda n: torch.zeros(n, dtype=torch.int32, device=DEV)
+    with pytest.raises(B.EhError):
+        B.dssd_draft(ctx, hid.h.permute(1, 0, 2), -1, -1, i32(4), i32(1), i32(4))
+    with pytest.raises(B.EhError):
+        B.dssd_draft(ctx, hid.h.permute(1, 0, 2), 4, -1, None, i32(1), i32(4))
+    B.eh_destroy(ctx)
+    # a context with a bias vector has no single-row kernel: drafting is refused, not emulated
+    bias = [torch.zeros(64, device=DEV) for _ in heads.W]
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [1.0, 1.0], max_rows=1, bias=bias)
+    with pytest.raises(B.EhError):
+        B.dssd_draft(ctx, hid.h.permute(1, 0, 2), 4, -1, i32(4), i32(1), i32(4))
+    B.eh_destroy(ctx)
