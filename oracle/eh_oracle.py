@@ -30,6 +30,9 @@ What each function follows (arXiv 2407.21082):
   exit head whose entropy is under its threshold supplies the token, which is
   appended to the draft buffer, until the buffer is full, an end-of-sequence
   token has been drafted, or no exit head is confident (fallback to the model).
+* ``dssd_tally``: Section 4.3.1, "Verification phase", and the figures of Section
+  4.3.2: tokens drafted, committed and discarded over verification rounds, the
+  acceptance rate (committed / drafted) and the mean accepted tokens per round.
 * ``confidence_metrics``: Section 3.4.1: the two confidence metrics the paper
   compares entropy with, the maximum probability and the difference between the
   two largest probabilities ("breaking ties").
@@ -63,6 +66,12 @@ __all__ = [
     "cascade",
     "dssd_verify",
     "accepted_prefix",
+    "dssd_draft",
+    "dssd_tally",
+    "confidence_metrics",
+    "head_metrics",
+    "correctness",
+    "calibrate_threshold",
 ]
 
 
@@ -369,6 +378,33 @@ def dssd_draft(H_by_position, token_by_position, tau, limit: int, eos_token: int
             reason = "limit"
             break
     return dict(draft=draft, exit_layer=layers, reason=reason, fallback_token=fallback, n_evals=n_evals)
+
+
+def dssd_tally(draft_len, accepted, exit_layers=None):
+    """Bookkeeping over verification rounds (Section 4.3.1, verification phase, and the
+    quantities Section 4.3.2 reports): every round b drafted draft_len[b] tokens of
+    which the first accepted[b] were committed; the rest were computed for nothing.
+
+    Returns dict(rounds, drafted, accepted, wasted, exit_layer_sum, acceptance_rate,
+    mean_accepted) where acceptance_rate = accepted / drafted (NaN if nothing was
+    drafted), mean_accepted = accepted / rounds (the "implicit speculation budget"),
+    and exit_layer_sum adds exit_layers[b][j] over the drafted tokens j < draft_len[b]
+    (0 without exit_layers), so that exit_layer_sum / drafted is the mean exit head
+    during drafting.
+    """
+    rounds = drafted = acc = waste = layer_sum = 0
+    for b in range(len(draft_len)):
+        n, a = int(draft_len[b]), int(accepted[b])
+        rounds += 1
+        drafted += n
+        acc += a
+        waste += n - a
+        if exit_layers is not None:
+            for j in range(n):
+                layer_sum += int(exit_layers[b][j])
+    return dict(rounds=rounds, drafted=drafted, accepted=acc, wasted=waste, exit_layer_sum=layer_sum,
+                acceptance_rate=acc / drafted if drafted else float("nan"),
+                mean_accepted=acc / rounds if rounds else float("nan"))
 
 
 # ----------------------------------------------------------------------------

@@ -574,3 +574,81 @@ def test_dssd_draft_consistent_with_exit_rule_and_cascade():
         assert int(c["exit_layer"][0]) == lay and int(c["token"][0]) == tk
     if r["reason"] == "fallback":
         assert O.exit_rule(H[len(r["draft"])], tau) == n_heads - 1
+
+
+# ---------------------------------------------------------------- verification bookkeeping
+def _figures():
+    rows = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "acceptance_figures.txt")):
+        if line.strip() and not line.startswith("#"):
+            f = line.split()
+            rows[f[0]] = [float(x) for x in f[1:]]
+    return rows
+
+
+def test_tally_reproduces_the_papers_printed_figures():
+    """Section 4.3.2 prints rate and waste of two systems; with rate = accepted / drafted and
+    wasted = drafted - accepted there must be integer token counts that print as those figures,
+    and the printed ratios must follow from them."""
+    fig = _figures()
+    rates = {}
+    for name in ("layerskip_best", "dssd_eps_0.9"):
+        pct, wasted = fig[name]
+        wasted = int(wasted)
+        found = []
+        for drafted in range(wasted, 100 * wasted):
+            t = O.dssd_tally([drafted], [drafted - wasted])
+            assert t["wasted"] == wasted and t["drafted"] == drafted and t["rounds"] == 1
+            if abs(100.0 * t["acceptance_rate"] - pct) <= 0.05 + 1e-9:
+                found.append((drafted, t["acceptance_rate"]))
+        assert found, name                                  # the printed pair is attainable ...
+        assert len(found) <= 2, (name, found)               # ... and pins the counts
+        rates[name] = found[0][1]
+        # the same counts under a wrong definition (waste over drafted, accepted over wasted+drafted)
+        d = found[0][0]
+        assert abs(100.0 * wasted / d - pct) > 1.0
+        assert abs(100.0 * (d - wasted) / (d + wasted) - pct) > 1.0
+    assert round(rates["dssd_eps_0.9"] / rates["layerskip_best"], 2) == fig["ratio_acceptance"][0]
+    assert int(fig["layerskip_best"][1] / fig["dssd_eps_0.9"][1]) == int(fig["ratio_waste"][0])
+
+
+def test_tally_against_token_by_token_enumeration():
+    """Every drafted token is individually either committed (it and all before it match the
+    model's prediction) or wasted; counting them one by one must give the tally of the
+    verification's outputs."""
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        B, k = int(rng.integers(1, 6)), int(rng.integers(1, 7))
+        draft = rng.integers(0, 2, size=(B, k))
+        target = rng.integers(0, 2, size=(B, k + 1))
+        lens = rng.integers(0, k + 1, size=B)
+        layers = rng.integers(0, 24, size=(B, k))
+        committed = wasted = lsum = 0
+        for b in range(B):
+            ok = True
+            for j in range(int(lens[b])):
+                ok = ok and draft[b, j] == target[b, j]
+                committed += ok
+                wasted += not ok
+                lsum += int(layers[b, j])
+        acc = [O.accepted_prefix(draft[b], target[b], int(lens[b])) for b in range(B)]
+        t = O.dssd_tally(lens, acc, layers)
+        assert (t["accepted"], t["wasted"], t["drafted"], t["rounds"], t["exit_layer_sum"]) == \
+               (committed, wasted, int(lens.sum()), B, lsum)
+        assert t["accepted"] + t["wasted"] == t["drafted"]
+        if t["drafted"]:
+            assert t["acceptance_rate"] == committed / t["drafted"]
+        assert t["mean_accepted"] == committed / B
+
+
+def test_tally_is_additive_and_handles_nothing_drafted():
+    a = O.dssd_tally([3, 0, 5], [1, 0, 5], [[1, 2, 3, 9, 9], [9] * 5, [4] * 5])
+    b = O.dssd_tally([2], [0], [[7, 8, 9, 9, 9]])
+    ab = O.dssd_tally([3, 0, 5, 2], [1, 0, 5, 0], [[1, 2, 3, 9, 9], [9] * 5, [4] * 5, [7, 8, 9, 9, 9]])
+    for key in ("rounds", "drafted", "accepted", "wasted", "exit_layer_sum"):
+        assert a[key] + b[key] == ab[key]
+    assert a["exit_layer_sum"] == 6 + 20 and b["exit_layer_sum"] == 15
+    z = O.dssd_tally([0, 0], [0, 0])
+    assert z["drafted"] == 0 and math.isnan(z["acceptance_rate"]) and z["mean_accepted"] == 0.0
+    e = O.dssd_tally([], [])
+    assert e["rounds"] == 0 and math.isnan(e["mean_accepted"])
