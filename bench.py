@@ -81,6 +81,29 @@ def oracle_threads():
         return os.cpu_count() or 1
 
 
+def cpu_head_evals(args, G, heads, chunks, what):
+    """Time the oracle's head evaluation on (head, rows) chunks until the CPU budget is used.
+    Widening a head's weights to fp64 is input marshalling and is not timed."""
+    from oracle import eh_oracle as O
+    f64 = G.to_f64_numpy
+    done, spent, n_chunks = 0, 0.0, 0
+    cached = (None, None)
+    for l, rows in chunks:
+        if cached[0] != l:
+            cached = (l, (f64(heads.W[l]), f64(heads.gamma[l]), f64(heads.beta[l])))
+        W64, g64, b64 = cached[1]
+        h64 = f64(rows)
+        c0 = time.perf_counter()
+        O.head_eval(h64, g64, b64, W64, 1e-5, True)
+        spent += time.perf_counter() - c0
+        done += h64.shape[0]
+        n_chunks += 1
+        if spent > args.cpu_seconds:
+            break
+    return {"value": done / spent, "unit": "evals/s", "cores": oracle_threads(), "kind": "oracle",
+            "sample": f"{what}: {n_chunks} chunks, {done} evaluations, {spent:.1f} s (fp64 numpy, weights pre-widened)"}
+
+
 def bench_calibrate(args, torch, B, G, dev):
     """Threshold calibration of one head (the step after config 2 in the paper's pipeline):
     M = 2^24 calibration tokens, the paper's sweep of 11 confidence levels in one call."""
@@ -438,6 +461,9 @@ def main():
                            + (", with max-probability and top-2 difference" if args.metrics else "")}
         out.update(ms_per_step=dt / args.steps * 1e3)
         cpu = None
+        if not args.no_cpu_baseline:
+            cpu = cpu_head_evals(args, G, heads, ((l, hid.h[l][:128]) for l in range(w.n_heads)),
+                                 "the first 128 tokens of each head in turn")
         B.eh_destroy(ctx)
     elif args.workload == "c3_dynexit":
         # 64 decode rows through 32 heads; a row leaves at its first H < tau and the
@@ -496,6 +522,12 @@ def main():
                "exited_by_layer_8_16_24": [float((exl < l).mean()) for l in (8, 16, 24)]}
         out.update(ms_per_step=dt / args.steps * 1e3)
         cpu = None
+        if not args.no_cpu_baseline:
+            # head by head on the rows this run's cascade kept alive up to that head
+            exd = ex.to(dev)
+            cpu = cpu_head_evals(args, G, heads,
+                                 ((l, hid.h[l][exd >= l]) for l in range(heads_run)),
+                                 "each head in turn on the rows still alive at it")
         B.eh_destroy(ctx)
     elif args.workload == "c4_verify":
         # 16 rows x (8 drafts + 1): argmax of the final head at 144 positions and the accepted
@@ -548,8 +580,29 @@ def main():
         cfg = {"workload": "c4_verify: d=2560 V=50304 final head, 16 rows x (8 drafts + 1) bf16, "
                            f"{calls_per_step} verifications per bench step over {n_copies} weight copies",
                "mean_accepted": float(acc.float().mean().item())}
+        # the bookkeeping of Section 4.3.2 on this batch's outcome (outside the timed region)
+        counters = torch.zeros(5, dtype=torch.int64, device=dev)
+        B.dssd_tally(ctxs[0], None, acc, Bsz, k, None, counters)
+        cnt = counters.tolist()
+        cfg.update(drafted=cnt[1], accepted=cnt[2], wasted=cnt[3], acceptance_rate=cnt[2] / max(cnt[1], 1))
         out.update(ms_per_step=dt / args.steps * 1e3)
         cpu = None
+        if not args.no_cpu_baseline:
+            from oracle import eh_oracle as O
+            f64 = G.to_f64_numpy
+            W64, g64, b64 = f64(heads.W[fin]), f64(heads.gamma[fin]), f64(heads.beta[fin])
+            done, spent = 0, 0.0
+            for b0 in range(0, Bsz, 2):
+                f2, d2 = f64(case.f_final[b0:b0 + 2]), draft[b0:b0 + 2].cpu().numpy()
+                c0 = time.perf_counter()
+                O.dssd_verify(f2, d2, g64, b64, W64, None, 1e-5, True)
+                spent += time.perf_counter() - c0
+                done += 2 * (k + 1)
+                if spent > args.cpu_seconds:
+                    break
+            cpu = {"value": done / spent, "unit": "evals/s", "cores": oracle_threads(), "kind": "oracle",
+                   "sample": f"{done // (k + 1)} of the {Bsz} rows, two at a time ({done} evaluations, {spent:.1f} s; "
+                             "fp64 numpy, weights pre-widened)"}
         for c in ctxs:
             B.eh_destroy(c)
     else:

@@ -234,6 +234,29 @@ eh_status dssd_draft(eh_ctx* ctx, const void* h_positions, int64_t pos_stride, i
                      int32_t* fallback_token, int64_t* n_evals_out, void* stream);
 
 /*
+ * Verification bookkeeping (Section 4.3.1, "Verification phase"; the acceptance
+ * rate and the discarded tokens of Section 4.3.2): adds a batch of B verification
+ * rounds to five running counters on the device,
+ *   counters[0] += B                       rounds
+ *   counters[1] += sum_b len_b             tokens drafted
+ *   counters[2] += sum_b accepted_b        tokens committed from the drafts
+ *   counters[3] += sum_b (len_b - accepted_b)   tokens drafted for nothing
+ *   counters[4] += sum_b sum_{j < len_b} exit_layers[b, j]   (0 if exit_layers is NULL)
+ * so that counters[2] / counters[1] is the acceptance rate, counters[2] /
+ * counters[0] the mean accepted tokens per round and counters[4] / counters[1] the
+ * mean exit head during drafting.  The caller zeroes the counters to start.
+ *
+ * draft_len    NULL (every round drafted k tokens) or device [B] int32, clamped to [0, k]
+ * accepted     device [B] int32 (dssd_verify's output), clamped to [0, len_b]
+ * exit_layers  NULL or device [B, k] int32 (row-major), read only below len_b
+ * counters     device [5] int64
+ */
+enum { EH_TALLY_ROUNDS = 0, EH_TALLY_DRAFTED = 1, EH_TALLY_ACCEPTED = 2, EH_TALLY_WASTED = 3,
+       EH_TALLY_LAYER_SUM = 4, EH_TALLY_COUNT = 5 };
+eh_status dssd_tally(eh_ctx* ctx, const int32_t* draft_len, const int32_t* accepted, int32_t B, int32_t k,
+                     const int32_t* exit_layers, int64_t* counters, void* stream);
+
+/*
  * Threshold calibration of one head (Section 3.4.1, "Calibration of Confidence
  * Thresholds"), entropy as the confidence metric: the M calibration tokens are
  * ordered by ascending confidence (descending entropy); for a level epsilon the

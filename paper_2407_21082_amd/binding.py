@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
                 4: "EH_ERR_RANGE", 5: "EH_ERR_HIP", 6: "EH_ERR_WORKSPACE"}
 
 # every symbol include/eh.h declares
-EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft",
+EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally",
            "eh_calibrate", "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
 
 
@@ -58,6 +58,7 @@ def _load() -> C.CDLL:
     lib.eh_cascade.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.dssd_draft.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.dssd_tally.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     lib.eh_calibrate.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double), i32, vp, vp, vp]
     lib.eh_check.argtypes = [vp, vp]
     lib.eh_decode_trace.argtypes = [vp, i32, vp, i32]
@@ -66,7 +67,7 @@ def _load() -> C.CDLL:
     lib.eh_last_error.restype = C.c_char_p
     lib.eh_version.argtypes = []
     lib.eh_version.restype = C.c_char_p
-    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "eh_check"):
+    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_check"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -204,6 +205,13 @@ def dssd_draft(ctx: EhContext, h_positions: torch.Tensor, limit: int, eos_token:
     _check(lib.dssd_draft(ctx.handle, _ptr(h_positions), h_positions.stride(0), h_positions.stride(1),
                           h_positions.shape[0], limit, eos_token, _ptr(draft), _ptr(draft_len), _ptr(exit_layers),
                           _ptr(stop_reason), _ptr(fallback_token), _ptr(n_evals_out), _stream(stream)), ctx.handle)
+
+
+def dssd_tally(ctx: EhContext, draft_len: Optional[torch.Tensor], accepted: torch.Tensor, B: int, k: int,
+               exit_layers: Optional[torch.Tensor], counters: torch.Tensor, stream=None) -> None:
+    """counters: int64[5] on the device = rounds, drafted, accepted, wasted, exit-layer sum (accumulated)."""
+    _check(lib.dssd_tally(ctx.handle, _ptr(draft_len), _ptr(accepted), B, k, _ptr(exit_layers), _ptr(counters),
+                          _stream(stream)), ctx.handle)
 
 
 def eh_calibrate(ctx: EhContext, H: torch.Tensor, pred: torch.Tensor, ref: torch.Tensor, eps,

@@ -615,6 +615,19 @@ eh_status dssd_draft(eh_ctx* ctx, const void* h_positions, int64_t pos_stride, i
   return EH_OK;
 }
 
+eh_status dssd_tally(eh_ctx* ctx, const int32_t* draft_len, const int32_t* accepted, int32_t B, int32_t k,
+                     const int32_t* exit_layers, int64_t* counters, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (B < 0 || k < 0) return fail(ctx, EH_ERR_SHAPE, "B and k must be non-negative");
+  if (!counters || (B > 0 && !accepted)) return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
+  if (B == 0) return EH_OK;
+  DeviceGuard guard(ctx->device);
+  hipLaunchKernelGGL(tally_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, draft_len, accepted, B, k, exit_layers,
+                     (unsigned long long*)counters);
+  EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
+}
+
 eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const int32_t* ref, int64_t M,
                        const double* eps, int32_t n_eps, float* tau_out, int64_t* n_exit_out, void* stream) {
   if (!ctx) return EH_ERR_NULL;

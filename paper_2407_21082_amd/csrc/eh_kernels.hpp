@@ -646,6 +646,39 @@ static __global__ void draft_finish_kernel(const int* __restrict__ state, int* _
   if (fallback_token) *fallback_token = state[3];
 }
 
+// ---------------------------------------------------------------------------
+// Verification bookkeeping (Section 4.3.1, verification phase; the quantities
+// reported in Section 4.3.2): adds one batch of rounds to the running counters
+// {rounds, drafted, accepted, wasted, exit-layer sum}.  One workgroup; lengths
+// are clamped to [0, k] and accepted counts to [0, length].
+// ---------------------------------------------------------------------------
+static __global__ void tally_kernel(const int* __restrict__ draft_len, const int* __restrict__ accepted, int B, int k,
+                                    const int* __restrict__ exit_layers, unsigned long long* __restrict__ counters) {
+  long long drafted = 0, acc = 0, layers = 0;
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    int n = draft_len ? draft_len[b] : k;
+    n = n < 0 ? 0 : (n > k ? k : n);
+    int a = accepted[b];
+    a = a < 0 ? 0 : (a > n ? n : a);
+    drafted += n;
+    acc += a;
+    if (exit_layers)
+      for (int j = 0; j < n; ++j) layers += exit_layers[(int64_t)b * k + j];
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    drafted += __shfl_xor(drafted, o);
+    acc += __shfl_xor(acc, o);
+    layers += __shfl_xor(layers, o);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    atomicAdd(&counters[1], (unsigned long long)drafted);
+    atomicAdd(&counters[2], (unsigned long long)acc);
+    atomicAdd(&counters[3], (unsigned long long)(drafted - acc));
+    atomicAdd(&counters[4], (unsigned long long)layers);
+  }
+  if (threadIdx.x == 0) atomicAdd(&counters[0], (unsigned long long)B);
+}
+
 static __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

@@ -630,3 +630,37 @@ def test_dssd_draft_errors(B):
     with pytest.raises(B.EhError):
         B.dssd_draft(ctx, hid.h.permute(1, 0, 2), 4, -1, i32(4), i32(1), i32(4))
     B.eh_destroy(ctx)
+
+
+# --------------------------------------------------------------- verification bookkeeping
+def test_dssd_tally_matches_oracle(B, small_ctx):
+    rng = np.random.default_rng(77)
+    counters = torch.zeros(5, dtype=torch.int64, device=DEV)
+    total = dict(rounds=0, drafted=0, accepted=0, wasted=0, exit_layer_sum=0)
+    for Bsz, k, with_len, with_layers in ((1, 1, True, True), (16, 8, True, True), (1000, 32, True, True),
+                                          (300, 5, False, True), (77, 9, True, False), (64, 0, True, True)):
+        lens = rng.integers(0, k + 1, size=Bsz)
+        acc = np.array([rng.integers(0, n + 1) for n in (lens if with_len else np.full(Bsz, k))])
+        layers = rng.integers(0, 24, size=(Bsz, max(k, 1)))[:, :k]
+        want = O.dssd_tally(lens if with_len else np.full(Bsz, k), acc, layers if with_layers else None)
+        for key in total:
+            total[key] += want[key]
+        B.dssd_tally(small_ctx, torch.tensor(lens, dtype=torch.int32, device=DEV) if with_len else None,
+                     torch.tensor(acc, dtype=torch.int32, device=DEV), Bsz, k,
+                     torch.tensor(layers, dtype=torch.int32, device=DEV).contiguous() if with_layers else None,
+                     counters)
+        torch.cuda.synchronize()
+        assert counters.tolist() == [total[x] for x in ("rounds", "drafted", "accepted", "wasted", "exit_layer_sum")]
+    # zero rounds change nothing; values outside their range are clamped (length to [0, k], accepted to [0, length])
+    before = counters.tolist()
+    B.dssd_tally(small_ctx, None, torch.zeros(1, dtype=torch.int32, device=DEV), 0, 4, None, counters)
+    torch.cuda.synchronize()
+    assert counters.tolist() == before
+    B.dssd_tally(small_ctx, torch.tensor([9, -3, 2], dtype=torch.int32, device=DEV),
+                 torch.tensor([7, 1, -1], dtype=torch.int32, device=DEV), 3, 4, None, counters)
+    torch.cuda.synchronize()
+    want = O.dssd_tally([4, 0, 2], [4, 0, 0])
+    assert counters.tolist() == [before[0] + 3, before[1] + want["drafted"], before[2] + want["accepted"],
+                                 before[3] + want["wasted"], before[4]]
+    with pytest.raises(B.EhError):
+        B.dssd_tally(small_ctx, None, torch.zeros(1, dtype=torch.int32, device=DEV), 1, 4, None, None)
