@@ -33,6 +33,10 @@ What each function follows (arXiv 2407.21082):
 * ``dssd_tally``: Section 4.3.1, "Verification phase", and the figures of Section
   4.3.2: tokens drafted, committed and discarded over verification rounds, the
   acceptance rate (committed / drafted) and the mean accepted tokens per round.
+* ``token_losses`` / ``head_losses``: Section 3.3, "Losses": the cross-entropy of the
+  head's distribution against the labels, the Kullback-Leibler divergence of the
+  head's distribution from the main model's (head first), their means over the
+  sequence and the hybrid objective alpha L_CE + (1 - alpha) L_KL.  Forward only.
 * ``confidence_metrics``: Section 3.4.1: the two confidence metrics the paper
   compares entropy with, the maximum probability and the difference between the
   two largest probabilities ("breaking ties").
@@ -72,6 +76,8 @@ __all__ = [
     "head_metrics",
     "correctness",
     "calibrate_threshold",
+    "token_losses",
+    "head_losses",
 ]
 
 
@@ -405,6 +411,58 @@ def dssd_tally(draft_len, accepted, exit_layers=None):
     return dict(rounds=rounds, drafted=drafted, accepted=acc, wasted=waste, exit_layer_sum=layer_sum,
                 acceptance_rate=acc / drafted if drafted else float("nan"),
                 mean_accepted=acc / rounds if rounds else float("nan"))
+
+
+# ----------------------------------------------------------------------------
+# Training objectives, forward only (Section 3.3, "Losses")
+# ----------------------------------------------------------------------------
+def token_losses(z_head, z_model, labels=None):
+    """Per-token loss terms of Section 3.3 from materialised logits.
+
+    y_hat = softmax(z_head) is the exit head's distribution and f = softmax(z_model)
+    the main model's.  For every token t:
+      kl[t] = sum_v y_hat_v * log(y_hat_v / f_v)      (the head's distribution comes first,
+                                                       as in the section's L_KL(y_hat || f_theta))
+      ce[t] = -log y_hat_{labels[t]}                  (NaN without labels)
+    Log-probabilities are taken as z - lse so that a vanishing probability contributes
+    0 * finite = 0 (the 0 log 0 = 0 convention) instead of 0 * inf.  Returns (kl, ce).
+    """
+    zs = np.asarray(z_head, dtype=np.float64)
+    zt = np.asarray(z_model, dtype=np.float64)
+    if zs.ndim == 1:
+        zs, zt = zs[None, :], zt[None, :]
+    L = zs.shape[0]
+    kl = np.empty(L)
+    ce = np.full(L, np.nan)
+    for t in range(L):
+        ms, mt = zs[t].max(), zt[t].max()
+        if not (np.isfinite(ms) and np.isfinite(mt)):
+            kl[t] = np.nan
+            continue
+        logp = zs[t] - (ms + np.log(np.exp(zs[t] - ms).sum()))     # log y_hat
+        logq = zt[t] - (mt + np.log(np.exp(zt[t] - mt).sum()))     # log f
+        kl[t] = (np.exp(logp) * (logp - logq)).sum()
+        if labels is not None:
+            ce[t] = -logp[int(labels[t])]
+    return kl, ce
+
+
+def head_losses(h_head, h_model, gamma_head, beta_head, W_head, gamma_model, beta_model, W_model,
+                labels=None, alpha=0.5, eps=1e-5, bf16=False):
+    """The three training objectives of Section 3.3 for one exit head on a sequence of
+    L tokens: both heads are LayerNorm -> projection (Section 3.2) on their own hidden
+    states, h_head [L, d] from the head's block and h_model [L, d] from the last.
+
+    L_CE = (1/L) sum_t ce[t]; L_KL = (1/L) sum_t kl[t]; L_hyb = alpha L_CE + (1 - alpha) L_KL.
+    Returns dict(kl[L], ce[L], L_kl, L_ce, L_hyb); the CE terms are NaN without labels.
+    """
+    zs = head_logits(layernorm(h_head, gamma_head, beta_head, eps, bf16_out=bf16), W_head)
+    zt = head_logits(layernorm(h_model, gamma_model, beta_model, eps, bf16_out=bf16), W_model)
+    kl, ce = token_losses(zs, zt, labels)
+    L = kl.shape[0]
+    L_kl = kl.sum() / L if L else float("nan")
+    L_ce = ce.sum() / L if L else float("nan")
+    return dict(kl=kl, ce=ce, L_kl=L_kl, L_ce=L_ce, L_hyb=alpha * L_ce + (1.0 - alpha) * L_kl)
 
 
 # ----------------------------------------------------------------------------

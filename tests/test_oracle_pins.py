@@ -652,3 +652,107 @@ def test_tally_is_additive_and_handles_nothing_drafted():
     assert z["drafted"] == 0 and math.isnan(z["acceptance_rate"]) and z["mean_accepted"] == 0.0
     e = O.dssd_tally([], [])
     assert e["rounds"] == 0 and math.isnan(e["mean_accepted"])
+
+
+# ---------------------------------------------------------------- training objectives (Section 3.3)
+def test_kl_direction_and_two_class_values():
+    """Hand-computed two-class values; the two directions differ, so a swapped operand fails."""
+    zp, zq = np.log([0.5, 0.5]), np.log([0.9, 0.1])
+    kl_pq, _ = O.token_losses(zp, zq)
+    kl_qp, _ = O.token_losses(zq, zp)
+    assert abs(kl_pq[0] - (0.5 * math.log(0.5 / 0.9) + 0.5 * math.log(0.5 / 0.1))) < 1e-14
+    assert abs(kl_qp[0] - (0.9 * math.log(0.9 / 0.5) + 0.1 * math.log(0.1 / 0.5))) < 1e-14
+    assert abs(kl_pq[0] - 0.5108256237659907) < 1e-12 and abs(kl_qp[0] - 0.3680642071684971) < 1e-12
+    # logits, not probabilities, go in: a shift of either row of logits changes nothing
+    kl_s, _ = O.token_losses(zp + 3.25, zq - 7.5)
+    assert abs(kl_s[0] - kl_pq[0]) < 1e-13
+
+
+def test_kl_against_scipy_and_gibbs():
+    from scipy.special import rel_entr, softmax
+    from scipy.stats import entropy
+    rng = np.random.default_rng(3)
+    zs = rng.normal(size=(40, 300)) * rng.uniform(0.1, 8.0, size=(40, 1))
+    zt = rng.normal(size=(40, 300)) * rng.uniform(0.1, 8.0, size=(40, 1))
+    kl, ce = O.token_losses(zs, zt)
+    p, q = softmax(zs, axis=1), softmax(zt, axis=1)
+    ref = rel_entr(p, q).sum(axis=1)                 # sum p log(p/q): the head's distribution first
+    assert np.allclose(kl, ref, rtol=1e-10, atol=1e-12)
+    assert np.allclose(kl, [entropy(p[t], q[t]) for t in range(40)], rtol=1e-10, atol=1e-12)
+    assert not np.allclose(kl, rel_entr(q, p).sum(axis=1), rtol=1e-3)      # not the other direction
+    assert (kl >= 0).all() and np.isnan(ce).all()
+    same, _ = O.token_losses(zs, zs + 1.5)           # the same distribution: exactly no divergence
+    assert np.abs(same).max() < 1e-13
+
+
+def test_kl_from_uniform_is_logV_minus_entropy_golden():
+    """Against the uniform distribution KL(y_hat || u) = ln V - H(y_hat): ties the loss to the
+    closed-form entropies of the golden table."""
+    for V, n, a, H_ref, _ in _golden_rows():
+        z = np.zeros(V)
+        z[:n] = a
+        kl, _ = O.token_losses(z, np.full(V, -2.0))
+        assert abs(kl[0] - (math.log(V) - H_ref)) < 1e-9 * max(1.0, math.log(V)), (V, n, a)
+
+
+def test_kl_vanishing_probability_and_nonfinite():
+    z = np.array([0.0, -2000.0, 1.0])                # exp underflows to exactly 0 for class 1
+    kl, ce = O.token_losses(z, np.array([0.0, 5.0, 1.0]), labels=[2])
+    p = np.exp([0.0, 1.0]) / (1.0 + math.e)
+    lq = np.array([0.0, 1.0]) - math.log(1.0 + math.e ** 5 + math.e)
+    assert abs(kl[0] - (p * (np.log(p) - lq)).sum()) < 1e-12
+    assert abs(ce[0] + math.log(p[1])) < 1e-12
+    kl, _ = O.token_losses(np.array([0.0, float("nan")]), np.array([0.0, 1.0]))
+    assert np.isnan(kl[0])
+
+
+def test_cross_entropy_values_and_relation_to_kl():
+    rng = np.random.default_rng(8)
+    V = 50
+    zs = rng.normal(size=(30, V)) * 3
+    labels = rng.integers(0, V, size=30)
+    _, ce = O.token_losses(zs, zs, labels)
+    lse = np.log(np.exp(zs).sum(axis=1))
+    assert np.allclose(ce, lse - zs[np.arange(30), labels], rtol=1e-12)
+    _, ce_u = O.token_losses(np.zeros((1, V)), np.zeros((1, V)), [7])
+    assert abs(ce_u[0] - math.log(V)) < 1e-14         # uniform prediction: ln V whatever the label
+    # CE against a label is the divergence of the label's (nearly) one-hot distribution from the
+    # prediction, read in the other direction: KL(onehot || y_hat) = -log y_hat_label
+    for t in range(5):
+        onehot = np.full(V, -800.0)
+        onehot[labels[t]] = 0.0
+        kl_rev, _ = O.token_losses(onehot, zs[t])
+        assert abs(kl_rev[0] - ce[t]) < 1e-10
+
+
+def test_head_losses_means_and_hybrid():
+    rng = np.random.default_rng(21)
+    L, d, V = 12, 24, 70
+    Ws, Wt = rng.normal(size=(V, d)) / 3, rng.normal(size=(V, d)) / 3
+    g1, b1, g2, b2 = rng.normal(size=d), rng.normal(size=d), rng.normal(size=d), rng.normal(size=d)
+    hs, ht = rng.normal(size=(L, d)) * 2, rng.normal(size=(L, d)) * 2
+    labels = rng.integers(0, V, size=L)
+    r = O.head_losses(hs, ht, g1, b1, Ws, g2, b2, Wt, labels, alpha=0.3)
+    # per token it is the head evaluation's own logits: lse and entropy tie the two code paths
+    zs = O.head_logits(O.layernorm(hs, g1, b1), Ws)
+    zt = O.head_logits(O.layernorm(ht, g2, b2), Wt)
+    H, lse, _, _ = O.softmax_stats(zs)
+    _, lse_t, _, _ = O.softmax_stats(zt)
+    ps = np.exp(zs - lse[:, None])
+    cross = -(ps * (zt - lse_t[:, None])).sum(axis=1)            # cross-entropy H(y_hat, f)
+    assert np.allclose(r["kl"], cross - H, rtol=1e-10, atol=1e-12)   # KL = H(p, q) - H(p)
+    assert np.allclose(r["ce"], lse - zs[np.arange(L), labels], rtol=1e-12)
+    assert abs(r["L_kl"] - r["kl"].mean()) < 1e-14 and abs(r["L_ce"] - r["ce"].mean()) < 1e-14
+    assert abs(r["L_hyb"] - (0.3 * r["L_ce"] + 0.7 * r["L_kl"])) < 1e-14
+    # the mean is over the sequence: repeating the sequence leaves every objective unchanged,
+    # and the same head on the same hidden states as the model has no divergence from it
+    r2 = O.head_losses(np.tile(hs, (2, 1)), np.tile(ht, (2, 1)), g1, b1, Ws, g2, b2, Wt, np.tile(labels, 2), 0.3)
+    assert abs(r2["L_kl"] - r["L_kl"]) < 1e-13 and abs(r2["L_hyb"] - r["L_hyb"]) < 1e-13
+    r0 = O.head_losses(hs, hs, g1, b1, Ws, g1, b1, Ws, labels, 1.0)
+    assert abs(r0["L_kl"]) < 1e-13 and abs(r0["L_hyb"] - r0["L_ce"]) < 1e-14
+    # bf16 mode rounds both heads' normalised activations, nothing else
+    rb = O.head_losses(hs, ht, g1, b1, Ws, g2, b2, Wt, labels, 0.3, bf16=True)
+    zs_b = O.head_logits(O.round_to_bf16(O.layernorm(hs, g1, b1)), Ws)
+    zt_b = O.head_logits(O.round_to_bf16(O.layernorm(ht, g2, b2)), Wt)
+    klb, ceb = O.token_losses(zs_b, zt_b, labels)
+    assert np.array_equal(rb["kl"], klb) and np.array_equal(rb["ce"], ceb)
