@@ -257,6 +257,27 @@ eh_status dssd_tally(eh_ctx* ctx, const int32_t* draft_len, const int32_t* accep
                      const int32_t* exit_layers, int64_t* counters, void* stream);
 
 /*
+ * The training objectives of Section 3.3 ("Losses") for one exit head on a sequence
+ * of n_rows tokens, forward only, without materialising either distribution: the
+ * head (LayerNorm + projection on h_head) and the model's own head (the context's
+ * last head, on h_model) are projected together and, per token t,
+ *   kl[t] = sum_v y_hat_v log(y_hat_v / f_v)    y_hat = softmax(head), f = softmax(model)
+ *   ce[t] = -log y_hat_{labels[t]}              (NaN without labels or for a label outside [0, V))
+ * are accumulated on the fly;  loss[0] = L_CE = mean ce, loss[1] = L_KL = mean kl,
+ * loss[2] = L_hyb = alpha * L_CE + (1 - alpha) * L_KL.
+ *
+ * h_head, h_model   device, n_rows rows of d elements (h_dtype), row strides in elements
+ * labels            NULL or device [n_rows] int32
+ * kl, ce            NULL or device [n_rows] float
+ * loss              device [3] float
+ * bf16 heads without a bias vector only (EH_ERR_DTYPE otherwise); 1 <= n_rows <= max_rows.
+ * The first call allocates its workspace in the context (and synchronises the device).
+ */
+eh_status eh_head_losses(eh_ctx* ctx, int32_t head, const void* h_head, int64_t row_stride_head,
+                         const void* h_model, int64_t row_stride_model, const int32_t* labels,
+                         int32_t n_rows, float alpha, float* kl, float* ce, float* loss, void* stream);
+
+/*
  * Threshold calibration of one head (Section 3.4.1, "Calibration of Confidence
  * Thresholds"), entropy as the confidence metric: the M calibration tokens are
  * ordered by ascending confidence (descending entropy); for a level epsilon the

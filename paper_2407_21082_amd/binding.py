@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
                 4: "EH_ERR_RANGE", 5: "EH_ERR_HIP", 6: "EH_ERR_WORKSPACE"}
 
 # every symbol include/eh.h declares
-EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally",
+EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses",
            "eh_calibrate", "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
 
 
@@ -59,6 +59,7 @@ def _load() -> C.CDLL:
     lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.dssd_draft.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.dssd_tally.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.eh_head_losses.argtypes = [vp, i32, vp, i64, vp, i64, vp, i32, C.c_float, vp, vp, vp, vp]
     lib.eh_calibrate.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double), i32, vp, vp, vp]
     lib.eh_check.argtypes = [vp, vp]
     lib.eh_decode_trace.argtypes = [vp, i32, vp, i32]
@@ -67,7 +68,7 @@ def _load() -> C.CDLL:
     lib.eh_last_error.restype = C.c_char_p
     lib.eh_version.argtypes = []
     lib.eh_version.restype = C.c_char_p
-    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_check"):
+    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses", "eh_check"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -212,6 +213,15 @@ def dssd_tally(ctx: EhContext, draft_len: Optional[torch.Tensor], accepted: torc
     """counters: int64[5] on the device = rounds, drafted, accepted, wasted, exit-layer sum (accumulated)."""
     _check(lib.dssd_tally(ctx.handle, _ptr(draft_len), _ptr(accepted), B, k, _ptr(exit_layers), _ptr(counters),
                           _stream(stream)), ctx.handle)
+
+
+def eh_head_losses(ctx: EhContext, head: int, h_head: torch.Tensor, h_model: torch.Tensor,
+                   labels: Optional[torch.Tensor], n_rows: int, alpha: float, kl: Optional[torch.Tensor],
+                   ce: Optional[torch.Tensor], loss: torch.Tensor, stream=None) -> None:
+    """h_head, h_model: [n_rows, d] (row stride free); loss: float[3] = L_CE, L_KL, L_hyb."""
+    _check(lib.eh_head_losses(ctx.handle, head, _ptr(h_head), h_head.stride(0), _ptr(h_model), h_model.stride(0),
+                              _ptr(labels), n_rows, alpha, _ptr(kl), _ptr(ce), _ptr(loss), _stream(stream)),
+           ctx.handle)
 
 
 def eh_calibrate(ctx: EhContext, H: torch.Tensor, pred: torch.Tensor, ref: torch.Tensor, eps,

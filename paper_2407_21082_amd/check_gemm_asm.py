@@ -25,7 +25,7 @@ import re
 import sys
 from collections import deque
 
-KERNEL_RE = re.compile(r"^(_Z\w*gemm(?:32)?_stats_kernel\w*):")
+KERNEL_RE = re.compile(r"^(_Z\w*gemm(?:32)?_(?:stats|kl)_kernel\w*):")
 LABEL_RE = re.compile(r"^(\.L\w+):")
 VREG_RE = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
 UNTRACKED_RE = re.compile(r"^global_load_dwordx4\s+v\[(\d+):(\d+)\]\s*,")  # any addressing form

@@ -327,6 +327,29 @@ namespace {
 
 // eh_eval_heads and eh_eval_heads_metrics.  `metrics`: also the maximum probability and the
 // difference of the two largest probabilities (either output may be NULL).
+// The many-heads workspace: per head, activations for max_rows rows (plus the zero blocks the
+// batched kernel may read past them), one set of partial statistics and one of second largest
+// logits.  Grow-only, kept by the context; the old one may still be in use on a stream.
+eh_status ensure_mh(eh_ctx* ctx, int n_heads_needed) {
+  if (ctx->mh_heads >= n_heads_needed) return EH_OK;
+  const size_t y_stride = (size_t)(ctx->R_pad_max / 16 + 32) * ctx->KS * kWave;
+  const size_t part_stride = (size_t)kStreamGrid * ctx->R_pad_max;
+  EH_HIP(ctx, hipDeviceSynchronize());
+  eh::frag_t* y = nullptr;
+  eh::Stats* pt = nullptr;
+  float* sec = nullptr;
+  hipError_t e = dev_alloc(ctx, &y, y_stride * n_heads_needed);
+  if (e == hipSuccess) e = dev_alloc(ctx, &pt, part_stride * n_heads_needed);
+  if (e == hipSuccess) e = dev_alloc(ctx, &sec, part_stride * n_heads_needed);
+  if (e == hipSuccess) e = hipMemset(y, 0, y_stride * n_heads_needed * sizeof(frag_t));
+  EH_HIP(ctx, e);
+  ctx->mh_yf = y;
+  ctx->mh_partials = pt;
+  ctx->mh_second = sec;
+  ctx->mh_heads = n_heads_needed;
+  return EH_OK;
+}
+
 eh_status eval_heads_impl(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, const void* h_layers,
                           int64_t layer_stride, int64_t row_stride, int32_t n_rows, float* H, float* lse,
                           int32_t* argmax, bool metrics, float* max_prob, float* margin, void* stream) {
@@ -360,22 +383,8 @@ eh_status eval_heads_impl(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, cons
   // them), one set of partial statistics and one of second largest logits
   const size_t y_stride = (size_t)(ctx->R_pad_max / 16 + 32) * ctx->KS * kWave;
   const size_t part_stride = (size_t)kStreamGrid * ctx->R_pad_max;
-  if (ctx->mh_heads < n_heads_eval) {
-    // grow-only workspace kept by the context; the old one may still be in use on a stream
-    EH_HIP(ctx, hipDeviceSynchronize());
-    eh::frag_t* y = nullptr;
-    eh::Stats* pt = nullptr;
-    float* sec = nullptr;
-    hipError_t e = dev_alloc(ctx, &y, y_stride * n_heads_eval);
-    if (e == hipSuccess) e = dev_alloc(ctx, &pt, part_stride * n_heads_eval);
-    if (e == hipSuccess) e = dev_alloc(ctx, &sec, part_stride * n_heads_eval);
-    if (e == hipSuccess) e = hipMemset(y, 0, y_stride * n_heads_eval * sizeof(frag_t));
-    EH_HIP(ctx, e);
-    ctx->mh_yf = y;
-    ctx->mh_partials = pt;
-    ctx->mh_second = sec;
-    ctx->mh_heads = n_heads_eval;
-  }
+  st = ensure_mh(ctx, n_heads_eval);
+  if (st != EH_OK) return st;
   const int R_pad = (n_rows + 31) & ~31;
   hipLaunchKernelGGL((ln_pack_heads_kernel<DtBf16, 32>), dim3(R_pad, n_heads_eval), dim3(64), 0, s, h_layers,
                      layer_stride, row_stride, n_rows, R_pad, ctx->d, ctx->KS,
@@ -624,6 +633,45 @@ eh_status dssd_tally(eh_ctx* ctx, const int32_t* draft_len, const int32_t* accep
   DeviceGuard guard(ctx->device);
   hipLaunchKernelGGL(tally_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, draft_len, accepted, B, k, exit_layers,
                      (unsigned long long*)counters);
+  EH_HIP(ctx, hipGetLastError());
+  return EH_OK;
+}
+
+eh_status eh_head_losses(eh_ctx* ctx, int32_t head, const void* h_head, int64_t row_stride_head,
+                         const void* h_model, int64_t row_stride_model, const int32_t* labels, int32_t n_rows,
+                         float alpha, float* kl, float* ce, float* loss, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (head < 0 || head >= ctx->n_heads) return fail(ctx, EH_ERR_RANGE, "head out of range");
+  if (ctx->dtype != EH_BF16 || !ctx->bias.empty())
+    return fail(ctx, EH_ERR_DTYPE, "the fused objectives need bf16 heads without a bias vector");
+  if (n_rows <= 0) return fail(ctx, EH_ERR_SHAPE, "the mean over an empty sequence is undefined");
+  if (!h_head || !h_model || !loss) return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
+  eh_status st = check_rows(ctx, h_head, row_stride_head, n_rows);
+  if (st == EH_OK) st = check_rows(ctx, h_model, row_stride_model, n_rows);
+  if (st != EH_OK) return st;
+  DeviceGuard guard(ctx->device);
+  hipStream_t s = (hipStream_t)stream;
+  st = ensure_mh(ctx, 2);
+  if (st != EH_OK) return st;
+  if (!ctx->kl_partials) {
+    EH_HIP(ctx, dev_alloc(ctx, &ctx->kl_partials, (size_t)kStreamGrid * ctx->R_pad_max));
+    EH_HIP(ctx, dev_alloc(ctx, &ctx->kl_rows, (size_t)2 * ctx->R_pad_max));
+  }
+  const size_t y_stride = (size_t)(ctx->R_pad_max / 16 + 32) * ctx->KS * kWave;
+  const int R_pad = (n_rows + 31) & ~31;
+  const int fin = ctx->n_heads - 1;
+  hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), dim3(R_pad), dim3(64), 0, s, h_head, row_stride_head,
+                     (const int*)nullptr, (const int*)nullptr, n_rows, R_pad, ctx->d, ctx->KS, ctx->gamma[head],
+                     ctx->beta[head], ctx->eps, ctx->mh_yf);
+  hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), dim3(R_pad), dim3(64), 0, s, h_model, row_stride_model,
+                     (const int*)nullptr, (const int*)nullptr, n_rows, R_pad, ctx->d, ctx->KS, ctx->gamma[fin],
+                     ctx->beta[fin], ctx->eps, ctx->mh_yf + y_stride);
+  int n_parts = 0;
+  EH_HIP(ctx, gemm32_kl_launch(ctx, head, fin, n_rows, ctx->mh_yf, ctx->mh_yf + y_stride, labels, ctx->kl_partials,
+                               &n_parts, s));
+  hipLaunchKernelGGL(kl_finalize_kernel, dim3(n_rows), dim3(64), 0, s, ctx->kl_partials, n_parts, R_pad, n_rows,
+                     ctx->V, ctx->kl_rows, kl, ce);
+  hipLaunchKernelGGL(kl_mean_kernel, dim3(1), dim3(256), 0, s, ctx->kl_rows, R_pad, n_rows, alpha, loss);
   EH_HIP(ctx, hipGetLastError());
   return EH_OK;
 }

@@ -160,4 +160,77 @@ __device__ __forceinline__ Stats stats_shfl_xor(const Stats& s, int mask) {
   return o;
 }
 
+// Running statistics for the training objectives (Section 3.3) of one token: the head's
+// logits zs and the model's logits zt of the same vocabulary entries arrive together.
+// Base-2 domain as above: ms = max zs*log2e, Ss = sum 2^(ts - ms), mt/St the same for the
+// model, C = sum 2^(ts - ms) * (zs - zt) (natural units), zl = the head's logit of the label.
+//   KL(head || model) = C / Ss - lse_s + lse_t,   CE = lse_s - zl,   lse = ln2 * (m + log2 S).
+struct KlStats {
+  float ms, Ss, C, mt, St, zl;
+  int lab;
+};
+
+__device__ __forceinline__ void kl_init(KlStats& s, int label) {
+  s.ms = kNegBig; s.Ss = 0.f; s.C = 0.f; s.mt = kNegBig; s.St = 0.f; s.zl = -INFINITY; s.lab = label;
+}
+
+__device__ __forceinline__ KlStats kl_merge(const KlStats& a, const KlStats& b) {
+  KlStats r;
+  r.ms = fmaxf(a.ms, b.ms);
+  const float ea = fast_exp2(a.ms - r.ms), eb = fast_exp2(b.ms - r.ms);
+  r.Ss = ea * a.Ss + eb * b.Ss;
+  r.C = ea * a.C + eb * b.C;
+  r.mt = fmaxf(a.mt, b.mt);
+  r.St = fast_exp2(a.mt - r.mt) * a.St + fast_exp2(b.mt - r.mt) * b.St;
+  r.zl = fmaxf(a.zl, b.zl);  // exactly one slice of the vocabulary holds the label
+  r.lab = a.lab;
+  return r;
+}
+
+// Four consecutive vocabulary rows row0..row0+3 of both heads (rows >= V are padding).
+__device__ __forceinline__ void kl_push4(KlStats& s, f32x4 zs, f32x4 zt, int row0, int V) {
+  const int nvalid = V - row0;
+  float a = -INFINITY, b = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (i < nvalid) {
+      a = fmaxf(a, zs[i]);
+      b = fmaxf(b, zt[i]);
+    }
+  }
+  const float na = a * kLog2e, nb = b * kLog2e;
+  if (na > s.ms) {
+    const float sc = fast_exp2(s.ms - na);
+    s.Ss *= sc;
+    s.C *= sc;
+    s.ms = na;
+  }
+  if (nb > s.mt) {
+    s.St *= fast_exp2(s.mt - nb);
+    s.mt = nb;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (i < nvalid) {
+      const float e = fast_exp2(zs[i] * kLog2e - s.ms);
+      s.Ss += e;
+      s.C += e * (zs[i] - zt[i]);
+      s.St += fast_exp2(zt[i] * kLog2e - s.mt);
+      if (row0 + i == s.lab) s.zl = zs[i];
+    }
+  }
+}
+
+__device__ __forceinline__ KlStats kl_shfl_xor(const KlStats& s, int mask) {
+  KlStats o;
+  o.ms = __shfl_xor(s.ms, mask);
+  o.Ss = __shfl_xor(s.Ss, mask);
+  o.C = __shfl_xor(s.C, mask);
+  o.mt = __shfl_xor(s.mt, mask);
+  o.St = __shfl_xor(s.St, mask);
+  o.zl = __shfl_xor(s.zl, mask);
+  o.lab = __shfl_xor(s.lab, mask);
+  return o;
+}
+
 }  // namespace eh

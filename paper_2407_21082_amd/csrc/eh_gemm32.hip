@@ -120,21 +120,33 @@ __host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Wa
 // wait on a compile-time count.
 // TOP2: also track the two largest logits of every token (z1 >= z2, with multiplicity) for the
 // "difference of the two largest probabilities" confidence metric (Section 3.4.1).
-template <int MT, int NB, bool ARGMAX_ONLY, bool TOP2>
+//
+// DUAL (the training objectives of Section 3.3, which need the logits of an exit head and of
+// the model's own head for the same token and vocabulary entry at once): the MT tiles are
+// MT/2 vocabulary tiles of the head's weights followed by the same MT/2 tiles of the model's
+// weights (wdelta bytes further), the NB token blocks are NB/2 blocks of the head's
+// activations followed by the same NB/2 blocks of the model's (yq2), and a tile only meets
+// the blocks of its own side: accumulator [m][j] and [m + MT/2][j] then hold the two logits
+// of the same (vocabulary row, token) in the same register of the same lane.
+template <int MT, int NB, bool ARGMAX_ONLY, bool TOP2, bool DUAL = false, typename ST = Stats>
 __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq,
                                        int T, int VT16, int KS, int V, int lane, int wave,
-                                       EH_LDS char* lds, Stats (&st)[NB]) {
+                                       EH_LDS char* lds, ST (&st)[DUAL ? NB / 2 : NB], long long wdelta = 0,
+                                       const frag_t* __restrict__ yq2 = nullptr) {
+  static_assert(!DUAL || (MT % 2 == 0 && NB % 2 == 0), "two equal sides");
+  constexpr int NA = DUAL ? NB / 2 : NB;  // accumulator tiles per weight tile
+  constexpr int MH = MT / 2, NH = NB / 2;
   constexpr int kDma = dma_per_wave(MT);
   constexpr int kGroup = kDma + 2 * NB;            // loads a wave issues per k-step
   constexpr int kInFlight = (kDepth - 1) * kGroup;  // younger than what SYNC needs
   static_assert(kInFlight < 64, "vmcnt field");
   constexpr int NF = 2 * MT;  // 16-row fragments per k-step
 
-  f32x16 acc[MT][NB];
+  f32x16 acc[MT][NA];
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
-    for (int n = 0; n < NB; ++n)
+    for (int n = 0; n < NA; ++n)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.f;
 
@@ -149,8 +161,10 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   for (int i = 0; i < kDma; ++i) {
     int f = wave + kG32Waves * i;
     if (f >= NF) f = (wave < NF) ? wave + kG32Waves * ((NF - 1 - wave) / kG32Waves) : NF - 1;
-    const int t16 = min(2 * T + f, VT16 - 1);  // a missing odd half tile repeats the last one (masked later)
-    wsrc[i] = ((long long)t16 * KS) << 10;
+    // a missing odd half tile repeats the last one (masked later)
+    const bool side2 = DUAL && f >= 2 * MH;
+    const int t16 = min(2 * T + (side2 ? f - 2 * MH : f), VT16 - 1);
+    wsrc[i] = (((long long)t16 * KS) << 10) + (side2 ? wdelta : 0);
     wdst[i] = f * 1024;
   }
   // weight fragments of k-step ks into their ring slot: this wave's i-th fragment, or all of them
@@ -164,8 +178,11 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   auto dma = [&](int ks) { static_for<kDma>([&](auto ic) { dma_part(ic, ks); }); };
   // activations: block n, k-step ks, half h -> fragment (n, 2*ks + h) of 2*KS per block
   const EH_GLOBAL char* ybase = uniform_ptr(yq);
+  const EH_GLOBAL char* ybase2 = uniform_ptr(DUAL ? yq2 : yq);
   auto load_b = [&](frag_t (&dst)[2], int n, int ks) {
-    const EH_GLOBAL char* p = ybase + (((long long)n * 2 * KS + 2 * min(ks, lastk)) << 10);
+    const bool side2 = DUAL && n >= NH;
+    const EH_GLOBAL char* p =
+        (side2 ? ybase2 : ybase) + (((long long)(side2 ? n - NH : n) * 2 * KS + 2 * min(ks, lastk)) << 10);
     load_untracked<0>(dst[0], p, lane16);
     load_untracked<1024>(dst[1], p, lane16);
   };
@@ -206,8 +223,11 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
       asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a[m][0]), "+v"(a[m][1]) : "n"(kLdsInFlight));
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
+        if (!DUAL || ((n < NH) == (m < MH))) {
+          const int j = DUAL ? (n < NH ? n : n - NH) : n;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) acc[m][n] = mma32(a[m][h], b[n][h], acc[m][n]);
+          for (int h = 0; h < 2; ++h) acc[m][j] = mma32(a[m][h], b[n][h], acc[m][j]);
+        }
         if (m == MT - 1) load_b(b[n], n, ks + kDepth);
       }
       if constexpr (m == 0) {
@@ -270,6 +290,24 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
 
   // accumulator register 4g+i of lane l: vocabulary row 32*tile + 8g + 4*(l/32) + i, token l%32
   const int half = lane >> 5;
+  if constexpr (DUAL) {
+#pragma unroll
+    for (int m = 0; m < MH; ++m) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int row0 = (T + m) * 32 + g * 8 + half * 4;
+#pragma unroll
+        for (int n = 0; n < NA; ++n) {
+          const f32x4 zs = {acc[m][n][4 * g], acc[m][n][4 * g + 1], acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]};
+          const f32x4 zt = {acc[m + MH][n][4 * g], acc[m + MH][n][4 * g + 1], acc[m + MH][n][4 * g + 2],
+                            acc[m + MH][n][4 * g + 3]};
+          kl_push4(st[n], zs, zt, row0, V);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    return;
+  } else {
   float z1[NB], z2[NB];
   EH_LDS float* top2 = (EH_LDS float*)(lds + g32_ring_bytes()) + threadIdx.x * 4;
   if constexpr (TOP2) {
@@ -302,6 +340,7 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   if constexpr (TOP2) {
 #pragma unroll
     for (int n = 0; n < NB; ++n) { top2[2 * n] = z1[n]; top2[2 * n + 1] = z2[n]; }
+  }
   }
 }
 
@@ -367,6 +406,71 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
   }
 }
 
+// The two projections of the training objectives (Section 3.3) fused: grid.x = workgroups over
+// the vocabulary, grid.y = groups of 4*NBH blocks of 32 tokens; a wave owns NBH token blocks,
+// for which it holds the head's and the model's activations, and walks its slice of the
+// vocabulary in passes of at most 3 tiles of 32 rows of both weight matrices.
+template <int NBH>
+__global__ __launch_bounds__(kG32Threads, 1) void gemm32_kl_kernel(
+    const frag_t* __restrict__ Wf, long long wdelta, const frag_t* __restrict__ yq, const frag_t* __restrict__ yq2,
+    int VT16, int KS, int V, int n_rows, int R_pad, const int* __restrict__ labels, KlStats* __restrict__ partials) {
+  extern __shared__ __attribute__((aligned(16))) char g32_smem[];
+  EH_LDS char* lds = (EH_LDS char*)g32_smem;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int live_blocks = (n_rows + 31) >> 5;
+  if (live_blocks - (int)(blockIdx.y * kG32Waves * NBH) <= 0) return;
+  const int nb_first = (blockIdx.y * kG32Waves + wave) * NBH;
+  const int nb_live = min(NBH, live_blocks - nb_first);
+  const int VT32 = (VT16 + 1) >> 1;
+  const int T0 = (int)((long long)VT32 * blockIdx.x / gridDim.x);
+  const int T1 = (int)((long long)VT32 * (blockIdx.x + 1) / gridDim.x);
+  KlStats st[NBH];
+#pragma unroll
+  for (int n = 0; n < NBH; ++n) {
+    const int token = (nb_first + n) * 32 + (lane & 31);
+    kl_init(st[n], (labels && token < n_rows) ? labels[token] : -1);
+  }
+  const frag_t* y1 = yq + (long long)nb_first * 2 * KS * kWave;
+  const frag_t* y2 = yq2 + (long long)nb_first * 2 * KS * kWave;
+  constexpr int kMaxMH = 3;
+  for (int t = T0; t < T1;) {
+    const int left = T1 - t;
+    const int passes = (left + kMaxMH - 1) / kMaxMH;
+    const int mh = (left + passes - 1) / passes;
+    switch (mh) {
+      case 3:
+        pass32<6, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, VT16, KS, V, lane, wave, lds, st, wdelta, y2);
+        break;
+      case 2:
+        pass32<4, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, VT16, KS, V, lane, wave, lds, st, wdelta, y2);
+        break;
+      default:
+        pass32<2, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, VT16, KS, V, lane, wave, lds, st, wdelta, y2);
+        break;
+    }
+    t += mh;
+  }
+#pragma unroll
+  for (int n = 0; n < NBH; ++n) {
+    st[n] = kl_merge(st[n], kl_shfl_xor(st[n], 32));  // lanes l and l+32 hold the same token
+    if (lane < 32 && n < nb_live) partials[(long long)blockIdx.x * R_pad + (nb_first + n) * 32 + lane] = st[n];
+  }
+}
+
+template <int NBH>
+void launch_kl(dim3 g, hipStream_t s, const frag_t* Wf, long long wdelta, const frag_t* yq, const frag_t* yq2,
+               int VT16, int KS, int V, int n_rows, int R_pad, const int* labels, KlStats* partials) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)gemm32_kl_kernel<NBH>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)g32_lds_bytes());
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm32_kl_kernel<NBH>), g, dim3(kG32Threads), g32_lds_bytes(), s, Wf, wdelta, yq, yq2, VT16,
+                     KS, V, n_rows, R_pad, labels, partials);
+}
+
 template <int NB, bool AO, bool TOP2>
 void launch32(dim3 g, hipStream_t s, const frag_t* Wf, const frag_t* yq, int VT16, int KS, int V,
               const int* n_rows_dev, int n_rows, int R_pad, Stats* partials, float* second) {
@@ -408,6 +512,26 @@ hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n
     else EH_L32(2, false, false);
   }
 #undef EH_L32
+  return hipGetLastError();
+}
+
+hipError_t gemm32_kl_launch(const eh_ctx* c, int head, int model_head, int n_rows, const frag_t* yf_head,
+                            const frag_t* yf_model, const int* labels, KlStats* partials, int* n_parts,
+                            hipStream_t s) {
+  const int R_pad = (n_rows + 31) & ~31;
+  const int blocks = R_pad / 32;
+  const int nbh = blocks <= kG32Waves ? 1 : 2;
+  const int groups = (blocks + kG32Waves * nbh - 1) / (kG32Waves * nbh);
+  const int cus = c->num_cu > 0 ? c->num_cu : 256;
+  const int VT32 = (c->VT + 1) / 2;
+  const int gx = std::max(1, std::min(VT32, cus / groups));
+  dim3 g(gx, groups);
+  *n_parts = gx;
+  const long long wdelta = (const char*)c->Wf[model_head] - (const char*)c->Wf[head];
+  if (nbh == 1)
+    launch_kl<1>(g, s, c->Wf[head], wdelta, yf_head, yf_model, c->VT, c->KS, c->V, n_rows, R_pad, labels, partials);
+  else
+    launch_kl<2>(g, s, c->Wf[head], wdelta, yf_head, yf_model, c->VT, c->KS, c->V, n_rows, R_pad, labels, partials);
   return hipGetLastError();
 }
 

@@ -38,6 +38,10 @@ struct eh_ctx {
   float* mh_second = nullptr;  // second largest logits, same shape as mh_partials
   int mh_heads = 0;
   CalibScratch calib;  // eh_calibrate's scratch, grown on demand
+  // workspace of eh_head_losses, allocated by its first call: partial statistics
+  // [kStreamGrid][R_pad_max] and the per-token loss terms [2][R_pad_max]
+  eh::KlStats* kl_partials = nullptr;
+  float* kl_rows = nullptr;
   float* ws_H = nullptr;        // [max_rows] internal outputs (cascade, verify)
   float* ws_lse = nullptr;
   int* ws_argmax = nullptr;
@@ -100,6 +104,13 @@ hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n
 hipError_t gemm32_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
                          const eh::frag_t* yf, eh::Stats* partials, float* second, int* n_parts,
                          hipStream_t s);
+// The fused projections of the training objectives (bf16, no bias vector): an exit head on
+// yf_head and the model's head on yf_model (both in the 32 x 16 operand order, same rows),
+// labels NULL or device [n_rows]; per-workgroup partial statistics go to
+// partials[*n_parts][n_rows rounded up to 32].
+hipError_t gemm32_kl_launch(const eh_ctx* ctx, int head, int model_head, int n_rows, const eh::frag_t* yf_head,
+                            const eh::frag_t* yf_model, const int* labels, eh::KlStats* partials, int* n_parts,
+                            hipStream_t s);
 // Threshold calibration of one head (eh_calib.hip): device inputs, host eps, device outputs.
 // Asynchronous on s; its scratch memory (about 20 bytes per token) lives in `sc`, grows on
 // demand (which synchronises the device) and is freed by the owner of `sc`.

@@ -679,6 +679,72 @@ static __global__ void tally_kernel(const int* __restrict__ draft_len, const int
   if (threadIdx.x == 0) atomicAdd(&counters[0], (unsigned long long)B);
 }
 
+// ---------------------------------------------------------------------------
+// Training objectives (Section 3.3): final merge of a token's partial statistics
+// (one wave per token), then the means over the sequence (one workgroup, fixed
+// summation order, fp64).
+// ---------------------------------------------------------------------------
+static __global__ __launch_bounds__(64) void kl_finalize_kernel(const KlStats* __restrict__ partials, int n_parts,
+                                                         int R_pad, int n_rows, int V,
+                                                         float* __restrict__ rows, float* __restrict__ kl_out,
+                                                         float* __restrict__ ce_out) {
+  const int p = blockIdx.x, lane = threadIdx.x;
+  if (p >= n_rows) return;
+  KlStats s;
+  kl_init(s, -1);
+  for (int g = lane; g < n_parts; g += kWave) {
+    const KlStats q = partials[(int64_t)g * R_pad + p];
+    const int lab = q.lab;
+    s = kl_merge(s, q);
+    s.lab = lab;
+  }
+#pragma unroll
+  for (int x = 32; x > 0; x >>= 1) {
+    const KlStats o = kl_shfl_xor(s, x);
+    const int lab = max(s.lab, o.lab);  // lanes that merged nothing still hold -1
+    s = kl_merge(s, o);
+    s.lab = lab;
+  }
+  if (lane == 0) {
+    const double Ss = (double)s.Ss, St = (double)s.St;
+    const double lse_s = kLn2d * ((double)s.ms + log2(Ss));
+    const double lse_t = kLn2d * ((double)s.mt + log2(St));
+    const float kl = (float)((double)s.C / Ss - lse_s + lse_t);
+    const float ce = (s.lab >= 0 && s.lab < V) ? (float)(lse_s - (double)s.zl) : NAN;
+    rows[p] = kl;
+    rows[R_pad + p] = ce;
+    if (kl_out) kl_out[p] = kl;
+    if (ce_out) ce_out[p] = ce;
+  }
+}
+
+// loss[0] = L_CE, loss[1] = L_KL, loss[2] = alpha * L_CE + (1 - alpha) * L_KL
+static __global__ __launch_bounds__(256) void kl_mean_kernel(const float* __restrict__ rows, int R_pad, int n_rows,
+                                                      float alpha, float* __restrict__ loss) {
+  __shared__ double skl[256], sce[256];
+  double a = 0.0, b = 0.0;
+  for (int r = threadIdx.x; r < n_rows; r += 256) {
+    a += (double)rows[r];
+    b += (double)rows[R_pad + r];
+  }
+  skl[threadIdx.x] = a;
+  sce[threadIdx.x] = b;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      skl[threadIdx.x] += skl[threadIdx.x + o];
+      sce[threadIdx.x] += sce[threadIdx.x + o];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double L_kl = skl[0] / n_rows, L_ce = sce[0] / n_rows;
+    loss[0] = (float)L_ce;
+    loss[1] = (float)L_kl;
+    loss[2] = (float)((double)alpha * L_ce + (1.0 - (double)alpha) * L_kl);
+  }
+}
+
 static __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

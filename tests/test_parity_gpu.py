@@ -664,3 +664,91 @@ def test_dssd_tally_matches_oracle(B, small_ctx):
                                  before[3] + want["wasted"], before[4]]
     with pytest.raises(B.EhError):
         B.dssd_tally(small_ctx, None, torch.zeros(1, dtype=torch.int32, device=DEV), 1, 4, None, None)
+
+
+# --------------------------------------------------------------- training objectives (Section 3.3)
+TOL_LOSS_ABS, TOL_LOSS_REL = 2e-3, 1e-4     # as for the entropy: fp32 logits, one exponential per logit
+
+
+def _loss_case(V, d, R, seed):
+    w = G.Workload("loss", d=d, V=V, n_heads=3, rows=R, dtype="bf16", seed=seed)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed + 5)
+    labels = torch.randint(0, V, (R,), generator=gen, device=DEV, dtype=torch.int32)
+    return w, heads, hid, labels
+
+
+def _oracle_losses(heads, hid, head, labels, alpha):
+    f = P.f64
+    fin = len(heads.W) - 1
+    return O.head_losses(f(hid.h[head]), f(hid.h[fin]), f(heads.gamma[head]), f(heads.beta[head]), f(heads.W[head]),
+                         f(heads.gamma[fin]), f(heads.beta[fin]), f(heads.W[fin]),
+                         None if labels is None else labels.cpu().numpy(), alpha, 1e-5, True)
+
+
+def _close(got, want):
+    return np.abs(got - want) <= TOL_LOSS_ABS + TOL_LOSS_REL * np.abs(want)
+
+
+@pytest.mark.parametrize("V,d,R", [(1000, 256, 5), (777, 512, 37), (2048, 256, 161), (1500, 160, 300), (33, 64, 33),
+                                   (4096, 128, 128), (50, 32, 1)])
+def test_head_losses_match_oracle(B, V, d, R):
+    w, heads, hid, labels = _loss_case(V, d, R, seed=V + d + R)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    for head, alpha in ((0, 0.3), (1, 0.75)):
+        kl = torch.full((R,), float("nan"), device=DEV)
+        ce = torch.full((R,), float("nan"), device=DEV)
+        loss = torch.full((3,), float("nan"), device=DEV)
+        B.eh_head_losses(ctx, head, hid.h[head], hid.h[2], labels, R, alpha, kl, ce, loss)
+        torch.cuda.synchronize()
+        want = _oracle_losses(heads, hid, head, labels, alpha)
+        kg, cg, lg = kl.double().cpu().numpy(), ce.double().cpu().numpy(), loss.double().cpu().numpy()
+        assert _close(kg, want["kl"]).all(), (head, np.abs(kg - want["kl"]).max())
+        assert _close(cg, want["ce"]).all(), (head, np.abs(cg - want["ce"]).max())
+        assert _close(lg, np.array([want["L_ce"], want["L_kl"], want["L_hyb"]])).all(), (lg, want["L_ce"], want["L_kl"])
+        assert (kg > -TOL_LOSS_ABS).all()
+    B.eh_destroy(ctx)
+
+
+def test_head_losses_special_cases(B):
+    V, d, R = 600, 128, 70
+    w, heads, hid, labels = _loss_case(V, d, R, seed=99)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    loss = torch.zeros(3, device=DEV)
+    kl = torch.zeros(R, device=DEV)
+    ce = torch.zeros(R, device=DEV)
+    # the model's head against itself: no divergence; alpha = 1 leaves the cross-entropy alone
+    B.eh_head_losses(ctx, 2, hid.h[2], hid.h[2], labels, R, 1.0, kl, ce, loss)
+    torch.cuda.synchronize()
+    want = _oracle_losses(heads, hid, 2, labels, 1.0)
+    assert kl.abs().max().item() <= 1e-5 and abs(loss[1].item()) <= 1e-5
+    assert _close(ce.double().cpu().numpy(), want["ce"]).all() and abs(loss[2].item() - loss[0].item()) <= 1e-6
+    # no labels: the divergence is unchanged, every cross-entropy term is NaN, and so are L_CE and L_hyb
+    B.eh_head_losses(ctx, 0, hid.h[0], hid.h[2], None, R, 0.5, kl, ce, loss)
+    torch.cuda.synchronize()
+    want = _oracle_losses(heads, hid, 0, None, 0.5)
+    assert _close(kl.double().cpu().numpy(), want["kl"]).all() and torch.isnan(ce).all()
+    assert math.isnan(loss[0].item()) and math.isnan(loss[2].item()) and _close(loss[1].item(), want["L_kl"])
+    # per-token outputs are optional; a strided view of the hidden states is accepted
+    wide = torch.zeros((R, 2 * d), dtype=hid.h.dtype, device=DEV)
+    wide[:, :d] = hid.h[0]
+    B.eh_head_losses(ctx, 0, wide[:, :d], hid.h[2], labels, R, 0.5, None, None, loss)
+    torch.cuda.synchronize()
+    want = _oracle_losses(heads, hid, 0, labels, 0.5)
+    assert _close(loss.double().cpu().numpy(), np.array([want["L_ce"], want["L_kl"], want["L_hyb"]])).all()
+    # a label outside the vocabulary gives that token a NaN cross-entropy, nothing else changes
+    bad = labels.clone()
+    bad[3] = V + 7
+    bad[4] = -1
+    B.eh_head_losses(ctx, 0, hid.h[0], hid.h[2], bad, R, 0.5, kl, ce, loss)
+    torch.cuda.synchronize()
+    c = ce.double().cpu().numpy()
+    assert np.isnan(c[3]) and np.isnan(c[4]) and _close(np.delete(c, [3, 4]), np.delete(want["ce"], [3, 4])).all()
+    assert _close(kl.double().cpu().numpy(), want["kl"]).all()
+    with pytest.raises(B.EhError):
+        B.eh_head_losses(ctx, 0, hid.h[0], hid.h[2], labels, 0, 0.5, None, None, loss)
+    with pytest.raises(B.EhError):
+        B.eh_head_losses(ctx, 5, hid.h[0], hid.h[2], labels, R, 0.5, None, None, loss)
+    B.eh_destroy(ctx)
