@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c1_decode",
-                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify", "f1_calibrate", "f3_draft"])
+                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify", "f1_calibrate", "f3_draft", "f4_losses"])
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per bench step (c1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -273,6 +273,78 @@ def bench_draft(args, torch, B, G, dev):
     print(json.dumps(line), flush=True)
 
 
+def bench_losses(args, torch, B, G, dev):
+    """The training objectives of Section 3.3, forward only, on config 2's shape: one step = the
+    KL / cross-entropy / hybrid objectives of each of the 23 exit heads against the model's head
+    on 512 tokens (one eh_head_losses call per exit head)."""
+    import numpy as np
+    w = G.CONFIGS["c2_calib"]
+    t_setup = time.time()
+    heads = G.make_heads(w, dev)
+    hid = G.make_hidden(w, heads, dev)
+    R, fin = w.rows, w.n_heads - 1
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    labels = torch.randint(0, w.V, (R,), generator=gen, device=dev, dtype=torch.int32)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    loss = torch.zeros((fin, 3), device=dev)
+
+    def step():
+        for l in range(fin):
+            B.eh_head_losses(ctx, l, hid.h[l], hid.h[fin], labels, R, 0.5, None, None, loss[l])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ev_s = ev0.elapsed_time(ev1) * 1e-3
+    launches = args.steps * fin
+    flops_per_launch = 2 * 2.0 * w.d * w.V * R          # two projections per call
+    avg_s = ev_s / launches
+    roof = {"bound": "mfma", "achieved": flops_per_launch / avg_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": flops_per_launch / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+            "kernel": "eh::gemm32_kl_kernel<2> (one launch = one exit head and the model's head on 512 tokens; the "
+                      "time per launch includes the two LayerNorm launches and the two reductions of the call)",
+            "avg_launch_us": avg_s * 1e6, "flops_per_launch": flops_per_launch, "launches": launches}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import eh_oracle as O
+        f64 = G.to_f64_numpy
+        Wt, gt, bt = f64(heads.W[fin]), f64(heads.gamma[fin]), f64(heads.beta[fin])
+        lab = labels.cpu().numpy()
+        done, spent, n_heads_done = 0, 0.0, 0
+        for l in range(fin):
+            Wl, gl, bl = f64(heads.W[l]), f64(heads.gamma[l]), f64(heads.beta[l])
+            hs, ht = f64(hid.h[l][:128]), f64(hid.h[fin][:128])
+            c0 = time.perf_counter()
+            O.head_losses(hs, ht, gl, bl, Wl, gt, bt, Wt, lab[:128], 0.5, 1e-5, True)
+            spent += time.perf_counter() - c0
+            done += 128
+            n_heads_done += 1
+            if spent > args.cpu_seconds:
+                break
+        cpu = {"value": done / spent, "unit": "token-head losses/s", "cores": oracle_threads(), "kind": "oracle",
+               "sample": f"the first 128 tokens of {n_heads_done} exit heads ({done} loss terms, {spent:.1f} s; "
+                         "fp64 numpy, weights pre-widened)"}
+    B.eh_destroy(ctx)
+    line = {"metric": "head_loss_terms_per_sec", "value": launches * R / dt, "unit": "token-head losses/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"f4_losses: d=2048 V=50304, {fin} exit heads x 512 tokens bf16 against the model's "
+                                   "head: KL, cross-entropy and hybrid objective per head",
+                       "L_kl_head0": float(loss[0, 1].item()), "L_ce_head0": float(loss[0, 0].item())},
+            "roofline": roof, "cpu_baseline": cpu, "setup_s": round(time.time() - t_setup, 1)}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -306,6 +378,8 @@ def main():
         return bench_calibrate(args, torch, B, G, dev)
     if args.workload == "f3_draft":
         return bench_draft(args, torch, B, G, dev)
+    if args.workload == "f4_losses":
+        return bench_losses(args, torch, B, G, dev)
     w = G.CONFIGS[args.workload]
     if args.library_gemm:
         R = max(w.rows, 16)

@@ -752,3 +752,38 @@ def test_head_losses_special_cases(B):
     with pytest.raises(B.EhError):
         B.eh_head_losses(ctx, 5, hid.h[0], hid.h[2], labels, R, 0.5, None, None, loss)
     B.eh_destroy(ctx)
+
+
+def test_head_losses_calibration_shape(B):
+    """Config 2's shape (d = 2048, V = 50304, 512 tokens): two exit heads against the model's head;
+    the oracle checks 40 sampled tokens per head, the means are checked for consistency with the
+    library's own per-token terms (fp64 mean of the returned values)."""
+    w = G.CONFIGS["c2_calib"]
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    R, fin = w.rows, w.n_heads - 1
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4242)
+    labels = torch.randint(0, w.V, (R,), generator=gen, device=DEV, dtype=torch.int32)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    sample = torch.arange(3, R, 13, device=DEV)[:40]
+    f = P.f64
+    Wt, gt, bt = f(heads.W[fin]), f(heads.gamma[fin]), f(heads.beta[fin])
+    for head in (2, 17):
+        kl = torch.zeros(R, device=DEV)
+        ce = torch.zeros(R, device=DEV)
+        loss = torch.zeros(3, device=DEV)
+        B.eh_head_losses(ctx, head, hid.h[head], hid.h[fin], labels, R, 0.25, kl, ce, loss)
+        torch.cuda.synchronize()
+        want = O.head_losses(f(hid.h[head][sample]), f(hid.h[fin][sample]), f(heads.gamma[head]), f(heads.beta[head]),
+                             f(heads.W[head]), gt, bt, Wt, labels[sample].cpu().numpy(), 0.25, 1e-5, True)
+        kg, cg = kl[sample].double().cpu().numpy(), ce[sample].double().cpu().numpy()
+        assert _close(kg, want["kl"]).all(), (head, np.abs(kg - want["kl"]).max())
+        assert _close(cg, want["ce"]).all(), (head, np.abs(cg - want["ce"]).max())
+        L_kl, L_ce = kl.double().mean().item(), ce.double().mean().item()
+        assert abs(loss[1].item() - L_kl) <= 1e-5 * max(1.0, abs(L_kl))
+        assert abs(loss[0].item() - L_ce) <= 1e-5 * max(1.0, abs(L_ce))
+        assert abs(loss[2].item() - (0.25 * L_ce + 0.75 * L_kl)) <= 1e-5 * max(1.0, abs(L_ce))
+        assert (kl > -TOL_LOSS_ABS).all() and torch.isfinite(kl).all() and torch.isfinite(ce).all()
+        print(f"head {head}: L_CE {loss[0].item():.4f} L_KL {loss[1].item():.4f}")
+    B.eh_destroy(ctx)
