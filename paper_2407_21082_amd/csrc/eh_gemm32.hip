@@ -85,6 +85,58 @@ __device__ __forceinline__ f32x16 mma32(const frag_t& a, const frag_t& b, f32x16
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// The 16 logits a lane holds of one 32-row tile (accumulator register j = 4g+i: vocabulary row
+// rowbase + 8g + i, increasing in j), all inside the vocabulary, pushed at once.  A single wave
+// per SIMD cannot hide the latency of a dependent chain, so the work is laid out as wide,
+// independent instruction groups: one maximum over the 16 (the running statistics are rescaled
+// at most once, in a branch that is rarely taken after the first tiles), then 16 independent
+// exponentials, then short sums.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+template <bool ARGMAX_ONLY>
+__device__ __forceinline__ void stats_push16(Stats& s, const f32x16& z, int rowbase) {
+  // eight three-way maxima (a NaN operand is ignored, as by fmaxf)
+  const float zmax = max3(max3(max3(z[0], z[1], z[2]), max3(z[3], z[4], z[5]), z[15]),
+                          max3(z[6], z[7], z[8]), max3(max3(z[9], z[10], z[11]), max3(z[12], z[13], z[14]), z[15]));
+  if (zmax > s.zb) {
+    int j = 15;
+#pragma unroll
+    for (int i = 14; i >= 0; --i) j = (z[i] == zmax) ? i : j;  // lowest index attaining the maximum
+    if (!ARGMAX_ONLY) {
+      const float mn = zmax * kLog2e;
+      const float dm = s.m - mn;
+      const float sc = fast_exp2(dm);
+      s.U = sc * (s.U + dm * s.S);
+      s.S = sc * s.S;
+      s.m = mn;
+    }
+    s.zb = zmax;
+    s.ib = rowbase + (j >> 2) * 8 + (j & 3);
+  }
+  if (!ARGMAX_ONLY) {
+    float t[16], e[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t[i] = z[i] * kLog2e - s.m;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) e[i] = fast_exp2(t[i]);
+    float S4[4], U4[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      S4[g] = (e[g] + e[g + 4]) + (e[g + 8] + e[g + 12]);
+      U4[g] = t[g] * e[g];
+      U4[g] += t[g + 4] * e[g + 4];
+      U4[g] += t[g + 8] * e[g + 8];
+      U4[g] += t[g + 12] * e[g + 12];
+    }
+    s.S += (S4[0] + S4[1]) + (S4[2] + S4[3]);
+    s.U += (U4[0] + U4[1]) + (U4[2] + U4[3]);
+  }
+}
+
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
 template <int N, typename F, int I = 0>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -316,6 +368,23 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   }
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
+    // wave-uniform: only the vocabulary's last tile can be ragged
+    if ((T + m + 1) * 32 <= V) {
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        stats_push16<ARGMAX_ONLY>(st[n], acc[m][n], (T + m) * 32 + half * 4);
+        if constexpr (TOP2) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float zi = acc[m][n][i];
+            z2[n] = fmaxf(z2[n], fminf(zi, z1[n]));
+            z1[n] = fmaxf(z1[n], zi);
+          }
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      continue;
+    }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int row0 = (T + m) * 32 + g * 8 + half * 4;
