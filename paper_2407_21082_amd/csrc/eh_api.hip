@@ -102,7 +102,7 @@ eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const
   const int RB = (batched && bf) ? 32 : 16;
   const int R_pad = (n_rows + RB - 1) / RB * RB;
   {
-    dim3 g(R_pad), b(64);
+    dim3 g(R_pad), b(kLnThreads);
     if (bf && RB == 32)
       hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
                          n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
@@ -386,7 +386,7 @@ eh_status eval_heads_impl(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, cons
   st = ensure_mh(ctx, n_heads_eval);
   if (st != EH_OK) return st;
   const int R_pad = (n_rows + 31) & ~31;
-  hipLaunchKernelGGL((ln_pack_heads_kernel<DtBf16, 32>), dim3(R_pad, n_heads_eval), dim3(64), 0, s, h_layers,
+  hipLaunchKernelGGL((ln_pack_heads_kernel<DtBf16, 32>), dim3(R_pad, n_heads_eval), dim3(kLnThreads), 0, s, h_layers,
                      layer_stride, row_stride, n_rows, R_pad, ctx->d, ctx->KS,
                      (const float* const*)(ctx->d_gamma + head0), (const float* const*)(ctx->d_beta + head0),
                      ctx->eps, ctx->mh_yf, (int64_t)y_stride);
@@ -479,7 +479,7 @@ eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride, in
     int* cnt = ctx->n_active[0];
     hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, s, cnt, (int64_t)3, 0);
     {
-      dim3 g(R_pad), b(64);
+      dim3 g(R_pad), b(kLnThreads);
       if (bf)
         hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, h_layers, row_stride, (const int*)nullptr,
                            (const int*)nullptr, n_rows, R_pad, ctx->d, ctx->KS, ctx->gamma[0], ctx->beta[0],
@@ -501,7 +501,7 @@ eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride, in
       const float* bn = last ? nullptr : ctx->beta[l + 1];
       float* Hl = H_out ? H_out + (int64_t)l * n_rows : nullptr;
 #define EH_POST(DT, RBV)                                                                              \
-  hipLaunchKernelGGL((cascade_post_kernel<DT, RBV>), dim3(n_rows), dim3(64), 0, s, ctx->partials, n_parts, \
+  hipLaunchKernelGGL((cascade_post_kernel<DT, RBV>), dim3(n_rows), dim3(kLnThreads), 0, s, ctx->partials, n_parts, \
                      R_pad, idx, live, n_rows, ctx->tau[l], last, l, exit_layer, token, Hl,            \
                      (unsigned long long*)n_evals_out, ctx->active[(l + 1) & 1], cnt + (l + 1) % 3,    \
                      cnt + (l + 2) % 3, hn, row_stride, ctx->d, ctx->KS, gn, bn, ctx->eps, ctx->yf)
@@ -549,7 +549,7 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, co
     const int RB = bf ? 32 : 16;
     const int R_pad = (int)((rows + RB - 1) / RB * RB);
     const int fin = ctx->n_heads - 1;
-    dim3 g(R_pad), b(64);
+    dim3 g(R_pad), b(kLnThreads);
     if (bf)
       hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, f_final, (int64_t)ctx->d, (const int*)nullptr,
                          (const int*)nullptr, (int)rows, R_pad, ctx->d, ctx->KS, ctx->gamma[fin], ctx->beta[fin],
@@ -660,10 +660,10 @@ eh_status eh_head_losses(eh_ctx* ctx, int32_t head, const void* h_head, int64_t 
   const size_t y_stride = (size_t)(ctx->R_pad_max / 16 + 32) * ctx->KS * kWave;
   const int R_pad = (n_rows + 31) & ~31;
   const int fin = ctx->n_heads - 1;
-  hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), dim3(R_pad), dim3(64), 0, s, h_head, row_stride_head,
+  hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), dim3(R_pad), dim3(kLnThreads), 0, s, h_head, row_stride_head,
                      (const int*)nullptr, (const int*)nullptr, n_rows, R_pad, ctx->d, ctx->KS, ctx->gamma[head],
                      ctx->beta[head], ctx->eps, ctx->mh_yf);
-  hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), dim3(R_pad), dim3(64), 0, s, h_model, row_stride_model,
+  hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), dim3(R_pad), dim3(kLnThreads), 0, s, h_model, row_stride_model,
                      (const int*)nullptr, (const int*)nullptr, n_rows, R_pad, ctx->d, ctx->KS, ctx->gamma[fin],
                      ctx->beta[fin], ctx->eps, ctx->mh_yf + y_stride);
   int n_parts = 0;

@@ -88,24 +88,44 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// LayerNorm of one row by one wave; out(c, chunk) receives the packed chunk c
-// (EPL consecutive outputs starting at k = c*EPL) for every c < n_chunks.
-template <typename DT, typename OutFn>
-__device__ __forceinline__ void wave_layernorm(const void* row, int d, int n_chunks,
-                                               const float* __restrict__ gamma,
-                                               const float* __restrict__ beta, float eps, int lane,
-                                               OutFn out) {
+// Rows are normalised by a workgroup of NW waves (kLnWaves in the kernels below; the decode
+// kernel has its own single-wave LayerNorm).  Sum over the workgroup: per wave, then over
+// the waves' totals in wave order through LDS (`red`, NW doubles, one array per call site
+// so that no barrier is needed between consecutive sums).
+constexpr int kLnWaves = 4;
+constexpr int kLnThreads = kLnWaves * kWave;
+template <int NW>
+__device__ __forceinline__ double group_sum(double v, double* red, int tid) {
+  v = wave_sum(v);
+  if (NW == 1) return v;
+  if ((tid & (kWave - 1)) == 0) red[tid >> 6] = v;
+  __syncthreads();
+  double t = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) t += red[w];
+  return t;
+}
+
+// LayerNorm of one row by NW waves (tid = thread in the group); out(c, chunk) receives the
+// packed chunk c (EPL consecutive outputs starting at k = c*EPL) for every c < n_chunks.
+// red: 2*NW doubles of LDS.
+template <typename DT, int NW, typename OutFn>
+__device__ __forceinline__ void group_layernorm(const void* row, int d, int n_chunks,
+                                                const float* __restrict__ gamma,
+                                                const float* __restrict__ beta, float eps, int tid,
+                                                double* red, OutFn out) {
+  constexpr int NT = NW * kWave;
   const int live_chunks = d / DT::EPL;
   double s = 0.0;
-  for (int c = lane; c < live_chunks; c += kWave) {
+  for (int c = tid; c < live_chunks; c += NT) {
     float x[DT::EPL];
     load_elems<DT>(row, c * DT::EPL, x);
 #pragma unroll
     for (int i = 0; i < DT::EPL; ++i) s += (double)x[i];
   }
-  const double mu = wave_sum(s) / (double)d;
+  const double mu = group_sum<NW>(s, red, tid) / (double)d;
   double v = 0.0;
-  for (int c = lane; c < live_chunks; c += kWave) {
+  for (int c = tid; c < live_chunks; c += NT) {
     float x[DT::EPL];
     load_elems<DT>(row, c * DT::EPL, x);
 #pragma unroll
@@ -114,9 +134,9 @@ __device__ __forceinline__ void wave_layernorm(const void* row, int d, int n_chu
       v += cdev * cdev;
     }
   }
-  const double var = wave_sum(v) / (double)d;
+  const double var = group_sum<NW>(v, red + NW, tid) / (double)d;
   const double rstd = 1.0 / sqrt(var + (double)eps);
-  for (int c = lane; c < n_chunks; c += kWave) {
+  for (int c = tid; c < n_chunks; c += NT) {
     frag_t o = mk_frag(0, 0, 0, 0);
     if (c < live_chunks) {
       float x[DT::EPL];
@@ -136,34 +156,37 @@ __device__ __forceinline__ void wave_layernorm(const void* row, int d, int n_chu
 // Same arithmetic, in the same order, for rows of at most kLnCache*64 chunks: the row is read
 // from memory once and kept in registers for the three sweeps (mean, variance, output).
 constexpr int kLnCache = 8;
-template <typename DT, typename OutFn>
-__device__ __forceinline__ void wave_layernorm_cached(const void* row, int d, int n_chunks,
-                                                      const float* __restrict__ gamma,
-                                                      const float* __restrict__ beta, float eps, int lane,
-                                                      OutFn out) {
+template <typename DT, int NW, typename OutFn>
+__device__ __forceinline__ void group_layernorm_cached(const void* row, int d, int n_chunks,
+                                                       const float* __restrict__ gamma,
+                                                       const float* __restrict__ beta, float eps, int tid,
+                                                       double* red, OutFn out) {
+  constexpr int NT = NW * kWave;
+  constexpr int NJ = kLnCache / NW;
+  static_assert(NJ * NW == kLnCache, "cache split");
   const int live_chunks = d / DT::EPL;
-  frag_t raw[kLnCache];
+  frag_t raw[NJ];
 #pragma unroll
-  for (int j = 0; j < kLnCache; ++j) {
-    const int c = lane + j * kWave;
+  for (int j = 0; j < NJ; ++j) {
+    const int c = tid + j * NT;
     raw[j] = mk_frag(0, 0, 0, 0);
     if (c < live_chunks) raw[j] = *(const frag_t*)((const char*)row + (int64_t)c * 16);
   }
   double s = 0.0;
 #pragma unroll
-  for (int j = 0; j < kLnCache; ++j) {
-    if (lane + j * kWave < live_chunks) {
+  for (int j = 0; j < NJ; ++j) {
+    if (tid + j * NT < live_chunks) {
       float x[DT::EPL];
       decode_elems<DT>(raw[j], x);
 #pragma unroll
       for (int i = 0; i < DT::EPL; ++i) s += (double)x[i];
     }
   }
-  const double mu = wave_sum(s) / (double)d;
+  const double mu = group_sum<NW>(s, red, tid) / (double)d;
   double v = 0.0;
 #pragma unroll
-  for (int j = 0; j < kLnCache; ++j) {
-    if (lane + j * kWave < live_chunks) {
+  for (int j = 0; j < NJ; ++j) {
+    if (tid + j * NT < live_chunks) {
       float x[DT::EPL];
       decode_elems<DT>(raw[j], x);
 #pragma unroll
@@ -173,11 +196,11 @@ __device__ __forceinline__ void wave_layernorm_cached(const void* row, int d, in
       }
     }
   }
-  const double var = wave_sum(v) / (double)d;
+  const double var = group_sum<NW>(v, red + NW, tid) / (double)d;
   const double rstd = 1.0 / sqrt(var + (double)eps);
 #pragma unroll
-  for (int j = 0; j < kLnCache; ++j) {
-    const int c = lane + j * kWave;
+  for (int j = 0; j < NJ; ++j) {
+    const int c = tid + j * NT;
     if (c < n_chunks) {
       frag_t o = mk_frag(0, 0, 0, 0);
       if (c < live_chunks) {
@@ -196,7 +219,7 @@ __device__ __forceinline__ void wave_layernorm_cached(const void* row, int d, in
   }
 }
 
-// One wave (= one workgroup) per row.
+// One workgroup of kLnWaves waves per row.
 // RB = rows per activation block: 16 (fragments of 16 rows x KPF k, the operand
 // order of the 16x16 matrix instructions) or 32 (bf16 only: fragments of 32 rows
 // x 16 k for v_mfma_f32_32x32x16_bf16; lane l of fragment (block, k16) holds row
@@ -212,17 +235,20 @@ __device__ __forceinline__ void put_chunk(frag_t* __restrict__ yf, int KS, int p
   else dst[(c >> 1) * kWave + (c & 1) * 32 + n] = v;
 }
 
-// LayerNorm of the row at `row` into position p (one wave).
+// LayerNorm of the row at `row` into position p (the whole workgroup of kLnWaves waves; every
+// thread of it must call; red: 2*kLnWaves doubles of LDS).
 template <typename DT, int RB>
 __device__ __forceinline__ void ln_write_row(const void* __restrict__ row, int d, int KS,
                                              const float* __restrict__ gamma,
                                              const float* __restrict__ beta, float eps,
-                                             frag_t* __restrict__ yf, int p, int lane) {
+                                             frag_t* __restrict__ yf, int p, int tid, double* red) {
   static_assert(RB == 16 || (RB == 32 && DT::EPL == 8), "row block");
   const int n_chunks = KS * 4;
   auto put = [&](int c, const frag_t& v) { put_chunk<RB>(yf, KS, p, c, v); };
-  if (n_chunks <= kLnCache * kWave) wave_layernorm_cached<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
-  else wave_layernorm<DT>(row, d, n_chunks, gamma, beta, eps, lane, put);
+  if (n_chunks <= kLnCache * kWave)
+    group_layernorm_cached<DT, kLnWaves>(row, d, n_chunks, gamma, beta, eps, tid, red, put);
+  else
+    group_layernorm<DT, kLnWaves>(row, d, n_chunks, gamma, beta, eps, tid, red, put);
 }
 
 template <typename DT, int RB>
@@ -230,18 +256,18 @@ __device__ __forceinline__ void ln_pack_row(const void* __restrict__ h, int64_t 
                                             const int* __restrict__ row_idx, int n_live, int R_pad, int d,
                                             int KS, const float* __restrict__ gamma,
                                             const float* __restrict__ beta, float eps,
-                                            frag_t* __restrict__ yf, int p, int lane) {
+                                            frag_t* __restrict__ yf, int p, int tid, double* red) {
   if (p >= R_pad) return;
   if (p >= n_live) {
-    for (int c = lane; c < KS * 4; c += kWave) put_chunk<RB>(yf, KS, p, c, mk_frag(0, 0, 0, 0));
+    for (int c = tid; c < KS * 4; c += kLnThreads) put_chunk<RB>(yf, KS, p, c, mk_frag(0, 0, 0, 0));
     return;
   }
   const int64_t r = row_idx ? row_idx[p] : p;
-  ln_write_row<DT, RB>((const char*)h + r * row_stride * DT::ESZ, d, KS, gamma, beta, eps, yf, p, lane);
+  ln_write_row<DT, RB>((const char*)h + r * row_stride * DT::ESZ, d, KS, gamma, beta, eps, yf, p, tid, red);
 }
 
 template <typename DT, int RB>
-__global__ __launch_bounds__(64) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
+__global__ __launch_bounds__(kLnThreads) void ln_pack_kernel(const void* __restrict__ h, int64_t row_stride,
                                                      const int* __restrict__ row_idx,
                                                      const int* __restrict__ n_rows_dev, int n_rows,
                                                      int R_pad, int d, int KS,
@@ -250,15 +276,16 @@ __global__ __launch_bounds__(64) void ln_pack_kernel(const void* __restrict__ h,
                                                      frag_t* __restrict__ yf) {
   int n_live = n_rows;
   if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
+  __shared__ double red[2 * kLnWaves];
   ln_pack_row<DT, RB>(h, row_stride, row_idx, n_live, R_pad, d, KS, gamma, beta, eps, yf, blockIdx.x,
-                      threadIdx.x);
+                      threadIdx.x, red);
 }
 
 // The same for several heads at once: blockIdx.y = head (relative to the first),
 // whose hidden states start layer_stride elements after the previous head's and
 // whose output goes y_stride fragments after it.
 template <typename DT, int RB>
-__global__ __launch_bounds__(64) void ln_pack_heads_kernel(const void* __restrict__ h_layers,
+__global__ __launch_bounds__(kLnThreads) void ln_pack_heads_kernel(const void* __restrict__ h_layers,
                                                            int64_t layer_stride, int64_t row_stride,
                                                            int n_rows, int R_pad, int d, int KS,
                                                            const float* const* __restrict__ gamma_tab,
@@ -267,8 +294,9 @@ __global__ __launch_bounds__(64) void ln_pack_heads_kernel(const void* __restric
                                                            int64_t y_stride) {
   const int l = blockIdx.y;
   const void* h = (const char*)h_layers + (int64_t)l * layer_stride * DT::ESZ;
+  __shared__ double red[2 * kLnWaves];
   ln_pack_row<DT, RB>(h, row_stride, nullptr, n_rows, R_pad, d, KS, gamma_tab[l], beta_tab[l], eps,
-                      yf + (int64_t)l * y_stride, blockIdx.x, threadIdx.x);
+                      yf + (int64_t)l * y_stride, blockIdx.x, threadIdx.x, red);
 }
 
 // ---------------------------------------------------------------------------
@@ -450,7 +478,7 @@ static __global__ __launch_bounds__(64) void finalize_metrics_kernel(
 // projection never lets a token column influence another.
 // ---------------------------------------------------------------------------
 template <typename DT, int RB>
-__global__ __launch_bounds__(64) void cascade_post_kernel(
+__global__ __launch_bounds__(kLnThreads) void cascade_post_kernel(
     const Stats* __restrict__ partials, int n_parts, int R_pad, const int* __restrict__ row_idx,
     const int* __restrict__ n_rows_dev, int n_rows, float tau, int is_last, int head,
     int* __restrict__ exit_layer,
@@ -459,35 +487,41 @@ __global__ __launch_bounds__(64) void cascade_post_kernel(
     const void* __restrict__ h_next, int64_t row_stride, int d, int KS,
     const float* __restrict__ gamma_next, const float* __restrict__ beta_next, float eps,
     frag_t* __restrict__ yf) {
-  const int p = blockIdx.x, lane = threadIdx.x;
-  if (p == 0 && lane == 0 && clear) *clear = 0;  // the counter of the head after next
+  __shared__ double red[2 * kLnWaves];
+  __shared__ int pos_s;
+  const int p = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+  if (p == 0 && tid == 0 && clear) *clear = 0;  // the counter of the head after next
   int n_live = n_rows;
   if (n_rows_dev) n_live = min(max(*n_rows_dev, 0), n_rows);
   if (p >= n_live) return;
   const int r = row_idx ? row_idx[p] : p;
-  Stats s;
-  stats_init(s);
-  for (int g = lane; g < n_parts; g += kWave) s = stats_merge(s, partials[(int64_t)g * R_pad + p]);
+  if (tid < kWave) {  // the first wave merges and decides, exactly as finalize_kernel does
+    Stats s;
+    stats_init(s);
+    for (int g = lane; g < n_parts; g += kWave) s = stats_merge(s, partials[(int64_t)g * R_pad + p]);
 #pragma unroll
-  for (int x = 32; x > 0; x >>= 1) s = stats_merge(s, stats_shfl_xor(s, x));
-  int pos = -1;
-  if (lane == 0) {
-    float H, l;
-    stats_finalize(s, H, l);
-    if (H_out) H_out[r] = H;
-    if (n_evals) atomicAdd(n_evals, 1ull);
-    if (is_last || H < tau) {  // NaN never passes the test
-      exit_layer[r] = head;
-      token[r] = s.ib;
-    } else {
-      pos = atomicAdd(n_active_next, 1);
-      active_next[pos] = r;
+    for (int x = 32; x > 0; x >>= 1) s = stats_merge(s, stats_shfl_xor(s, x));
+    if (lane == 0) {
+      int pos = -1;
+      float H, l;
+      stats_finalize(s, H, l);
+      if (H_out) H_out[r] = H;
+      if (n_evals) atomicAdd(n_evals, 1ull);
+      if (is_last || H < tau) {  // NaN never passes the test
+        exit_layer[r] = head;
+        token[r] = s.ib;
+      } else {
+        pos = atomicAdd(n_active_next, 1);
+        active_next[pos] = r;
+      }
+      pos_s = pos;
     }
   }
-  pos = __shfl(pos, 0);
+  __syncthreads();
+  const int pos = pos_s;
   if (pos < 0) return;
   ln_write_row<DT, RB>((const char*)h_next + (int64_t)r * row_stride * DT::ESZ, d, KS, gamma_next, beta_next,
-                       eps, yf, pos, lane);
+                       eps, yf, pos, tid, red);
 }
 
 // ---------------------------------------------------------------------------
