@@ -137,6 +137,52 @@ __device__ __forceinline__ void stats_push16(Stats& s, const f32x16& z, int rowb
   }
 }
 
+// The same for the training objectives: the head's and the model's 16 logits of one tile
+// (same rows, same tokens), all inside the vocabulary.
+__device__ __forceinline__ void kl_push16(KlStats& s, const f32x16& zs, const f32x16& zt, int rowbase) {
+  const float a = max3(max3(max3(zs[0], zs[1], zs[2]), max3(zs[3], zs[4], zs[5]), zs[15]),
+                       max3(zs[6], zs[7], zs[8]), max3(max3(zs[9], zs[10], zs[11]), max3(zs[12], zs[13], zs[14]), zs[15]));
+  const float b = max3(max3(max3(zt[0], zt[1], zt[2]), max3(zt[3], zt[4], zt[5]), zt[15]),
+                       max3(zt[6], zt[7], zt[8]), max3(max3(zt[9], zt[10], zt[11]), max3(zt[12], zt[13], zt[14]), zt[15]));
+  const float na = a * kLog2e, nb = b * kLog2e;
+  if (na > s.ms) {
+    const float sc = fast_exp2(s.ms - na);
+    s.Ss *= sc;
+    s.C *= sc;
+    s.ms = na;
+  }
+  if (nb > s.mt) {
+    s.St *= fast_exp2(s.mt - nb);
+    s.mt = nb;
+  }
+  float e[16], f[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) e[i] = fast_exp2(zs[i] * kLog2e - s.ms);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) f[i] = fast_exp2(zt[i] * kLog2e - s.mt);
+  float S4[4], T4[4], C4[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    S4[g] = (e[g] + e[g + 4]) + (e[g + 8] + e[g + 12]);
+    T4[g] = (f[g] + f[g + 4]) + (f[g + 8] + f[g + 12]);
+    C4[g] = e[g] * (zs[g] - zt[g]);
+    C4[g] += e[g + 4] * (zs[g + 4] - zt[g + 4]);
+    C4[g] += e[g + 8] * (zs[g + 8] - zt[g + 8]);
+    C4[g] += e[g + 12] * (zs[g + 12] - zt[g + 12]);
+  }
+  s.Ss += (S4[0] + S4[1]) + (S4[2] + S4[3]);
+  s.St += (T4[0] + T4[1]) + (T4[2] + T4[3]);
+  s.C += (C4[0] + C4[1]) + (C4[2] + C4[3]);
+  // the label's logit: accumulator j = 4g+i holds row rowbase + 8g + i
+  const int off = s.lab - rowbase;
+  if (off >= 0 && off < 32 && (off & 4) == 0) {
+    const int j = (off >> 3) * 4 + (off & 3);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (i == j) s.zl = zs[i];
+  }
+}
+
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
 template <int N, typename F, int I = 0>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -345,6 +391,12 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   if constexpr (DUAL) {
 #pragma unroll
     for (int m = 0; m < MH; ++m) {
+      if ((T + m + 1) * 32 <= V) {  // wave-uniform: only the vocabulary's last tile can be ragged
+#pragma unroll
+        for (int n = 0; n < NA; ++n) kl_push16(st[n], acc[m][n], acc[m + MH][n], (T + m) * 32 + half * 4);
+        __builtin_amdgcn_sched_barrier(0);
+        continue;
+      }
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int row0 = (T + m) * 32 + g * 8 + half * 4;
