@@ -390,7 +390,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const frag_t* __restrict__ 
 // ---------------------------------------------------------------------------
 // Merge the per-workgroup partials of each live row and finalise:
 // H = ln2 (log2 S - U/S), lse = ln2 (m + log2 S), argmax = ib.
-// One wave per row.
+// One wave per row (the cascade step kernel merges the same way with its first wave).
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void stats_finalize(const Stats& s, float& H, float& lse) {
   const double S = (double)s.S, U = (double)s.U;
