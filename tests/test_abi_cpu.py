@@ -54,6 +54,47 @@ def test_null_arguments():
     assert B.lib.eh_destroy(None) == 1
     assert B.lib.eh_eval(None, 0, None, 0, None, None, 0, None, None, None, None) == 1
     assert B.lib.dssd_verify(None, None, None, None, 1, 1, None, None, None, None) == 1
+    assert B.lib.eh_eval_heads(None, 0, 1, None, 0, 0, 1, None, None, None, None) == 1
+    assert B.lib.eh_eval_heads_metrics(None, 0, 1, None, 0, 0, 1, None, None, None, None, None, None) == 1
+    assert B.lib.eh_cascade(None, None, 0, 0, 1, None, None, None, None, None) == 1
+    assert B.lib.dssd_draft(None, None, 0, 0, 1, 1, -1, None, None, None, None, None, None, None) == 1
+    assert B.lib.dssd_tally(None, None, None, 1, 1, None, None, None) == 1
+    assert B.lib.eh_head_losses(None, 0, None, 0, None, 0, None, 1, 0.5, None, None, None, None) == 1
+    assert B.lib.eh_calibrate(None, None, None, None, 1, None, 1, None, None, None) == 1
+
+
+# ---------------------------------------------------------------- repository rules, checked on the tree
+def _sources(*dirs, exts=(".py", ".hip", ".hpp", ".h")):
+    for d in dirs:
+        for base, _, files in os.walk(os.path.join(ROOT, d)):
+            if "_build" in base or "__pycache__" in base:
+                continue
+            for f in files:
+                if f.endswith(exts):
+                    yield os.path.join(base, f)
+
+
+def test_product_never_touches_the_oracle_or_working_files():
+    """The library and its binding are the product: no import of the oracle, no CPU fallback module,
+    nothing read from the working folder."""
+    for path in _sources("paper_2407_21082_amd", "include"):
+        text = open(path).read()
+        assert "oracle" not in text.lower() or path.endswith("check_gemm_asm.py"), path
+        assert "_work/" not in text, path
+    for path in list(_sources("tests", "oracle", "workloads")) + [os.path.join(ROOT, "bench.py"),
+                                                                   os.path.join(ROOT, "__graft_entry__.py")]:
+        assert "_work/" not in open(path).read(), path
+    # the oracle in turn imports nothing of the product
+    for path in _sources("oracle"):
+        assert "paper_2407_21082_amd" not in open(path).read(), path
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0 and "single-GPU" in r.stderr and r.stdout.strip() == ""
 
 
 # ---------------------------------------------------------------- generators
