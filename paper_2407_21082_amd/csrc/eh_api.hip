@@ -391,10 +391,9 @@ eh_status eval_heads_impl(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval, cons
                      (const float* const*)(ctx->d_gamma + head0), (const float* const*)(ctx->d_beta + head0),
                      ctx->eps, ctx->mh_yf, (int64_t)y_stride);
   int n_parts = 0;
-  for (int l = 0; l < n_heads_eval; ++l)
-    EH_HIP(ctx, gemm32_launch(ctx, head0 + l, nullptr, n_rows, false, ctx->mh_yf + (size_t)l * y_stride,
-                              ctx->mh_partials + (size_t)l * part_stride,
-                              metrics ? ctx->mh_second + (size_t)l * part_stride : nullptr, &n_parts, s));
+  EH_HIP(ctx, gemm32_launch_heads(ctx, head0, n_heads_eval, nullptr, n_rows, false, ctx->mh_yf, (long long)y_stride,
+                                  ctx->mh_partials, metrics ? ctx->mh_second : nullptr, (long long)part_stride,
+                                  &n_parts, s));
   if (metrics)
     hipLaunchKernelGGL(finalize_metrics_kernel, dim3(n_rows, n_heads_eval), dim3(64), 0, s, ctx->mh_partials,
                        ctx->mh_second, n_parts, R_pad, n_rows, H, lse, argmax, max_prob, margin,

@@ -197,7 +197,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 // last one (same bytes to the same place) so that all waves count alike.
 __host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Waves - 1) / kG32Waves; }
 
-// One pass: MT tiles of 32 vocabulary rows starting at tile T, all of k, this
+// One pass: MT tiles of 32 vocabulary rows starting at 16-row tile T16 (the workgroup's tiles end
+// at t16_end, its rows at row_hi; a missing last half tile is masked), all of k, this
 // wave's NB blocks of 32 tokens.
 //
 // k-step s (32 values of k) uses, per tile m, the operands a[m][0], a[m][1] (the
@@ -228,7 +229,7 @@ __host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Wa
 // of the same (vocabulary row, token) in the same register of the same lane.
 template <int MT, int NB, bool ARGMAX_ONLY, bool TOP2, bool DUAL = false, typename ST = Stats>
 __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq,
-                                       int T, int VT16, int KS, int V, int lane, int wave,
+                                       int T16, int t16_end, int KS, int row_hi, int lane, int wave,
                                        EH_LDS char* lds, ST (&st)[DUAL ? NB / 2 : NB], long long wdelta = 0,
                                        const frag_t* __restrict__ yq2 = nullptr) {
   static_assert(!DUAL || (MT % 2 == 0 && NB % 2 == 0), "two equal sides");
@@ -261,7 +262,7 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
     if (f >= NF) f = (wave < NF) ? wave + kG32Waves * ((NF - 1 - wave) / kG32Waves) : NF - 1;
     // a missing odd half tile repeats the last one (masked later)
     const bool side2 = DUAL && f >= 2 * MH;
-    const int t16 = min(2 * T + (side2 ? f - 2 * MH : f), VT16 - 1);
+    const int t16 = min(T16 + (side2 ? f - 2 * MH : f), t16_end - 1);
     wsrc[i] = (((long long)t16 * KS) << 10) + (side2 ? wdelta : 0);
     wdst[i] = f * 1024;
   }
@@ -391,21 +392,21 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   if constexpr (DUAL) {
 #pragma unroll
     for (int m = 0; m < MH; ++m) {
-      if ((T + m + 1) * 32 <= V) {  // wave-uniform: only the vocabulary's last tile can be ragged
+      if (T16 * 16 + (m + 1) * 32 <= row_hi) {  // wave-uniform: only the workgroup's last tile can be ragged
 #pragma unroll
-        for (int n = 0; n < NA; ++n) kl_push16(st[n], acc[m][n], acc[m + MH][n], (T + m) * 32 + half * 4);
+        for (int n = 0; n < NA; ++n) kl_push16(st[n], acc[m][n], acc[m + MH][n], T16 * 16 + m * 32 + half * 4);
         __builtin_amdgcn_sched_barrier(0);
         continue;
       }
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int row0 = (T + m) * 32 + g * 8 + half * 4;
+        const int row0 = T16 * 16 + m * 32 + g * 8 + half * 4;
 #pragma unroll
         for (int n = 0; n < NA; ++n) {
           const f32x4 zs = {acc[m][n][4 * g], acc[m][n][4 * g + 1], acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]};
           const f32x4 zt = {acc[m + MH][n][4 * g], acc[m + MH][n][4 * g + 1], acc[m + MH][n][4 * g + 2],
                             acc[m + MH][n][4 * g + 3]};
-          kl_push4(st[n], zs, zt, row0, V);
+          kl_push4(st[n], zs, zt, row0, row_hi);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -421,10 +422,10 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
     // wave-uniform: only the vocabulary's last tile can be ragged
-    if ((T + m + 1) * 32 <= V) {
+    if (T16 * 16 + (m + 1) * 32 <= row_hi) {
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
-        stats_push16<ARGMAX_ONLY>(st[n], acc[m][n], (T + m) * 32 + half * 4);
+        stats_push16<ARGMAX_ONLY>(st[n], acc[m][n], T16 * 16 + m * 32 + half * 4);
         if constexpr (TOP2) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
@@ -439,15 +440,15 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const int row0 = (T + m) * 32 + g * 8 + half * 4;
+      const int row0 = T16 * 16 + m * 32 + g * 8 + half * 4;
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
         const f32x4 z = {acc[m][n][4 * g], acc[m][n][4 * g + 1], acc[m][n][4 * g + 2], acc[m][n][4 * g + 3]};
-        stats_push4<ARGMAX_ONLY>(st[n], z, row0, V);
+        stats_push4<ARGMAX_ONLY>(st[n], z, row0, row_hi);
         if constexpr (TOP2) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float zi = (row0 + i < V) ? z[i] : -INFINITY;
+            const float zi = (row0 + i < row_hi) ? z[i] : -INFINITY;
             z2[n] = fmaxf(z2[n], fminf(zi, z1[n]));
             z1[n] = fmaxf(z1[n], zi);
           }
@@ -465,12 +466,30 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   }
 }
 
-// grid.x = workgroups over the vocabulary, grid.y = groups of 4*NB blocks of 32 tokens
+// This workgroup's slice of the vocabulary in 16-row tiles, [t0, t1).  gran = 2 hands out whole
+// 32-row tiles (no matrix instruction is spent on a half tile: the compute-bound shapes);
+// gran = 1 hands out 16-row tiles, which halves the imbalance between workgroups (the
+// bandwidth-bound shapes, where a workgroup's time is its bytes).
+__device__ __forceinline__ void vocab_slice(int VT16, int gran, int& t0, int& t1) {
+  const int units = (VT16 + gran - 1) / gran;
+  t0 = gran * (int)((long long)units * blockIdx.x / gridDim.x);
+  t1 = min(VT16, gran * (int)((long long)units * (blockIdx.x + 1) / gridDim.x));
+}
+
+// grid.x = workgroups over the vocabulary, grid.y = groups of 4*NB blocks of 32 tokens,
+// grid.z = heads (Wf_tab, if given, holds the weights of head blockIdx.z; activations and
+// outputs of consecutive heads lie y_stride fragments / part_stride records apart): the heads
+// of one launch are independent, so a workgroup of the next head starts wherever one of this
+// head has finished and the imbalance between workgroups does not idle the chip per head.
 template <int NB, bool ARGMAX_ONLY, bool TOP2>
 __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
-    const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq, int VT16, int KS, int V,
-    const int* __restrict__ n_rows_dev, int n_rows, int R_pad, Stats* __restrict__ partials,
-    float* __restrict__ second) {
+    const frag_t* __restrict__ Wf, const frag_t* const* __restrict__ Wf_tab, const frag_t* __restrict__ yq,
+    long long y_stride, int VT16, int KS, int V, int gran, const int* __restrict__ n_rows_dev, int n_rows,
+    int R_pad, Stats* __restrict__ partials, float* __restrict__ second, long long part_stride) {
+  if (Wf_tab) Wf = Wf_tab[blockIdx.z];
+  yq += (long long)blockIdx.z * y_stride;
+  partials += (long long)blockIdx.z * part_stride;
+  if (TOP2) second += (long long)blockIdx.z * part_stride;
   extern __shared__ __attribute__((aligned(16))) char g32_smem[];
   EH_LDS char* lds = (EH_LDS char*)g32_smem;
   const int lane = threadIdx.x & 63;
@@ -484,9 +503,9 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
   if (live_blocks - (int)(blockIdx.y * kG32Waves * NB) <= 0) return;
   const int nb_first = (blockIdx.y * kG32Waves + wave) * NB;  // my first token block
   const int nb_live = min(NB, live_blocks - nb_first);
-  const int VT32 = (VT16 + 1) >> 1;
-  const int T0 = (int)((long long)VT32 * blockIdx.x / gridDim.x);
-  const int T1 = (int)((long long)VT32 * (blockIdx.x + 1) / gridDim.x);
+  int T0, T1;
+  vocab_slice(VT16, gran, T0, T1);
+  const int row_hi = min(V, T1 * 16);
   Stats st[NB];
 #pragma unroll
   for (int n = 0; n < NB; ++n) stats_init(st[n]);
@@ -497,20 +516,20 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel(
   }
   const frag_t* ybase = yq + (long long)nb_first * 2 * KS * kWave;
   for (int t = T0; t < T1;) {
-    const int left = T1 - t;
+    const int left = (T1 - t + 1) >> 1;  // 32-row tiles, the last one possibly half
     // split what is left into passes of at most kMaxMT tiles of about equal size
     const int passes = (left + kMaxMT - 1) / kMaxMT;
     const int mt = (left + passes - 1) / passes;
     switch (mt) {
-      case 7: pass32<7, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 6: pass32<6, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 5: pass32<5, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 4: pass32<4, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 3: pass32<3, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      case 2: pass32<2, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
-      default: pass32<1, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, VT16, KS, V, lane, wave, lds, st); break;
+      case 7: pass32<7, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, T1, KS, row_hi, lane, wave, lds, st); break;
+      case 6: pass32<6, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, T1, KS, row_hi, lane, wave, lds, st); break;
+      case 5: pass32<5, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, T1, KS, row_hi, lane, wave, lds, st); break;
+      case 4: pass32<4, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, T1, KS, row_hi, lane, wave, lds, st); break;
+      case 3: pass32<3, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, T1, KS, row_hi, lane, wave, lds, st); break;
+      case 2: pass32<2, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, T1, KS, row_hi, lane, wave, lds, st); break;
+      default: pass32<1, NB, ARGMAX_ONLY, TOP2>(Wf, ybase, t, T1, KS, row_hi, lane, wave, lds, st); break;
     }
-    t += mt;
+    t += 2 * mt;
   }
   // lanes l and l+32 hold the same token: fold the two row groups
 #pragma unroll
@@ -543,9 +562,9 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_kl_kernel(
   if (live_blocks - (int)(blockIdx.y * kG32Waves * NBH) <= 0) return;
   const int nb_first = (blockIdx.y * kG32Waves + wave) * NBH;
   const int nb_live = min(NBH, live_blocks - nb_first);
-  const int VT32 = (VT16 + 1) >> 1;
-  const int T0 = (int)((long long)VT32 * blockIdx.x / gridDim.x);
-  const int T1 = (int)((long long)VT32 * (blockIdx.x + 1) / gridDim.x);
+  int T0, T1;
+  vocab_slice(VT16, 2, T0, T1);
+  const int row_hi = min(V, T1 * 16);
   KlStats st[NBH];
 #pragma unroll
   for (int n = 0; n < NBH; ++n) {
@@ -556,21 +575,21 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_kl_kernel(
   const frag_t* y2 = yq2 + (long long)nb_first * 2 * KS * kWave;
   constexpr int kMaxMH = 3;
   for (int t = T0; t < T1;) {
-    const int left = T1 - t;
+    const int left = (T1 - t + 1) >> 1;
     const int passes = (left + kMaxMH - 1) / kMaxMH;
     const int mh = (left + passes - 1) / passes;
     switch (mh) {
       case 3:
-        pass32<6, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, VT16, KS, V, lane, wave, lds, st, wdelta, y2);
+        pass32<6, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, T1, KS, row_hi, lane, wave, lds, st, wdelta, y2);
         break;
       case 2:
-        pass32<4, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, VT16, KS, V, lane, wave, lds, st, wdelta, y2);
+        pass32<4, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, T1, KS, row_hi, lane, wave, lds, st, wdelta, y2);
         break;
       default:
-        pass32<2, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, VT16, KS, V, lane, wave, lds, st, wdelta, y2);
+        pass32<2, 2 * NBH, false, false, true, KlStats>(Wf, y1, t, T1, KS, row_hi, lane, wave, lds, st, wdelta, y2);
         break;
     }
-    t += mh;
+    t += 2 * mh;
   }
 #pragma unroll
   for (int n = 0; n < NBH; ++n) {
@@ -593,22 +612,26 @@ void launch_kl(dim3 g, hipStream_t s, const frag_t* Wf, long long wdelta, const 
 }
 
 template <int NB, bool AO, bool TOP2>
-void launch32(dim3 g, hipStream_t s, const frag_t* Wf, const frag_t* yq, int VT16, int KS, int V,
-              const int* n_rows_dev, int n_rows, int R_pad, Stats* partials, float* second) {
+void launch32(dim3 g, hipStream_t s, const frag_t* Wf, const frag_t* const* Wf_tab, const frag_t* yq,
+              long long y_stride, int VT16, int KS, int V, int gran, const int* n_rows_dev, int n_rows, int R_pad,
+              Stats* partials, float* second, long long part_stride) {
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)gemm32_stats_kernel<NB, AO, TOP2>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)g32_lds_bytes());
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm32_stats_kernel<NB, AO, TOP2>), g, dim3(kG32Threads), g32_lds_bytes(), s, Wf, yq,
-                     VT16, KS, V, n_rows_dev, n_rows, R_pad, partials, second);
+  hipLaunchKernelGGL((gemm32_stats_kernel<NB, AO, TOP2>), g, dim3(kG32Threads), g32_lds_bytes(), s, Wf, Wf_tab, yq,
+                     y_stride, VT16, KS, V, gran, n_rows_dev, n_rows, R_pad, partials, second, part_stride);
 }
 
 }  // namespace
 
-hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
-                         const frag_t* yf, Stats* partials, float* second, int* n_parts, hipStream_t s) {
+// n_heads > 1: heads head .. head+n_heads-1 in one launch (grid.z), their activations y_stride
+// fragments and their partials (and second largest logits) part_stride records apart.
+hipError_t gemm32_launch_heads(const eh_ctx* c, int head, int n_heads, const int* n_rows_dev, int n_rows,
+                               bool argmax_only, const frag_t* yf, long long y_stride, Stats* partials,
+                               float* second, long long part_stride, int* n_parts, hipStream_t s) {
   const int R_pad = (n_rows + 31) & ~31;
   const int blocks = R_pad / 32;
   const int nb = blocks <= kG32Waves ? 1 : 2;
@@ -616,11 +639,16 @@ hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n
   const int cus = c->num_cu > 0 ? c->num_cu : 256;
   const int VT32 = (c->VT + 1) / 2;
   const int gx = std::max(1, std::min(VT32, cus / groups));
-  dim3 g(gx, groups);
+  dim3 g(gx, groups, n_heads);
   *n_parts = gx;
+  // one token group of at most 5 blocks streams the weights once and is paced by that stream:
+  // balance the bytes (16-row tiles); otherwise balance the matrix instructions (32-row tiles)
+  const int gran = (groups == 1 && blocks <= 5) ? 1 : 2;
   const frag_t* Wf = c->Wf[head];
-#define EH_L32(NB_, AO_, T2_) \
-  launch32<NB_, AO_, T2_>(g, s, Wf, yf, c->VT, c->KS, c->V, n_rows_dev, n_rows, R_pad, partials, second)
+  const frag_t* const* tab = n_heads > 1 ? (const frag_t* const*)(c->d_Wf + head) : nullptr;
+#define EH_L32(NB_, AO_, T2_)                                                                              \
+  launch32<NB_, AO_, T2_>(g, s, Wf, tab, yf, y_stride, c->VT, c->KS, c->V, gran, n_rows_dev, n_rows, R_pad, \
+                          partials, second, part_stride)
   if (second) {  // entropy statistics plus the second largest logit
     if (argmax_only) return hipErrorInvalidValue;
     if (nb == 1) EH_L32(1, false, true);
@@ -634,6 +662,11 @@ hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n
   }
 #undef EH_L32
   return hipGetLastError();
+}
+
+hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
+                         const frag_t* yf, Stats* partials, float* second, int* n_parts, hipStream_t s) {
+  return gemm32_launch_heads(c, head, 1, n_rows_dev, n_rows, argmax_only, yf, 0, partials, second, 0, n_parts, s);
 }
 
 hipError_t gemm32_kl_launch(const eh_ctx* c, int head, int model_head, int n_rows, const frag_t* yf_head,

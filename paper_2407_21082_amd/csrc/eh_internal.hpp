@@ -104,6 +104,12 @@ hipError_t gemm_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n
 hipError_t gemm32_launch(const eh_ctx* ctx, int head, const int* n_rows_dev, int n_rows, bool argmax_only,
                          const eh::frag_t* yf, eh::Stats* partials, float* second, int* n_parts,
                          hipStream_t s);
+// Several consecutive heads in one launch (independent heads: eh_eval_heads): the activations
+// of head l lie l * y_stride fragments behind yf, its partials (and second largest logits)
+// l * part_stride records behind partials (second).
+hipError_t gemm32_launch_heads(const eh_ctx* ctx, int head, int n_heads, const int* n_rows_dev, int n_rows,
+                               bool argmax_only, const eh::frag_t* yf, long long y_stride, eh::Stats* partials,
+                               float* second, long long part_stride, int* n_parts, hipStream_t s);
 // The fused projections of the training objectives (bf16, no bias vector): an exit head on
 // yf_head and the model's head on yf_model (both in the 32 x 16 operand order, same rows),
 // labels NULL or device [n_rows]; per-workgroup partial statistics go to
