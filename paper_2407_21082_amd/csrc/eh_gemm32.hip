@@ -293,11 +293,15 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   // a tile's matrix instructions is lgkmcnt(2*(MT-1)).  Nothing else in the loop
   // may use that counter (no scalar loads); the build checks the generated code.
   const uint32_t laneoff = (uint32_t)(uintptr_t)lds + ((lane & 31) >> 4) * 1024 + (((lane >> 5) * 16 + (lane & 15)) << 4);
-  auto fetch_a = [&](frag_t (&a)[2], auto mc, int ks) {
+  auto fetch_a_half = [&](frag_t& ah, auto mc, auto hc, int ks) {
     constexpr int m = decltype(mc)::value;
+    constexpr int h = decltype(hc)::value;
     const uint32_t p = laneoff + (ks & (kSlots - 1)) * kSlotBytes;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[0]) : "v"(p), "n"(m * 2048) : "memory");
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a[1]) : "v"(p), "n"(m * 2048 + 512) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(ah) : "v"(p), "n"(m * 2048 + h * 512) : "memory");
+  };
+  auto fetch_a = [&](frag_t (&a)[2], auto mc, int ks) {
+    fetch_a_half(a[0], mc, std::integral_constant<int, 0>{}, ks);
+    fetch_a_half(a[1], mc, std::integral_constant<int, 1>{}, ks);
   };
   constexpr int kLdsInFlight = 2 * (MT - 1);
 
@@ -320,20 +324,28 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
     static_for<MT>([&](auto mc) {
       constexpr int m = decltype(mc)::value;
       asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a[m][0]), "+v"(a[m][1]) : "n"(kLdsInFlight));
+      // a wave issues one instruction per four cycles, and up to seven fit behind a matrix
+      // instruction: each k half is re-read right behind the matrix instructions that used it,
+      // instead of everything queueing up behind the tile's last one
+      static_for<2>([&](auto hc) {
+        constexpr int h = decltype(hc)::value;
 #pragma unroll
-      for (int n = 0; n < NB; ++n) {
-        if (!DUAL || ((n < NH) == (m < MH))) {
-          const int j = DUAL ? (n < NH ? n : n - NH) : n;
-#pragma unroll
-          for (int h = 0; h < 2; ++h) acc[m][j] = mma32(a[m][h], b[n][h], acc[m][j]);
+        for (int n = 0; n < NB; ++n) {
+          if (!DUAL || ((n < NH) == (m < MH))) {
+            const int j = DUAL ? (n < NH ? n : n - NH) : n;
+            acc[m][j] = mma32(a[m][h], b[n][h], acc[m][j]);
+          }
         }
-        if (m == MT - 1) load_b(b[n], n, ks + kDepth);
-      }
-      if constexpr (m == 0) {
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_barrier" ::: "memory");
+        if constexpr (m == 0 && h == 1) asm volatile("s_barrier" ::: "memory");
+        if constexpr (m != 0) fetch_a_half(a[m][h], mc, hc, ks + 1);
+        if constexpr (h == 0) __builtin_amdgcn_sched_barrier(0);
+      });
+      if constexpr (m == MT - 1) {
+#pragma unroll
+        for (int n = 0; n < NB; ++n) load_b(b[n], n, ks + kDepth);
       }
-      fetch_a(a[m], mc, ks + 1);
+      if constexpr (m == 0) fetch_a(a[m], mc, ks + 1);  // slot ks+1 is complete only behind the barrier
       // DMA piece i travels with tile min(i, MT-1)
       static_for<kDma>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
