@@ -36,6 +36,11 @@ HBM_PEAK_GBS = 8000.0
 # (profiles/c1_decode_persistent_kernel.md).  Reported as that ratio times this run's
 # algorithmic bytes per launch.
 TRAFFIC_RATIO_C1 = (1.9281e9 + 1.42e6) / 1.7635e9
+# The same for the batched projection kernel (profiles/c2_calib_gemm32_kernel.md,
+# profiles/c3_dynexit_c4_verify_kernels.md): measured HBM bytes per head.
+TRAFFIC_BYTES_C2 = 269.4e6 + 1.31e6        # 206 MB of weights, read 1.3 times by the two token groups
+TRAFFIC_RATIO_C3 = (263.3e6 + 0.28e6) / 257.7e6
+TRAFFIC_RATIO_C4 = (268.8e6 + 0.82e6) / 258.3e6
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -526,7 +531,7 @@ def main():
         avg_s = ev_s / launches
         roof = {"bound": "mfma", "achieved": flops_per_launch / avg_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": flops_per_launch / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": None,
+                "traffic": TRAFFIC_BYTES_C2,
                 "kernel": "eh::gemm32_stats_kernel<2,false> (one launch = one head on 512 rows; the time per "
                           "launch includes its 1/24 share of the LayerNorm and final-merge launches)",
                 "avg_launch_us": avg_s * 1e6,
@@ -587,7 +592,7 @@ def main():
         bytes_per_launch = w.d * w.V * esz + (evals / launches) * (w.d * esz + 12)
         avg_s = ev_s / launches
         roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C3 * bytes_per_launch,
                 "kernel": "eh::gemm32_stats_kernel<1,false> (one launch = one head on the live rows)",
                 "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
         cfg = {"workload": "c3_dynexit: d=2560 V=50304 32 heads x 64 rows bf16, rows exit at first H<tau, "
@@ -648,7 +653,7 @@ def main():
         bytes_per_launch = w.d * w.V * esz + Bsz * (k + 1) * (w.d * esz + 4)
         avg_s = ev_s / launches
         roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C4 * bytes_per_launch,
                 "kernel": "eh::gemm32_stats_kernel<2,true> (one launch = one verification, 144 positions)",
                 "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
         cfg = {"workload": "c4_verify: d=2560 V=50304 final head, 16 rows x (8 drafts + 1) bf16, "
