@@ -787,3 +787,55 @@ def test_head_losses_calibration_shape(B):
         assert (kl > -TOL_LOSS_ABS).all() and torch.isfinite(kl).all() and torch.isfinite(ce).all()
         print(f"head {head}: L_CE {loss[0].item():.4f} L_KL {loss[1].item():.4f}")
     B.eh_destroy(ctx)
+
+
+def test_dssd_draft_decode_shape(B):
+    """The decode workload's heads (d = 1024, V = 50304, 24 heads), windows of 32 positions as
+    bench.py drafts them: the oracle's cascade, position by position until the draft stops,
+    feeds its drafting rule; a window in which an entropy the decision hinged on lies within
+    1e-3 of its threshold is logged and skipped."""
+    w = G.CONFIGS["c1_decode"]
+    heads = G.make_heads(w, DEV)
+    limit, n_win = 32, 6
+    hid = G.make_hidden(w, heads, DEV, rows=limit * n_win)
+    tau = G.tau_linear(w)
+    f = P.f64
+    W64 = [f(x) for x in heads.W]
+    g64 = [f(x) for x in heads.gamma]
+    b64 = [f(x) for x in heads.beta]
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=1)
+    hp = hid.h.permute(1, 0, 2)
+    checked, skipped = 0, []
+    for i in range(n_win):
+        draft = torch.full((limit,), -7, dtype=torch.int32, device=DEV)
+        layers = torch.full((limit,), -7, dtype=torch.int32, device=DEV)
+        ln = torch.zeros(1, dtype=torch.int32, device=DEV)
+        reason = torch.zeros(1, dtype=torch.int32, device=DEV)
+        fb = torch.zeros(1, dtype=torch.int32, device=DEV)
+        nev = torch.zeros(1, dtype=torch.int64, device=DEV)
+        B.dssd_draft(ctx, hp[i * limit:(i + 1) * limit], limit, -1, draft, ln, layers, reason, fb, nev)
+        torch.cuda.synchronize()
+        B.eh_check(ctx)
+        Ht, At, close = [], [], False
+        for t in range(i * limit, (i + 1) * limit):
+            r = O.cascade([f(hid.h[l, t:t + 1]) for l in range(w.n_heads)], g64, b64, W64, tau, w.ln_eps, True)
+            e = int(r["exit_layer"][0])
+            Hrow = [float(r["H"][l][0]) if l <= e else float("nan") for l in range(w.n_heads)]
+            close = close or any(abs(Hrow[l] - tau[l]) < 1e-3 for l in range(min(e + 1, w.n_heads - 1)))
+            close = close or float(r["gap"][e][0]) < 1e-3
+            Ht.append(Hrow)
+            At.append([int(r["token"][0]) if l == e else -1 for l in range(w.n_heads)])
+            if e == w.n_heads - 1:
+                break
+        if close:
+            skipped.append(i)
+            continue
+        want = O.dssd_draft(Ht, At, tau, limit, -1)
+        n = int(ln.item())
+        got = dict(draft=draft[:n].tolist(), exit_layer=layers[:n].tolist(), reason=B.DRAFT_REASONS[int(reason.item())],
+                   fallback_token=int(fb.item()), n_evals=int(nev.item()))
+        assert got == want, (i, got, want)
+        checked += 1
+    print(f"draft windows checked {checked}, skipped for near-ties {skipped}")
+    assert checked >= n_win - 2
+    B.eh_destroy(ctx)
