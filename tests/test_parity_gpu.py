@@ -16,6 +16,7 @@ from tests import parity_util as P
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+TOL_P = 2e-4   # a probability moves by at most p(1-p) <= 1/4 of a logit error; logits carry fp32
 
 
 @pytest.fixture(scope="module")
@@ -260,14 +261,39 @@ def test_c2_batched_calibration(B):
     ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
     sample = torch.arange(0, R, 8, device=DEV)
     log = []
+    per_head = []
     for l in range(w.n_heads):
         H, lse, am = _outs(R)
         B.eh_eval(ctx, l, hid.h[l], R, H, lse, am)
         torch.cuda.synchronize()
+        per_head.append((H, lse, am))
         sel = slice(None) if l in (0, 11, 23) else sample
         orc = P.oracle_head(hid.h[l][sel], heads.gamma[l], heads.beta[l], heads.W[l], True)
         P.compare_head(f"c2/head{l}", H[sel], lse[sel], am[sel], orc, log)
     print("c2 near-ties:", log)
+    # the form bench.py times: all heads in one call (one projection launch for the 24 heads),
+    # bit for bit what the per-head calls gave; then the same with the two extra metrics
+    Hb = torch.full((w.n_heads, R), float("nan"), device=DEV)
+    Lb = torch.full((w.n_heads, R), float("nan"), device=DEV)
+    Ab = torch.full((w.n_heads, R), -7, dtype=torch.int32, device=DEV)
+    B.eh_eval_heads(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab)
+    torch.cuda.synchronize()
+    for l in range(w.n_heads):
+        assert torch.equal(Hb[l], per_head[l][0]) and torch.equal(Lb[l], per_head[l][1])
+        assert torch.equal(Ab[l], per_head[l][2])
+    Pm = torch.full((w.n_heads, R), float("nan"), device=DEV)
+    Mg = torch.full((w.n_heads, R), float("nan"), device=DEV)
+    H2, L2, A2 = torch.zeros_like(Hb), torch.zeros_like(Lb), torch.zeros_like(Ab)
+    B.eh_eval_heads_metrics(ctx, 0, w.n_heads, hid.h, R, H2, L2, A2, Pm, Mg)
+    torch.cuda.synchronize()
+    assert torch.equal(H2, Hb) and torch.equal(L2, Lb) and torch.equal(A2, Ab)
+    for l in (3, 20):
+        sel = sample[:32]
+        pm_o, mg_o = O.head_metrics(P.f64(hid.h[l][sel]), P.f64(heads.gamma[l]), P.f64(heads.beta[l]),
+                                    P.f64(heads.W[l]), 1e-5, True)
+        dp = np.abs(Pm[l][sel].double().cpu().numpy() - pm_o).max()
+        dm = np.abs(Mg[l][sel].double().cpu().numpy() - mg_o).max()
+        assert dp <= TOL_P and dm <= TOL_P, (l, dp, dm)
     B.eh_destroy(ctx)
 
 
@@ -432,7 +458,6 @@ def test_calibrate_large_set_properties(B, small_ctx):
 
 
 # --------------------------------------------------------------- the other two confidence metrics
-TOL_P = 2e-4   # a probability moves by at most p(1-p) <= 1/4 of a logit error; logits carry fp32
                # accumulation error well under 8e-4 at these sizes
 
 
