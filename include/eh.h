@@ -109,8 +109,9 @@ eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride
  * Several heads on the same positions in one call (Section 3.4.1, "Calibration of
  * Confidence Thresholds": the confidence of every head is needed at every token of
  * the calibration set).  Same results as eh_eval for heads head0 .. head0 +
- * n_heads_eval - 1, but the LayerNorm of all heads runs as one launch and so does
- * the final merge, which takes about 15 us per head off a 512-row batch.
+ * n_heads_eval - 1, but the LayerNorm of all heads runs as one launch and so do
+ * their projections (bf16 heads, more than 16 rows) and the final merge, which
+ * takes about 15 us per head off a 512-row batch.
  *
  * h_layers      device; head head0 + l reads row r at element
  *               l * layer_stride + r * row_stride
