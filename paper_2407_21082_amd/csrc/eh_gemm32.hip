@@ -275,15 +275,31 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
                                      (EH_LDS void*)(slot + wdst[i]), 16, 0, 0);
   };
   auto dma = [&](int ks) { static_for<kDma>([&](auto ic) { dma_part(ic, ks); }); };
+  // the same with the step's scalars (k offset in bytes, ring slot offset) worked out beforehand
+  auto dma_part_pre = [&](auto ic, long long k10, int slotoff) {
+    constexpr int i = decltype(ic)::value;
+    __builtin_amdgcn_global_load_lds((const EH_GLOBAL void*)(wbase + wsrc[i] + k10 + lane16),
+                                     (EH_LDS void*)(lds + slotoff + wdst[i]), 16, 0, 0);
+  };
   // activations: block n, k-step ks, half h -> fragment (n, 2*ks + h) of 2*KS per block
   const EH_GLOBAL char* ybase = uniform_ptr(yq);
   const EH_GLOBAL char* ybase2 = uniform_ptr(DUAL ? yq2 : yq);
-  auto load_b = [&](frag_t (&dst)[2], int n, int ks) {
+  auto b_ptr = [&](int n, int ks) {
     const bool side2 = DUAL && n >= NH;
-    const EH_GLOBAL char* p =
-        (side2 ? ybase2 : ybase) + (((long long)(side2 ? n - NH : n) * 2 * KS + 2 * min(ks, lastk)) << 10);
+    return (side2 ? ybase2 : ybase) + (((long long)(side2 ? n - NH : n) * 2 * KS + 2 * min(ks, lastk)) << 10);
+  };
+  auto load_b = [&](frag_t (&dst)[2], int n, int ks) {
+    const EH_GLOBAL char* p = b_ptr(n, ks);
     load_untracked<0>(dst[0], p, lane16);
     load_untracked<1024>(dst[1], p, lane16);
+  };
+  auto load_b_half = [&](frag_t& dst, int n, int ks, auto hc) {
+    load_untracked<decltype(hc)::value * 1024>(dst, b_ptr(n, ks), lane16);
+  };
+  auto load_b_half_pre = [&](frag_t& dst, int n, long long b10, auto hc) {
+    const bool side2 = DUAL && n >= NH;
+    const EH_GLOBAL char* p = (side2 ? ybase2 : ybase) + (((long long)(side2 ? n - NH : n) * 2 * KS) << 10) + b10;
+    load_untracked<decltype(hc)::value * 1024>(dst, p, lane16);
   };
   // LDS read with the 16x32 -> 32x16 lane permutation: lane l takes row l%32 and
   // k group 2h + l/32, i.e. lane (2h + l/32)*16 + l%16 of fragment (l%32)/16.
@@ -314,6 +330,15 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
   // tiles, the LDS reads for step ks+1 and the pieces of DMA(ks+D+1): a single wave issues
   // about one instruction per four cycles, so everything that is not a matrix instruction
   // has to sit between matrix instructions or the matrix core idles while it is issued.
+  // Scalars of a step's loads are worked out a few tiles ahead, where the wave has issue slots
+  // to spare (a wave issues one instruction per four clocks: anything left for the slot it is
+  // needed in delays the next matrix instruction): at tile kPre the byte offset of the
+  // activations of step ks+D, and k offset and ring slot of the weights of the NEXT step's DMA.
+  constexpr bool kAhead = MT >= 4;
+  constexpr int kPre = MT - 3;
+  long long nx_k10 = (long long)min(kDepth + 1, lastk) << 10;  // for step 0: DMA(D+1)
+  int nx_slot = ((kDepth + 1) & (kSlots - 1)) * kSlotBytes;
+  long long nx_b10 = 0;
   auto step = [&](frag_t (&b)[NB][2], int ks) {
     asm volatile("s_waitcnt vmcnt(%0) ; step-sync" ::"n"(kInFlight) : "memory");
 #pragma unroll
@@ -339,18 +364,36 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (m == 0 && h == 1) asm volatile("s_barrier" ::: "memory");
         if constexpr (m != 0) fetch_a_half(a[m][h], mc, hc, ks + 1);
-        if constexpr (h == 0) __builtin_amdgcn_sched_barrier(0);
-      });
-      if constexpr (m == MT - 1) {
+        if constexpr (m == MT - 1) {  // the last use of this k half of the activations: reload it for step ks+D
 #pragma unroll
-        for (int n = 0; n < NB; ++n) load_b(b[n], n, ks + kDepth);
-      }
-      if constexpr (m == 0) fetch_a(a[m], mc, ks + 1);  // slot ks+1 is complete only behind the barrier
-      // DMA piece i travels with tile min(i, MT-1)
-      static_for<kDma>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        if constexpr ((i < MT - 1 ? i : MT - 1) == m) dma_part(ic, ks + kDepth + 1);
+          for (int n = 0; n < NB; ++n) {
+            if constexpr (kAhead) load_b_half_pre(b[n][h], n, nx_b10, hc);
+            else load_b_half(b[n][h], n, ks + kDepth, hc);
+          }
+        }
+        if constexpr (h == 0) {
+          // DMA piece i travels with tile min(i, MT-1), behind its first matrix instructions
+          // (the slot it fills was last read several steps ago: no need to be past the barrier)
+          static_for<kDma>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr ((i < MT - 1 ? i : MT - 1) == m) {
+              if constexpr (kAhead) dma_part_pre(ic, nx_k10, nx_slot);
+              else dma_part(ic, ks + kDepth + 1);
+            }
+          });
+          if constexpr (kAhead && m == kPre) {
+            nx_b10 = (long long)(2 * min(ks + kDepth, lastk)) << 10;
+            asm volatile("" : "+s"(nx_b10));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        } else if constexpr (kAhead && m == kPre) {
+          // this step's DMA pieces (tiles 0 .. kDma-1 <= kPre, first slot) are out: the next step's
+          nx_k10 = (long long)min(ks + kDepth + 2, lastk) << 10;
+          nx_slot = ((ks + kDepth + 2) & (kSlots - 1)) * kSlotBytes;
+          asm volatile("" : "+s"(nx_k10), "+s"(nx_slot));
+        }
       });
+      if constexpr (m == 0) fetch_a(a[m], mc, ks + 1);  // slot ks+1 is complete only behind the barrier
       __builtin_amdgcn_sched_barrier(0);
     });
   };
