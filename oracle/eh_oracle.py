@@ -490,13 +490,18 @@ def calibrate_threshold(H, t, epsilon: float):
     the result does not depend on how ties are ordered; (ii) if no candidate
     qualifies the head never exits: tau = -inf; (iii) a NaN entropy is no
     candidate and belongs to no suffix (such a row never passes the exit test);
-    (iv) the proportion test is `correct >= epsilon * size` in float64.
+    (iv) the proportion test is the section's own expression, the quotient
+    correct / size compared with epsilon, the quotient being the correctly rounded
+    double (IEEE division): a proportion of exactly p/q therefore meets a level
+    written as the decimal p/q (7 of 10 at 0.7, 11 of 20 at 0.55), which a product
+    epsilon * size rounded to double does not guarantee.
 
     Quadratic on purpose (two nested sweeps, no sort, no running sums).
     Returns (tau, n) with n the number of samples with H <= tau.
     """
     H = np.asarray(H, dtype=np.float64)
     t = np.asarray(t)
+    level = float(epsilon)
     best_H, best_n = -np.inf, 0
     for j in range(H.shape[0]):
         if np.isnan(H[j]):
@@ -504,6 +509,6 @@ def calibrate_threshold(H, t, epsilon: float):
         inside = H <= H[j]                       # NaN compares false: never inside
         size = int(np.count_nonzero(inside))
         correct = int(np.count_nonzero(t[inside]))
-        if float(correct) >= float(epsilon) * float(size) and H[j] > best_H:
+        if correct / size >= level and H[j] > best_H:
             best_H, best_n = float(H[j]), size
     return best_H, best_n

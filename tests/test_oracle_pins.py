@@ -360,7 +360,7 @@ def _calibrate_by_sorting(H, t, eps):
     M = len(Hs)
     suffix_correct = np.cumsum(ts[::-1])[::-1]
     for j in range(M):
-        if suffix_correct[j] >= eps * (M - j):
+        if suffix_correct[j] / (M - j) >= eps:
             return float(Hs[j]), M - j
     return -np.inf, 0
 
@@ -452,6 +452,29 @@ def test_calibration_exhaustive_small():
                     want = (v, len(inside))
                     break
             assert O.calibrate_threshold(values, t, float(eps)) == want
+
+
+def test_calibration_level_at_the_boundary():
+    """Candidates that sit exactly on the level or beside it.  The proportion test is the
+    quotient correct / size, correctly rounded, against epsilon (Section 3.4.1): p of q samples
+    meet the level typed as the decimal p/q whichever side of p/q that decimal's double lies on,
+    one sample fewer does not, and the doubles next to the level decide as their order says."""
+    from fractions import Fraction
+    # the double nearest 0.7 lies below 7/10, those nearest 0.01 and 0.55 lie above 1/100 and 11/20
+    assert Fraction(0.7) < Fraction(7, 10) and Fraction(0.01) > Fraction(1, 100) and Fraction(0.55) > Fraction(11, 20)
+
+    def one_value(n, c, eps):          # n samples at one entropy, c of them right: a single candidate
+        return O.calibrate_threshold(np.full(n, 1.25), np.array([1] * c + [0] * (n - c)), eps)
+
+    for eps, n, c in ((0.7, 10, 7), (0.01, 100, 1), (0.55, 20, 11), (0.02, 50, 1), (0.07, 100, 7), (0.4, 5, 2),
+                      (0.3, 10, 3), (0.1, 10, 1), (0.9, 10, 9), (0.6, 5, 3), (1.0, 9, 9), (0.0, 4, 0)):
+        assert one_value(n, c, eps) == (1.25, n), (eps, n, c)
+        if c > 0:
+            assert one_value(n, c - 1, eps) == (-np.inf, 0), (eps, n, c)
+        up, down = float(np.nextafter(eps, 2.0)), float(np.nextafter(eps, -1.0))
+        assert one_value(n, c, up) == (-np.inf, 0), (eps, n, c)
+        if eps > 0.0:
+            assert one_value(n, c, down) == (1.25, n), (eps, n, c)
 
 
 def test_correctness_indicator():
