@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the early-exit head evaluation hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1_decode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
 Default workload (the one the headline metric is quoted on): batch-1 decode,
 Pythia-410M-shaped heads (d=1024, V=50304, 23 exit heads + final, bf16 weights,
@@ -15,7 +15,16 @@ Prints ONE JSON line:  value = (row, head) evaluations per second over the
 timed steps; "roofline" = algorithmic bytes of the dominant kernel per launch
 over its average launch duration (HIP events on the launch stream) against
 the 8 TB/s HBM peak; "cpu_baseline" = the fp64 CPU oracle timed on a bounded
-sample of the same workload on this machine's host cores.
+sample of the same workload on this machine's host cores (all BLAS threads, and
+one thread as "value_1core").
+
+Without --workload the line is the decode workload's and carries two more
+objects, timed in the same run: "batched" = the batched configurations
+(calibration pass on 512 tokens against the matrix-core peak; 64-row dynamic
+exit and 144-position verification against the HBM peak), each with its own
+evaluations/s, time per head and roofline object, and "read_ceiling" = what a
+plain read of the same weight buffers reaches on this chip.  With --workload
+NAME only that workload runs and the line is its own.
 """
 from __future__ import annotations
 
@@ -49,8 +58,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c1_decode",
-                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify", "f1_calibrate", "f3_draft", "f4_losses"])
+    ap.add_argument("--workload", default=None,
+                    choices=["c1_decode", "c2_calib", "c3_dynexit", "c4_verify", "f1_calibrate", "f3_draft", "f4_losses",
+                             "read_ceiling", "mfma_ceiling"])
+    ap.add_argument("--batched-steps", type=int, default=100,
+                    help="timed steps of each batched configuration in the default run (their steps are milliseconds)")
+    ap.add_argument("--batched-warmup", type=int, default=20)
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per bench step (c1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -59,9 +72,6 @@ def parse():
     ap.add_argument("--metrics", action="store_true",
                     help="c2_calib only: also produce the maximum probability and the top-2 probability "
                          "difference of every (head, token) (eh_eval_heads_metrics)")
-    ap.add_argument("--library-gemm", action="store_true",
-                    help="only time the vendor GEMM library (torch.matmul, bf16) on the workload's "
-                         "projection shape: context for the MFMA roofline fraction, not part of the path")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -350,6 +360,353 @@ def bench_losses(args, torch, B, G, dev):
     print(json.dumps(line), flush=True)
 
 
+def timed(torch, step, steps, warmup):
+    """warmup untimed steps, then `steps` timed ones between HIP events on the launch stream
+    (and the host clock around the same region).  Returns (host seconds, event seconds)."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0, ev0.elapsed_time(ev1) * 1e-3
+
+
+def oracle_rate(run_some, seconds):
+    """Times the oracle twice on the same sample recipe: with one BLAS thread for about a
+    third of the budget, then with all of them.  run_some(deadline_seconds) -> (units, spent)."""
+    out = {}
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1, user_api="blas"):
+            n1, t1 = run_some(max(2.0, seconds / 3.0))
+        out["value_1core"] = n1 / t1
+        out["sample_1core"] = f"{n1} units in {t1:.1f} s with one BLAS thread"
+    except Exception as e:        # threadpoolctl missing: the all-thread figure alone
+        out["value_1core"] = None
+        out["sample_1core"] = f"not measured ({type(e).__name__})"
+    n, t = run_some(seconds)
+    out["value"] = n / t
+    return out, n, t
+
+
+def run_c1(args, torch, B, G, dev, steps, warmup, cpu_leg, ceiling):
+    import numpy as np
+    w = G.CONFIGS["c1_decode"]
+    heads = G.make_heads(w, dev)
+    esz = 2
+    n_dec = args.decode_steps or w.steps
+    hid = G.make_hidden(w, heads, dev, rows=n_dec)           # [n_heads, n_dec, d]
+    tau = G.tau_linear(w)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=16)
+    ex = torch.full((n_dec,), -1, dtype=torch.int32, device=dev)
+    tok = torch.full((n_dec,), -1, dtype=torch.int32, device=dev)
+    nev = torch.zeros(1, dtype=torch.int64, device=dev)
+    views = [hid.h[:, t:t + 1] for t in range(n_dec)]
+
+    def step():
+        for t in range(n_dec):
+            B.eh_cascade(ctx, views[t], 1, ex[t:t + 1], tok[t:t + 1], None, nev)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    nev.zero_()
+    dt, ev_s = timed(torch, step, steps, 0)
+    B.eh_check(ctx)                       # raises if the kernel reported a device-side failure
+    evals = int(nev.item())
+    # Dominant kernel: the persistent decode kernel, one launch per decode step (LayerNorm,
+    # projection, entropy/argmax, exchange and exit test of every head up to the exit head).
+    # Algorithmic bytes per launch = evaluations in that launch x (weights of one head + one
+    # hidden row + 12 bytes of results); average launch duration from HIP events around the
+    # timed region, on the stream the launches went to (launches are back to back).
+    launches = steps * n_dec
+    bytes_per_eval = w.d * w.V * esz + w.d * esz + 12
+    bytes_per_launch = bytes_per_eval * evals / launches
+    avg_s = ev_s / launches
+    roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
+            "traffic": TRAFFIC_RATIO_C1 * bytes_per_launch,
+            "kernel": "eh::decode_kernel<DtBf16> (one launch = one decode step's cascade)",
+            "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
+    cfg = {"workload": "c1_decode: d=1024 V=50304 24 heads batch-1 bf16, "
+                       f"{n_dec} decode steps per bench step, exit at first H<tau",
+           "decode_steps": n_dec, "mean_evals_per_decode_step": evals / launches,
+           "mean_exit_layer": float(ex.float().mean().item())}
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+           "cpu_baseline": None}
+    if ceiling:
+        res["read_ceiling"] = read_ceiling(torch, B, ctx, w, dev)
+    if cpu_leg:
+        from oracle import eh_oracle as O
+        f64 = G.to_f64_numpy
+        W64 = [f64(Wl) for Wl in heads.W]                      # input marshalling, not timed
+        g64 = [f64(g) for g in heads.gamma]
+        b64 = [f64(b) for b in heads.beta]
+
+        def run_some(seconds):
+            done_evals, t0 = 0, time.perf_counter()
+            for t in range(0, n_dec):
+                hl = [f64(hid.h[l, t:t + 1]) for l in range(w.n_heads)]
+                r = O.cascade(hl, g64, b64, W64, tau, w.ln_eps, True)
+                done_evals += int(r["exit_layer"][0]) + 1
+                if time.perf_counter() - t0 > seconds:
+                    break
+            return done_evals, time.perf_counter() - t0
+
+        rates, n, t = oracle_rate(run_some, args.cpu_seconds)
+        res["cpu_baseline"] = {"value": rates["value"], "unit": "evals/s", "cores": oracle_threads(), "kind": "oracle",
+                               "value_1core": rates["value_1core"],
+                               "sample": f"the first decode steps of the same workload ({n} evaluations, {t:.1f} s; fp64 "
+                                         f"numpy, weights pre-widened); one core: {rates['sample_1core']}"}
+    B.eh_destroy(ctx)
+    return res
+
+
+def read_ceiling(torch, B, ctx, w, dev, reps=5):
+    """A plain read of the context's weight buffers: what the chip delivers to the simplest
+    streaming kernel, as one launch over all heads and as one launch per head, with loads into
+    registers (the decode kernel's way) and straight into LDS (the batched kernel's way)."""
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+    out = {"unit": "GB/s", "peak": HBM_PEAK_GBS, "heads": w.n_heads}
+    for how, hname in ((B.PROBE_READ_REGISTERS, "registers"), (B.PROBE_READ_LDS, "lds")):
+        for per_head, lname in ((False, "one_launch"), (True, "launch_per_head")):
+            nbytes = B.eh_probe_read_weights(ctx, how, per_head, 0, w.n_heads, sink)     # warm-up
+            torch.cuda.synchronize()
+            ms = event_ms(lambda: [B.eh_probe_read_weights(ctx, how, per_head, 0, w.n_heads, sink) for _ in range(reps)],
+                          torch)
+            out[f"{hname}_{lname}"] = nbytes * reps / (ms * 1e-3) / 1e9
+    out["bytes_per_sweep"] = nbytes
+    return out
+
+
+def run_c2(args, torch, B, G, dev, steps, warmup, cpu_leg):
+    # every head on every token; one step = all 24 heads on 512 tokens (eh_eval_heads)
+    w = G.CONFIGS["c2_calib"]
+    heads = G.make_heads(w, dev)
+    hid = G.make_hidden(w, heads, dev)
+    R = w.rows
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
+    Hb = torch.zeros((w.n_heads, R), device=dev)
+    Lb = torch.zeros((w.n_heads, R), device=dev)
+    Ab = torch.zeros((w.n_heads, R), dtype=torch.int32, device=dev)
+    Pb = torch.zeros((w.n_heads, R), device=dev)
+    Mb = torch.zeros((w.n_heads, R), device=dev)
+
+    def step():
+        # all heads in one call: one LayerNorm launch, one projection launch, one launch for the final merges
+        if args.metrics:
+            B.eh_eval_heads_metrics(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab, Pb, Mb)
+        else:
+            B.eh_eval_heads(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab)
+
+    dt, ev_s = timed(torch, step, steps, warmup)
+    evals = steps * w.n_heads * R
+    launches = steps * w.n_heads
+    flops_per_launch = 2.0 * w.d * w.V * R
+    avg_s = ev_s / launches
+    roof = {"bound": "mfma", "achieved": flops_per_launch / avg_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": flops_per_launch / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "traffic": TRAFFIC_BYTES_C2,
+            "kernel": "eh::gemm32_stats_kernel<2,false,false> (one head on 512 rows = 1/24 of the launch; the time "
+                      "per head includes its share of the LayerNorm and final-merge launches)",
+            "avg_launch_us": avg_s * 1e6,
+            "flops_per_launch": flops_per_launch, "launches": launches}
+    cfg = {"workload": "c2_calib: d=2048 V=50304 24 heads x 512 tokens bf16, all heads on all tokens"
+                       + (", with max-probability and top-2 difference" if args.metrics else "")}
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+           "cpu_baseline": None, "us_per_head": avg_s * 1e6}
+    if cpu_leg:
+        res["cpu_baseline"] = cpu_head_evals(args, G, heads, ((l, hid.h[l][:128]) for l in range(w.n_heads)),
+                                             "the first 128 tokens of each head in turn")
+    B.eh_destroy(ctx)
+    return res
+
+
+def run_c3(args, torch, B, G, dev, steps, warmup, cpu_leg, keep=None):
+    # 64 decode rows through 32 heads; a row leaves at its first H < tau and the
+    # survivors are compacted between heads.  Thresholds: the 10/40/70 % exit schedule,
+    # set from this library's own entropies of every head on every row (a bench input,
+    # not a parity reference).
+    w = G.CONFIGS["c3_dynexit"]
+    heads = G.make_heads(w, dev)
+    esz = 2
+    hid = G.make_hidden(w, heads, dev)
+    R = w.rows
+    ctx0 = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")] * w.n_heads, max_rows=R)
+    Hall = torch.zeros((w.n_heads, R), device=dev)
+    for l in range(w.n_heads):
+        B.eh_eval(ctx0, l, hid.h[l], R, Hall[l], None, None)
+    torch.cuda.synchronize()
+    B.eh_destroy(ctx0)
+    tau = G.tau_for_schedule(Hall.cpu().numpy(), w.n_heads)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=R)
+    ex = torch.full((R,), -1, dtype=torch.int32, device=dev)
+    tok = torch.full((R,), -1, dtype=torch.int32, device=dev)
+    nev = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def step():
+        B.eh_cascade(ctx, hid.h, R, ex, tok, None, nev)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    nev.zero_()
+    dt, ev_s = timed(torch, step, steps, 0)
+    B.eh_check(ctx)
+    evals = int(nev.item())
+    exl = ex.cpu().numpy()
+    heads_run = int(exl.max()) + 1                       # heads that still had a live row
+    launches = steps * heads_run
+    # dominant kernel: the projection of one head on the live rows; it streams the head's
+    # weights once whatever the number of live rows (HBM-bound: <= 64 flop per byte)
+    bytes_per_launch = w.d * w.V * esz + (evals / launches) * (w.d * esz + 12)
+    avg_s = ev_s / launches
+    roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C3 * bytes_per_launch,
+            "kernel": "the projection of one head on the live rows (time per head = cascade time / heads run)",
+            "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
+    cfg = {"workload": "c3_dynexit: d=2560 V=50304 32 heads x 64 rows bf16, rows exit at first H<tau, "
+                       "compaction between heads",
+           "mean_evals_per_cascade": evals / steps,
+           "exited_by_layer_8_16_24": [float((exl < l).mean()) for l in (8, 16, 24)]}
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+           "cpu_baseline": None, "us_per_head": avg_s * 1e6}
+    if cpu_leg:
+        # head by head on the rows this run's cascade kept alive up to that head
+        exd = ex.to(dev)
+        res["cpu_baseline"] = cpu_head_evals(args, G, heads, ((l, hid.h[l][exd >= l]) for l in range(heads_run)),
+                                             "each head in turn on the rows still alive at it")
+    B.eh_destroy(ctx)
+    if keep is not None:
+        keep["heads"] = heads
+    return res
+
+
+def run_c4(args, torch, B, G, dev, steps, warmup, cpu_leg, heads=None):
+    # 16 rows x (8 drafts + 1): argmax of the final head at 144 positions and the accepted
+    # prefix per row.  Four copies of the final head are used in turn so that the 257.6 MB
+    # weight stream comes from HBM, not from the last-level cache.
+    w = G.CONFIGS["c4_verify"]
+    esz = 2
+    fin = w.n_heads - 1
+    if heads is None:
+        heads = G.make_heads(w, dev)
+    Bsz, k = 16, 8
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    draft = torch.randint(0, w.V, (Bsz, k), generator=gen, device=dev)
+    case = G.make_verify_case(w, heads, draft, dev)
+    n_copies = 4
+    ctxs = []
+    for c in range(n_copies):
+        Wc = heads.W[fin].clone()
+        ctxs.append(B.eh_create([Wc], [heads.gamma[fin]], [heads.beta[fin]], [float("inf")],
+                                max_rows=Bsz * (k + 1)))
+        del Wc
+    acc = torch.full((Bsz,), -1, dtype=torch.int32, device=dev)
+    nxt = torch.full((Bsz,), -1, dtype=torch.int32, device=dev)
+    d32 = draft.to(torch.int32).contiguous()
+    calls_per_step = 8
+
+    def step():
+        for i in range(calls_per_step):
+            B.dssd_verify(ctxs[i % n_copies], case.f_final, d32, None, acc, nxt, None)
+
+    dt, ev_s = timed(torch, step, steps, warmup)
+    launches = steps * calls_per_step
+    evals = launches * Bsz * (k + 1)
+    bytes_per_launch = w.d * w.V * esz + Bsz * (k + 1) * (w.d * esz + 4)
+    avg_s = ev_s / launches
+    roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C4 * bytes_per_launch,
+            "kernel": "the argmax-only projection of one verification, 144 positions (time per verification = "
+                      "all launches of a dssd_verify call)",
+            "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
+    cfg = {"workload": "c4_verify: d=2560 V=50304 final head, 16 rows x (8 drafts + 1) bf16, "
+                       f"{calls_per_step} verifications per bench step over {n_copies} weight copies",
+           "mean_accepted": float(acc.float().mean().item())}
+    # the bookkeeping of Section 4.3.2 on this batch's outcome (outside the timed region)
+    counters = torch.zeros(5, dtype=torch.int64, device=dev)
+    B.dssd_tally(ctxs[0], None, acc, Bsz, k, None, counters)
+    cnt = counters.tolist()
+    cfg.update(drafted=cnt[1], accepted=cnt[2], wasted=cnt[3], acceptance_rate=cnt[2] / max(cnt[1], 1))
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+           "cpu_baseline": None, "us_per_head": avg_s * 1e6}
+    if cpu_leg:
+        from oracle import eh_oracle as O
+        f64 = G.to_f64_numpy
+        W64, g64, b64 = f64(heads.W[fin]), f64(heads.gamma[fin]), f64(heads.beta[fin])
+        done, spent = 0, 0.0
+        for b0 in range(0, Bsz, 2):
+            f2, d2 = f64(case.f_final[b0:b0 + 2]), draft[b0:b0 + 2].cpu().numpy()
+            c0 = time.perf_counter()
+            O.dssd_verify(f2, d2, g64, b64, W64, None, 1e-5, True)
+            spent += time.perf_counter() - c0
+            done += 2 * (k + 1)
+            if spent > args.cpu_seconds:
+                break
+        res["cpu_baseline"] = {"value": done / spent, "unit": "evals/s", "cores": oracle_threads(), "kind": "oracle",
+                               "sample": f"{done // (k + 1)} of the {Bsz} rows, two at a time ({done} evaluations, "
+                                         f"{spent:.1f} s; fp64 numpy, weights pre-widened)"}
+    for c in ctxs:
+        B.eh_destroy(c)
+    return res
+
+
+def run_ceiling(args, torch, B, G, dev):
+    """--workload read_ceiling / mfma_ceiling: the practical ceilings alone, as their own line."""
+    t_setup = time.time()
+    if args.workload == "read_ceiling":
+        out = {}
+        for name in ("c1_decode", "c3_dynexit"):
+            w = G.CONFIGS[name]
+            heads = G.make_heads(w, dev)
+            ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")] * w.n_heads, max_rows=16)
+            del heads
+            out[name] = read_ceiling(torch, B, ctx, w, dev, reps=max(1, args.steps))
+            B.eh_destroy(ctx)
+            torch.cuda.empty_cache()
+        best = out["c1_decode"]["registers_one_launch"]
+        line = {"metric": "weight_read_GBps", "value": best, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                "warmup": 1, "ms_per_step": out["c1_decode"]["bytes_per_sweep"] / best / 1e6, "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+                "config": {"workload": "read_ceiling: a plain read of every head's re-tiled weights (2.47 GB for the decode "
+                                       "workload, 8.24 GB for the 64-row one), four variants each", "variants": out},
+                "roofline": {"bound": "hbm", "achieved": best, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": best / HBM_PEAK_GBS, "traffic": None, "kernel": "eh probe_read_reg_kernel, one launch"},
+                "cpu_baseline": None, "setup_s": round(time.time() - t_setup, 1)}
+    else:
+        w = G.Workload("probe", d=64, V=64, n_heads=1, rows=4, dtype="bf16", seed=1)
+        heads = G.make_heads(w, dev)
+        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")], max_rows=4)
+        sink = torch.zeros(1024 * 256, device=dev)
+        out = {}
+        for name, iters, rnd in (("zeros_4000", 4000, False), ("random_4000", 4000, True), ("random_130", 130, True)):
+            flops = B.eh_probe_mfma(ctx, iters, rnd, sink)
+            torch.cuda.synchronize()
+            reps = max(3, args.steps)
+            ms = event_ms(lambda: [B.eh_probe_mfma(ctx, iters, rnd, sink) for _ in range(reps)], torch)
+            out[name] = flops * reps / (ms * 1e-3) / 1e12
+        B.eh_destroy(ctx)
+        best = out["random_4000"]
+        line = {"metric": "mfma_bf16_TFLOPs", "value": best, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+                "warmup": 1, "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                "dtype": "bf16", "data": "synthetic",
+                "config": {"workload": "mfma_ceiling: the batched kernel's 28 matrix instructions per k-step from registers "
+                                       "only, one workgroup of 4 waves per compute unit; iterations and operands vary",
+                           "variants_TFLOPs": out},
+                "roofline": {"bound": "mfma", "achieved": best, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": best / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "eh probe_mfma_kernel"},
+                "cpu_baseline": None, "setup_s": round(time.time() - t_setup, 1)}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -357,7 +714,6 @@ def main():
               "supported (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     from paper_2407_21082_amd import binding as B     # raises if libeh.so is missing
@@ -385,313 +741,46 @@ def main():
         return bench_draft(args, torch, B, G, dev)
     if args.workload == "f4_losses":
         return bench_losses(args, torch, B, G, dev)
-    w = G.CONFIGS[args.workload]
-    if args.library_gemm:
-        R = max(w.rows, 16)
-        y = torch.randn(R, w.d, device=dev, dtype=torch.bfloat16)
-        Ws = [torch.randn(w.V, w.d, device=dev, dtype=torch.bfloat16) * 0.02 for _ in range(6)]
-        o = torch.empty(R, w.V, device=dev, dtype=torch.bfloat16)
-        for Wl in Ws:
-            torch.matmul(y, Wl.t(), out=o)
-        torch.cuda.synchronize()
-        n = 0
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(4):
-            for Wl in Ws:
-                torch.matmul(y, Wl.t(), out=o)
-                n += 1
-        e1.record()
-        e1.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / n
-        print(json.dumps({"library_gemm": {"shape": [R, w.d, w.V], "dtype": "bf16", "us_per_gemm": us,
-                                           "tflops": 2.0 * R * w.d * w.V / us * 1e-6,
-                                           "note": "logits written as bf16, no LayerNorm, no statistics"}}))
-        return
+    if args.workload in ("read_ceiling", "mfma_ceiling"):
+        return run_ceiling(args, torch, B, G, dev)
     t_setup = time.time()
-    heads = G.make_heads(w, dev)
-    esz = 2 if w.dtype == "bf16" else 4
-    out = {}
+    cpu_leg = not args.no_cpu_baseline
+    extra = {}
+    if args.workload is None:
+        # the headline line (decode) plus the batched configurations, all timed in this run
+        res = run_c1(args, torch, B, G, dev, args.steps, args.warmup, cpu_leg, ceiling=True)
+        extra["read_ceiling"] = res.pop("read_ceiling")
+        torch.cuda.empty_cache()
+        bs, bw = args.batched_steps, args.batched_warmup
+        batched = {}
 
-    if args.workload == "c1_decode":
-        n_dec = args.decode_steps or w.steps
-        hid = G.make_hidden(w, heads, dev, rows=n_dec)           # [n_heads, n_dec, d]
-        tau = G.tau_linear(w)
-        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=16)
-        ex = torch.full((n_dec,), -1, dtype=torch.int32, device=dev)
-        tok = torch.full((n_dec,), -1, dtype=torch.int32, device=dev)
-        nev = torch.zeros(1, dtype=torch.int64, device=dev)
-        views = [hid.h[:, t:t + 1] for t in range(n_dec)]
+        def brief(r):
+            return {"value": r["value"], "unit": "evals/s", "us_per_head": r["us_per_head"], "steps": bs, "warmup": bw,
+                    "workload": r["config"]["workload"], "roofline": r["roofline"]}
 
-        def step():
-            for t in range(n_dec):
-                B.eh_cascade(ctx, views[t], 1, ex[t:t + 1], tok[t:t + 1], None, nev)
-
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        nev.zero_()
-        torch.cuda.synchronize()
-        ev0 = torch.cuda.Event(enable_timing=True)
-        ev1 = torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        ev0.record()
-        for _ in range(args.steps):
-            step()
-        ev1.record()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        ev_s = ev0.elapsed_time(ev1) * 1e-3
-        B.eh_check(ctx)                       # raises if the kernel reported a device-side failure
-        evals = int(nev.item())
-        evals_per_step = evals / args.steps
-        value = evals / dt
-
-        # Dominant kernel: the persistent decode kernel, one launch per decode step
-        # (LayerNorm, projection, entropy/argmax, exchange and exit test of every head
-        # up to the exit head).  Algorithmic bytes per launch = evaluations in that
-        # launch x (weights of one head + one hidden row + 12 bytes of results);
-        # average launch duration from HIP events around the timed region, on the
-        # stream the launches went to (launches are back to back).
-        launches = args.steps * n_dec
-        bytes_per_eval = w.d * w.V * esz + w.d * esz + 12
-        bytes_per_launch = bytes_per_eval * evals / launches
-        avg_s = ev_s / launches
-        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
-                "traffic": TRAFFIC_RATIO_C1 * bytes_per_launch,
-                "kernel": "eh::decode_kernel<DtBf16> (one launch = one decode step's cascade)",
-                "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch,
-                "launches": launches}
-        cfg = {"workload": "c1_decode: d=1024 V=50304 24 heads batch-1 bf16, "
-                           f"{n_dec} decode steps per bench step, exit at first H<tau",
-               "decode_steps": n_dec, "mean_evals_per_decode_step": evals_per_step / n_dec,
-               "mean_exit_layer": float(ex.float().mean().item())}
-        out.update(ms_per_step=dt / args.steps * 1e3)
-
-        cpu = None
-        if not args.no_cpu_baseline:
-            from oracle import eh_oracle as O
-            f64 = G.to_f64_numpy
-            W64 = [f64(Wl) for Wl in heads.W]                      # input marshalling, not timed
-            g64 = [f64(g) for g in heads.gamma]
-            b64 = [f64(b) for b in heads.beta]
-            done_evals, done_steps = 0, 0
-            t0 = time.perf_counter()
-            for t in range(0, n_dec):
-                hl = [f64(hid.h[l, t:t + 1]) for l in range(w.n_heads)]
-                r = O.cascade(hl, g64, b64, W64, tau, w.ln_eps, True)
-                done_evals += int(r["exit_layer"][0]) + 1
-                done_steps += 1
-                if time.perf_counter() - t0 > args.cpu_seconds:
-                    break
-            cdt = time.perf_counter() - t0
-            cpu = {"value": done_evals / cdt, "unit": "evals/s", "cores": oracle_threads(),
-                   "kind": "oracle",
-                   "sample": f"first {done_steps} decode steps of the same workload "
-                             f"({done_evals} evaluations, {cdt:.1f} s; fp64 numpy, weights pre-widened)"}
-        B.eh_destroy(ctx)
+        batched["c2_calib"] = brief(run_c2(args, torch, B, G, dev, bs, bw, False))
+        torch.cuda.empty_cache()
+        keep = {}
+        batched["c3_dynexit"] = brief(run_c3(args, torch, B, G, dev, bs, bw, False, keep))
+        batched["c4_verify"] = brief(run_c4(args, torch, B, G, dev, bs, bw, False, keep.get("heads")))
+        extra["batched"] = batched
+    elif args.workload == "c1_decode":
+        res = run_c1(args, torch, B, G, dev, args.steps, args.warmup, cpu_leg, ceiling=False)
     elif args.workload == "c2_calib":
-        # every head on every token; one step = all 24 heads on 512 tokens (eh_eval_heads)
-        hid = G.make_hidden(w, heads, dev)
-        R = w.rows
-        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=R)
-        Hb = torch.zeros((w.n_heads, R), device=dev)
-        Lb = torch.zeros((w.n_heads, R), device=dev)
-        Ab = torch.zeros((w.n_heads, R), dtype=torch.int32, device=dev)
-        Pb = torch.zeros((w.n_heads, R), device=dev)
-        Mb = torch.zeros((w.n_heads, R), device=dev)
-
-        def step():
-            # all heads in one call: one LayerNorm launch, one projection launch per head,
-            # one launch for the final merges
-            if args.metrics:
-                B.eh_eval_heads_metrics(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab, Pb, Mb)
-            else:
-                B.eh_eval_heads(ctx, 0, w.n_heads, hid.h, R, Hb, Lb, Ab)
-
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        ev0 = torch.cuda.Event(enable_timing=True)
-        ev1 = torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        ev0.record()
-        for _ in range(args.steps):
-            step()
-        ev1.record()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        ev_s = ev0.elapsed_time(ev1) * 1e-3
-        evals = args.steps * w.n_heads * R
-        value = evals / dt
-        launches = args.steps * w.n_heads
-        flops_per_launch = 2.0 * w.d * w.V * R
-        avg_s = ev_s / launches
-        roof = {"bound": "mfma", "achieved": flops_per_launch / avg_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": flops_per_launch / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": TRAFFIC_BYTES_C2,
-                "kernel": "eh::gemm32_stats_kernel<2,false> (one launch = one head on 512 rows; the time per "
-                          "launch includes its 1/24 share of the LayerNorm and final-merge launches)",
-                "avg_launch_us": avg_s * 1e6,
-                "flops_per_launch": flops_per_launch, "launches": launches}
-        cfg = {"workload": "c2_calib: d=2048 V=50304 24 heads x 512 tokens bf16, all heads on all tokens"
-                           + (", with max-probability and top-2 difference" if args.metrics else "")}
-        out.update(ms_per_step=dt / args.steps * 1e3)
-        cpu = None
-        if not args.no_cpu_baseline:
-            cpu = cpu_head_evals(args, G, heads, ((l, hid.h[l][:128]) for l in range(w.n_heads)),
-                                 "the first 128 tokens of each head in turn")
-        B.eh_destroy(ctx)
+        res = run_c2(args, torch, B, G, dev, args.steps, args.warmup, cpu_leg)
     elif args.workload == "c3_dynexit":
-        # 64 decode rows through 32 heads; a row leaves at its first H < tau and the
-        # survivors are compacted between heads.  Thresholds: the 10/40/70 % exit schedule,
-        # set from this library's own entropies of every head on every row (a bench input,
-        # not a parity reference).
-        hid = G.make_hidden(w, heads, dev)
-        R = w.rows
-        ctx0 = B.eh_create(heads.W, heads.gamma, heads.beta, [float("inf")] * w.n_heads, max_rows=R)
-        Hall = torch.zeros((w.n_heads, R), device=dev)
-        for l in range(w.n_heads):
-            B.eh_eval(ctx0, l, hid.h[l], R, Hall[l], None, None)
-        torch.cuda.synchronize()
-        B.eh_destroy(ctx0)
-        tau = G.tau_for_schedule(Hall.cpu().numpy(), w.n_heads)
-        ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=R)
-        ex = torch.full((R,), -1, dtype=torch.int32, device=dev)
-        tok = torch.full((R,), -1, dtype=torch.int32, device=dev)
-        nev = torch.zeros(1, dtype=torch.int64, device=dev)
-
-        def step():
-            B.eh_cascade(ctx, hid.h, R, ex, tok, None, nev)
-
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        nev.zero_()
-        torch.cuda.synchronize()
-        ev0 = torch.cuda.Event(enable_timing=True)
-        ev1 = torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        ev0.record()
-        for _ in range(args.steps):
-            step()
-        ev1.record()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        ev_s = ev0.elapsed_time(ev1) * 1e-3
-        B.eh_check(ctx)
-        evals = int(nev.item())
-        value = evals / dt
-        exl = ex.cpu().numpy()
-        heads_run = int(exl.max()) + 1                       # heads that still had a live row
-        launches = args.steps * heads_run
-        # dominant kernel: the batched projection of one head on the live rows; it streams the
-        # head's weights once whatever the number of live rows (HBM-bound: <= 64 flop per byte)
-        bytes_per_launch = w.d * w.V * esz + (evals / launches) * (w.d * esz + 12)
-        avg_s = ev_s / launches
-        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C3 * bytes_per_launch,
-                "kernel": "eh::gemm32_stats_kernel<1,false> (one launch = one head on the live rows)",
-                "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
-        cfg = {"workload": "c3_dynexit: d=2560 V=50304 32 heads x 64 rows bf16, rows exit at first H<tau, "
-                           "compaction between heads",
-               "mean_evals_per_cascade": evals / args.steps,
-               "exited_by_layer_8_16_24": [float((exl < l).mean()) for l in (8, 16, 24)]}
-        out.update(ms_per_step=dt / args.steps * 1e3)
-        cpu = None
-        if not args.no_cpu_baseline:
-            # head by head on the rows this run's cascade kept alive up to that head
-            exd = ex.to(dev)
-            cpu = cpu_head_evals(args, G, heads,
-                                 ((l, hid.h[l][exd >= l]) for l in range(heads_run)),
-                                 "each head in turn on the rows still alive at it")
-        B.eh_destroy(ctx)
+        res = run_c3(args, torch, B, G, dev, args.steps, args.warmup, cpu_leg)
     elif args.workload == "c4_verify":
-        # 16 rows x (8 drafts + 1): argmax of the final head at 144 positions and the accepted
-        # prefix per row.  Four copies of the final head are used in turn so that the 257.6 MB
-        # weight stream comes from HBM, not from the last-level cache.
-        Bsz, k = 16, 8
-        fin = w.n_heads - 1
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(1234)
-        draft = torch.randint(0, w.V, (Bsz, k), generator=gen, device=dev)
-        case = G.make_verify_case(w, heads, draft, dev)
-        n_copies = 4
-        ctxs = []
-        for c in range(n_copies):
-            Wc = heads.W[fin].clone()
-            ctxs.append(B.eh_create([Wc], [heads.gamma[fin]], [heads.beta[fin]], [float("inf")],
-                                    max_rows=Bsz * (k + 1)))
-            del Wc
-        acc = torch.full((Bsz,), -1, dtype=torch.int32, device=dev)
-        nxt = torch.full((Bsz,), -1, dtype=torch.int32, device=dev)
-        d32 = draft.to(torch.int32).contiguous()
-        calls_per_step = 8
-
-        def step():
-            for i in range(calls_per_step):
-                B.dssd_verify(ctxs[i % n_copies], case.f_final, d32, None, acc, nxt, None)
-
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        ev0 = torch.cuda.Event(enable_timing=True)
-        ev1 = torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        ev0.record()
-        for _ in range(args.steps):
-            step()
-        ev1.record()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        ev_s = ev0.elapsed_time(ev1) * 1e-3
-        launches = args.steps * calls_per_step
-        evals = launches * Bsz * (k + 1)
-        value = evals / dt
-        bytes_per_launch = w.d * w.V * esz + Bsz * (k + 1) * (w.d * esz + 4)
-        avg_s = ev_s / launches
-        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C4 * bytes_per_launch,
-                "kernel": "eh::gemm32_stats_kernel<2,true> (one launch = one verification, 144 positions)",
-                "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
-        cfg = {"workload": "c4_verify: d=2560 V=50304 final head, 16 rows x (8 drafts + 1) bf16, "
-                           f"{calls_per_step} verifications per bench step over {n_copies} weight copies",
-               "mean_accepted": float(acc.float().mean().item())}
-        # the bookkeeping of Section 4.3.2 on this batch's outcome (outside the timed region)
-        counters = torch.zeros(5, dtype=torch.int64, device=dev)
-        B.dssd_tally(ctxs[0], None, acc, Bsz, k, None, counters)
-        cnt = counters.tolist()
-        cfg.update(drafted=cnt[1], accepted=cnt[2], wasted=cnt[3], acceptance_rate=cnt[2] / max(cnt[1], 1))
-        out.update(ms_per_step=dt / args.steps * 1e3)
-        cpu = None
-        if not args.no_cpu_baseline:
-            from oracle import eh_oracle as O
-            f64 = G.to_f64_numpy
-            W64, g64, b64 = f64(heads.W[fin]), f64(heads.gamma[fin]), f64(heads.beta[fin])
-            done, spent = 0, 0.0
-            for b0 in range(0, Bsz, 2):
-                f2, d2 = f64(case.f_final[b0:b0 + 2]), draft[b0:b0 + 2].cpu().numpy()
-                c0 = time.perf_counter()
-                O.dssd_verify(f2, d2, g64, b64, W64, None, 1e-5, True)
-                spent += time.perf_counter() - c0
-                done += 2 * (k + 1)
-                if spent > args.cpu_seconds:
-                    break
-            cpu = {"value": done / spent, "unit": "evals/s", "cores": oracle_threads(), "kind": "oracle",
-                   "sample": f"{done // (k + 1)} of the {Bsz} rows, two at a time ({done} evaluations, {spent:.1f} s; "
-                             "fp64 numpy, weights pre-widened)"}
-        for c in ctxs:
-            B.eh_destroy(c)
+        res = run_c4(args, torch, B, G, dev, args.steps, args.warmup, cpu_leg)
     else:
-        raise SystemExit("unknown workload: " + args.workload)
+        raise SystemExit("unknown workload: " + str(args.workload))
 
-    line = {"metric": "exit_head_evals_per_sec", "value": value, "unit": "evals/s", "n_gpus": 1,
-            "steps": args.steps, "warmup": args.warmup, "ms_per_step": out["ms_per_step"],
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
-            "data": "synthetic", "config": cfg, "roofline": roof, "cpu_baseline": cpu,
-            "setup_s": round(time.time() - t_setup, 1)}
+    line = {"metric": "exit_head_evals_per_sec", "value": res["value"], "unit": "evals/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": res["dtype"],
+            "data": "synthetic", "config": res["config"], "roofline": res["roofline"], "cpu_baseline": res["cpu_baseline"]}
+    line.update(extra)
+    line["setup_s"] = round(time.time() - t_setup, 1)
     print(json.dumps(line), flush=True)
 
 

@@ -16,8 +16,18 @@
  *     All work of a call is enqueued on it; calls do not synchronise the host.
  *   - A context serialises its calls: it owns one workspace, so two calls on
  *     the same context must be ordered on the same stream (or by the caller).
- *   - Row statistics of rows whose input contains NaN/Inf are NaN; such rows
- *     never pass the exit test.  This is defined behaviour, not an error.
+ *   - A row whose hidden state contains NaN or Inf has NaN statistics (every
+ *     logit is NaN) and argmax / token / target -1; it never passes the exit test
+ *     and so leaves at the last head.  This is defined behaviour, not an error.
+ *     Weights, gamma and beta must be finite.
+ *   - Calls with at most 16 rows (heads without a bias vector, d up to 2048 for
+ *     bf16 / 1024 for fp32) run a persistent kernel whose workgroups wait for each
+ *     other, one workgroup per compute unit: the stream must have the device to
+ *     itself while such a call runs (no other kernel holding compute units on
+ *     another stream or from another context).  eh_create checks that the grid
+ *     fits the empty device.  Every wait is bounded (eh_set_spin_limit); a call
+ *     that gives up sets a flag that eh_check reports and clears, rows it did not
+ *     finish read -1 / NaN, and the context stays usable.
  */
 #ifndef EH_H_
 #define EH_H_
@@ -156,12 +166,11 @@ eh_status eh_eval_heads_metrics(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval
  * exit_layer, token  device, indexed by row r, in-out (caller initialises to -1)
  * active_idx_out     device [n_rows]; may alias nothing else
  * n_active_out       device int32
- * tau_override       if not NaN, used instead of the context's tau[head]
  */
 eh_status eh_exit_decide(eh_ctx* ctx, int32_t head, const float* H, const int32_t* argmax,
                          const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows,
                          int32_t* exit_layer, int32_t* token, int32_t* active_idx_out,
-                         int32_t* n_active_out, float tau_override, void* stream);
+                         int32_t* n_active_out, void* stream);
 
 /*
  * Whole dynamic-exit cascade for n_rows independent rows (Section 3.4.2): heads
@@ -306,25 +315,22 @@ eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const i
 
 /*
  * Waits for `stream` and reports failures that only the device can see: the
- * persistent decode kernel (used for calls with at most 16 rows) waits for other
- * workgroups with a bounded spin, and a timeout there sets a sticky flag in the
- * context.  Returns EH_ERR_HIP if the flag is set (every later call on the
- * context is then a no-op on the device) or if the synchronisation fails.
+ * persistent kernel behind calls with at most 16 rows waits for other workgroups
+ * with a bounded spin, and a call that gave up sets a flag in the context.
+ * Returns EH_ERR_HIP if the flag is set (or if the synchronisation fails) and
+ * clears it: outputs of rows the failed call did not finish hold -1 (exit_layer,
+ * token, argmax) or NaN (H, lse), later calls run normally.
  */
 eh_status eh_check(eh_ctx* ctx, void* stream);
 
 /*
- * Diagnostics of the persistent decode kernel.  With enable != 0, later decode
- * launches make workgroup 0 record 16 wall-clock stamps (100 MHz ticks) per
- * head; host_out (host, nullable, n entries) first receives the stamps recorded
- * so far (the call synchronises the device): 16 per head, followed by four per
- * workgroup (streaming start/end, records sent, decision known) for the fourth
- * head of the launch.  Stamp slots of the per-head part:
- * 0/1 first streaming wave starts / finishes the head, 4..8 service wave: passes
- * the previous barrier, partial+ticket(+decision) done, live-row mask known,
- * LayerNorm of the next head done, passes this head's barrier.
+ * Bound of the persistent kernel's waits (Section 3.4.2 cascade with at most 16
+ * rows): the number of polls of another workgroup's record after which a workgroup
+ * gives up (each poll is followed by a short sleep; the default, 2^22, is several
+ * seconds).  polls >= 0; 0 makes a workgroup give up at its first unanswered poll,
+ * which is how the failure path is tested without hanging anything.
  */
-eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n);
+eh_status eh_set_spin_limit(eh_ctx* ctx, int32_t polls);
 
 /* Message describing the last error on this context (or, with ctx == NULL, the
  * last eh_create failure of the calling thread).  Never NULL.  The string is

@@ -8,7 +8,6 @@ load, importing this module raises.
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
 from typing import List, Optional, Sequence
 
@@ -24,7 +23,9 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
 
 # every symbol include/eh.h declares
 EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses",
-           "eh_calibrate", "eh_check", "eh_decode_trace", "eh_last_error", "eh_version"]
+           "eh_calibrate", "eh_check", "eh_set_spin_limit", "eh_last_error", "eh_version"]
+# the measurement entry points include/eh_probe.h declares
+PROBE_EXPORTS = ["eh_probe_read_weights", "eh_probe_mfma"]
 
 
 class EhError(RuntimeError):
@@ -54,7 +55,7 @@ def _load() -> C.CDLL:
     lib.eh_eval.argtypes = [vp, i32, vp, i64, vp, vp, i32, vp, vp, vp, vp]
     lib.eh_eval_heads.argtypes = [vp, i32, i32, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.eh_eval_heads_metrics.argtypes = [vp, i32, i32, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp]
-    lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, f32, vp]
+    lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.eh_cascade.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.dssd_verify.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.dssd_draft.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -62,13 +63,17 @@ def _load() -> C.CDLL:
     lib.eh_head_losses.argtypes = [vp, i32, vp, i64, vp, i64, vp, i32, C.c_float, vp, vp, vp, vp]
     lib.eh_calibrate.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double), i32, vp, vp, vp]
     lib.eh_check.argtypes = [vp, vp]
-    lib.eh_decode_trace.argtypes = [vp, i32, vp, i32]
-    lib.eh_decode_trace.restype = C.c_int
+    lib.eh_set_spin_limit.argtypes = [vp, i32]
+    lib.eh_probe_read_weights.argtypes = [vp, i32, i32, i32, i32, vp, C.POINTER(i64), vp]
+    lib.eh_probe_mfma.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
+    lib.eh_probe_read_weights.restype = C.c_int
+    lib.eh_probe_mfma.restype = C.c_int
     lib.eh_last_error.argtypes = [vp]
     lib.eh_last_error.restype = C.c_char_p
     lib.eh_version.argtypes = []
     lib.eh_version.restype = C.c_char_p
-    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses", "eh_check"):
+    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade",
+                 "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses", "eh_calibrate", "eh_check", "eh_set_spin_limit"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -132,7 +137,7 @@ def eh_create(W: Sequence[torch.Tensor], gamma: Sequence[torch.Tensor], beta: Se
                   gamma=arr(*[g.data_ptr() for g in gamma]),
                   beta=arr(*[b.data_ptr() for b in beta]),
                   bias=arr(*[b.data_ptr() for b in bias]) if bias is not None else None,
-                  tau=(C.c_float * n)(*[float(t) if math.isfinite(t) else 3.0e38 for t in tau]))
+                  tau=(C.c_float * n)(*[float(t) for t in tau]))
     torch.cuda.synchronize(dev)       # the library copies the weights synchronously
     out = C.c_void_p()
     st = lib.eh_create(C.byref(cfg), C.byref(out))
@@ -179,11 +184,10 @@ def eh_eval_heads_metrics(ctx: EhContext, head0: int, n_heads_eval: int, h_layer
 def eh_exit_decide(ctx: EhContext, head: int, H: torch.Tensor, argmax: torch.Tensor, n_rows: int,
                    exit_layer: torch.Tensor, token: torch.Tensor, active_idx_out: torch.Tensor,
                    n_active_out: torch.Tensor, row_idx: Optional[torch.Tensor] = None,
-                   n_rows_dev: Optional[torch.Tensor] = None, tau_override: float = float("nan"),
-                   stream=None) -> None:
+                   n_rows_dev: Optional[torch.Tensor] = None, stream=None) -> None:
     _check(lib.eh_exit_decide(ctx.handle, head, _ptr(H), _ptr(argmax), _ptr(row_idx), _ptr(n_rows_dev),
                               n_rows, _ptr(exit_layer), _ptr(token), _ptr(active_idx_out),
-                              _ptr(n_active_out), tau_override, _stream(stream)), ctx.handle)
+                              _ptr(n_active_out), _stream(stream)), ctx.handle)
 
 
 def eh_cascade(ctx: EhContext, h_layers: torch.Tensor, n_rows: int, exit_layer: torch.Tensor,
@@ -238,19 +242,29 @@ def eh_check(ctx: EhContext, stream=None) -> None:
     _check(lib.eh_check(ctx.handle, _stream(stream)), ctx.handle)
 
 
-def eh_decode_trace(ctx: EhContext, enable: bool, read: bool = False, per_workgroup: bool = False):
-    """Switch the decode kernel's per-head time stamps on/off; optionally return
-    what was recorded so far as a list of [n_heads][16] tick counts (100 MHz)."""
-    n = ctx.n_heads * 16
-    extra = 4 * 256 if per_workgroup else 0
-    buf = (C.c_uint64 * (n + extra))() if read else None
-    _check(lib.eh_decode_trace(ctx.handle, 1 if enable else 0, buf, (n + extra) if read else 0), ctx.handle)
-    if not read:
-        return None
-    heads = [[buf[l * 16 + k] for k in range(16)] for l in range(ctx.n_heads)]
-    if not per_workgroup:
-        return heads
-    return heads, [[buf[n + g * 4 + k] for k in range(4)] for g in range(256)]
+def eh_set_spin_limit(ctx: EhContext, polls: int) -> None:
+    """Bound of the persistent kernel's waits for other workgroups (polls before it gives up)."""
+    _check(lib.eh_set_spin_limit(ctx.handle, polls), ctx.handle)
+
+
+PROBE_READ_REGISTERS, PROBE_READ_LDS = 0, 1
+
+
+def eh_probe_read_weights(ctx: EhContext, how: int, per_head: bool, head0: int, n_heads_read: int,
+                          sink: torch.Tensor, stream=None) -> int:
+    """Plain read of the context's weights (measurement only); returns the bytes one call reads."""
+    n = C.c_int64(0)
+    _check(lib.eh_probe_read_weights(ctx.handle, how, 1 if per_head else 0, head0, n_heads_read, _ptr(sink),
+                                     C.byref(n), _stream(stream)), ctx.handle)
+    return n.value
+
+
+def eh_probe_mfma(ctx: EhContext, iters: int, random_operands: bool, sink: torch.Tensor, stream=None) -> float:
+    """Registers-only matrix instruction stream (measurement only); returns the flops of one call."""
+    f = C.c_double(0.0)
+    _check(lib.eh_probe_mfma(ctx.handle, iters, 1 if random_operands else 0, _ptr(sink), C.byref(f),
+                             _stream(stream)), ctx.handle)
+    return f.value
 
 
 def dssd_verify(ctx: EhContext, f_final: torch.Tensor, draft: torch.Tensor,

@@ -17,8 +17,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libeh.so")
-PROBE = os.path.join(PKG, "mfma_probe")   # stand-alone matrix-core rate probe (csrc/mfma_probe.hip)
-SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip", "eh_gemm32.hip", "eh_calib.hip"]
+SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip", "eh_gemm32.hip", "eh_calib.hip", "eh_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -61,9 +60,7 @@ def build(verbose: bool = True) -> str:
     asms = [os.path.join(objdir, s.replace(".hip", ".s")) for s in checked]
     cmds += [[hipcc, *compile_flags, "-S", "--cuda-device-only", "-I", os.path.join(ROOT, "include"),
               "-I", CSRC, os.path.join(CSRC, s), "-o", a] for s, a in zip(checked, asms)]
-    cmds.append([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-                 "-packed-fp32-ops", "-Wall", os.path.join(CSRC, "mfma_probe.hip"), "-o", PROBE])
-    with ThreadPoolExecutor(max_workers=min(6, len(cmds))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as ex:
         outs = list(ex.map(lambda c: _run(c, verbose), cmds))
     from . import check_gemm_asm
     for src, path in zip(checked, asms):

@@ -152,7 +152,10 @@ DecodeParams decode_base(eh_ctx* c) {
   p.records = c->dec_records; p.n_heads_alloc = c->n_heads;
   if (++c->dec_epoch == 0u) ++c->dec_epoch;  // never 0
   p.epoch = c->dec_epoch; p.status = c->dec_status;
+  p.spin_limit = c->spin_limit;
+#ifdef EH_DIAGNOSTICS
   p.trace = c->dec_trace_on ? c->dec_trace : nullptr;
+#endif
   return p;
 }
 
@@ -271,8 +274,10 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
       hipDeviceProp_t prop;
       if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return bail(e, "device properties");
       c->num_cu = prop.multiProcessorCount;
-      const char* env = getenv("EH_DISABLE_GEMM");   // diagnostics: force the simple streaming kernel
+#ifdef EH_DIAGNOSTICS
+      const char* env = getenv("EH_DISABLE_GEMM");   // force the simple streaming kernel
       c->use_gemm = !(env && env[0] == '1');
+#endif
     }
     if (c->decode_grid > 0) {
       const size_t nrec = 2 * np * c->decode_grid * 16 * 5;
@@ -425,7 +430,7 @@ eh_status eh_eval_heads_metrics(eh_ctx* ctx, int32_t head0, int32_t n_heads_eval
 eh_status eh_exit_decide(eh_ctx* ctx, int32_t head, const float* H, const int32_t* argmax,
                          const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows,
                          int32_t* exit_layer, int32_t* token, int32_t* active_idx_out,
-                         int32_t* n_active_out, float tau_override, void* stream) {
+                         int32_t* n_active_out, void* stream) {
   if (!ctx) return EH_ERR_NULL;
   if (head < 0 || head >= ctx->n_heads) return fail(ctx, EH_ERR_RANGE, "head out of range");
   if (n_rows < 0 || n_rows > ctx->max_rows) return fail(ctx, EH_ERR_WORKSPACE, "n_rows outside [0, max_rows]");
@@ -433,7 +438,7 @@ eh_status eh_exit_decide(eh_ctx* ctx, int32_t head, const float* H, const int32_
     return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
   if (active_idx_out == row_idx) return fail(ctx, EH_ERR_RANGE, "active_idx_out must not alias row_idx");
   DeviceGuard guard(ctx->device);
-  const float tau = std::isnan(tau_override) ? ctx->tau[head] : tau_override;
+  const float tau = ctx->tau[head];
   hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, H, argmax, row_idx,
                      n_rows_dev, n_rows, tau, head == ctx->n_heads - 1 ? 1 : 0, head, exit_layer, token,
                      active_idx_out, n_active_out, (float*)nullptr, (unsigned long long*)nullptr);
@@ -697,6 +702,7 @@ eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const i
   return EH_OK;
 }
 
+#ifdef EH_DIAGNOSTICS
 eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n) {
   if (!ctx) return EH_ERR_NULL;
   if (!ctx->dec_trace) return fail(ctx, EH_ERR_RANGE, "this context has no decode kernel");
@@ -710,6 +716,7 @@ eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32
   ctx->dec_trace_on = enable ? 1 : 0;
   return EH_OK;
 }
+#endif
 
 eh_status eh_check(eh_ctx* ctx, void* stream) {
   if (!ctx) return EH_ERR_NULL;
@@ -718,9 +725,21 @@ eh_status eh_check(eh_ctx* ctx, void* stream) {
   if (ctx->dec_status) {
     int flag = 0;
     EH_HIP(ctx, hipMemcpy(&flag, ctx->dec_status, sizeof(int), hipMemcpyDeviceToHost));
-    if (flag != 0)
-      return fail(ctx, EH_ERR_HIP, "decode kernel gave up waiting for another workgroup (context disabled)");
+    if (flag != 0) {
+      // report once and re-arm: the failed call's unfinished rows hold -1 / NaN
+      EH_HIP(ctx, hipMemset(ctx->dec_status, 0, sizeof(int)));
+      return fail(ctx, EH_ERR_HIP,
+                  "the persistent kernel gave up waiting for another workgroup: the stream did not have the "
+                  "device to itself (rows it did not finish hold -1 / NaN)");
+    }
   }
+  return EH_OK;
+}
+
+eh_status eh_set_spin_limit(eh_ctx* ctx, int32_t polls) {
+  if (!ctx) return EH_ERR_NULL;
+  if (polls < 0) return fail(ctx, EH_ERR_RANGE, "polls must be non-negative");
+  ctx->spin_limit = polls;
   return EH_OK;
 }
 

@@ -84,14 +84,16 @@ __global__ __launch_bounds__(1024) void calib_search_kernel(const uint32_t* __re
   const unsigned wg_first = (unsigned)((int64_t)blockIdx.x * blockDim.x);
   const int lane = threadIdx.x & 63;
   bool cand = false;
-  double sc = 0.0, n = 0.0;
+  // proportion of correct predictions among the tokens at least as confident as this one:
+  // the section's quotient as a correctly rounded double (IEEE division), compared with the
+  // levels as it stands, so that exactly p of q tokens meet a level written as the decimal p/q
+  double prop = 0.0;
   if (j < M) {
     const uint32_t k = keys[j];
     cand = k != 0u && (j == 0 || keys[j - 1] != k);
     if (cand) {
       const uint32_t total = prefix[M - 1];
-      sc = (double)(total - (j ? prefix[j - 1] : 0u));
-      n = (double)(M - j);
+      prop = (double)(total - (j ? prefix[j - 1] : 0u)) / (double)(M - j);
     }
   }
   bool any = false;
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(1024) void calib_search_kernel(const uint32_t* __re
     if (cur[e] <= wg_first) continue;  // uniform over the workgroup
     any = true;
     // lanes hold ascending positions: the first lane that qualifies is the wave's minimum
-    const unsigned long long q = __ballot(cand && sc >= eps.v[e] * n);
+    const unsigned long long q = __ballot(cand && prop >= eps.v[e]);
     if (lane == 0 && q) atomicMin(&wg_min[e], (unsigned)(j + __builtin_ctzll(q)));
   }
   if (!any) return;  // uniform

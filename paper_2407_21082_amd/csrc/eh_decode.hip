@@ -23,8 +23,11 @@
 //    decision for head l is still being formed and drop it if every row has
 //    exited.  Nothing of a dropped head is ever published.
 //
-// Every wait on another workgroup is bounded (kSpinLimit); a timeout sets the
-// context's sticky status word and makes every wave leave.
+// Every wait on another workgroup is bounded (DecodeParams::spin_limit polls); a
+// timeout sets the context's status word and makes every wave leave.  The kernel
+// assumes that all its workgroups are resident at once (one per compute unit):
+// the stream has to own the device while it runs.  Workgroup 0 presets the outputs
+// of the live rows to -1 / NaN, so a launch that gives up leaves defined values.
 #include "eh_internal.hpp"
 #include "eh_kernels.hpp"
 
@@ -36,7 +39,7 @@ constexpr int kStreamers = 8;
 constexpr int kThreads = (kStreamers + 2) * kWave;  // streamers + exchange wave + LayerNorm wave
 constexpr int kRing = 4;              // fragments per ring buffer (two buffers per streamer wave)
 constexpr int kMaxLag = 3;            // heads the streamers may be ahead of the oldest open exchange
-constexpr int kSpinLimit = 1 << 22;   // polls of a global flag before giving up
+constexpr int kSpinLimit = 1 << 22;   // polls of a flag of this workgroup (LDS) before giving up
 constexpr int kMaxChunksPerLane = 4;  // LayerNorm keeps a row in registers: d <= 4*64*EPL
 
 // LDS-only barrier: waits for this wave's LDS traffic, not for the global loads
@@ -190,6 +193,7 @@ __device__ __forceinline__ void ln_row_to_lds(const void* row, int d, int KS,
 // 4 exchange wave passes the previous barrier, 5 records of head l-1 sent,
 // 6 exchange and decision for head l-1 done, 7 LayerNorm(l+1) done (LayerNorm
 // wave), 8 exchange wave passes barrier l.
+#ifdef EH_DIAGNOSTICS
 __device__ __forceinline__ void stamp(const DecodeParams& p, int l, int slot, int lane) {
   if (p.trace && lane == 0) {
     if (blockIdx.x == 0) p.trace[l * 16 + slot] = wall_clock64();
@@ -198,6 +202,9 @@ __device__ __forceinline__ void stamp(const DecodeParams& p, int l, int slot, in
       p.trace[p.n_heads_alloc * 16 + blockIdx.x * 4 + (slot < 2 ? slot : slot - 3)] = wall_clock64();
   }
 }
+#else
+__device__ __forceinline__ void stamp(const DecodeParams&, int, int, int) {}
+#endif
 
 __device__ __forceinline__ unsigned long long poll_mask(const unsigned long long* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -573,14 +580,14 @@ struct Service {
           if (writer) {
             if (leaves) {
               p.exit_layer[n] = c;
-              p.token[n] = s.ib;
+              p.token[n] = stats_token(s);
             }
             if (p.H_out) p.H_out[(long long)c * p.n_rows + n] = H;
           }
         } else if (writer) {
           if (p.H) p.H[n] = H;
           if (p.lse) p.lse[n] = lse;
-          if (p.argmax) p.argmax[n] = s.ib;
+          if (p.argmax) p.argmax[n] = stats_token(s);
         }
       }
     }
@@ -659,7 +666,7 @@ struct Service {
           if (!done) __builtin_amdgcn_s_sleep(2);
         }
         if (done) break;
-        if (spins > kSpinLimit) { fail_all(par); break; }
+        if (spins >= p.spin_limit) { fail_all(par); break; }
       }
       if (lane == 0) *sm.live_word(par) = (int)live;
       stamp(p, l, 6, lane);
@@ -671,7 +678,7 @@ struct Service {
     sent = p.l1;
     for (int spins = 0; c < sent && live != 0u; ++spins) {
       if (pass()) { spins = 0; continue; }
-      if (spins > kSpinLimit) {
+      if (spins >= p.spin_limit) {
         if (lane == 0) atomicExch(p.status, 1);
         return;
       }
@@ -706,10 +713,28 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(const DecodeParams 
   sm.y_bytes = (unsigned)p.KS * kWave * 16;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in an SGPR
-  if (*(volatile int*)p.status != 0) return;  // a previous launch failed: do nothing
   // no live row at all (the count lives on the device: e.g. a drafting loop that has stopped):
   // every workgroup reads the same word, so the whole grid leaves together
   if (p.n_rows_dev && *p.n_rows_dev <= 0) return;
+  if (blockIdx.x == 0) {
+    // Preset the outputs of the live rows (workgroup 0 is also the one that writes the results,
+    // much later): whatever a launch that gives up has not finished reads -1 / NaN.
+    int n_live = p.n_rows;
+    if (p.n_rows_dev) n_live = min(*p.n_rows_dev, p.n_rows);
+    const int t = threadIdx.x;
+    if (p.decide) {
+      if (t < n_live) { p.exit_layer[t] = -1; p.token[t] = -1; }
+      if (p.H_out)
+        for (int i = t; i < p.n_heads * p.n_rows; i += kThreads) p.H_out[i] = NAN;
+    } else if (t < n_live) {
+      if (p.H) p.H[t] = NAN;
+      if (p.lse) p.lse[t] = NAN;
+      if (p.argmax) p.argmax[t] = -1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // landed before this workgroup's barrier below
+  }
+  // a launch that gave up has not been acknowledged yet (eh_check clears the flag): do nothing
+  if (*(volatile int*)p.status != 0) return;
   // zero both activation buffers (columns of rows that are not live stay zero)
   {
     lds_frag_t* y = sm.ybuf(0);

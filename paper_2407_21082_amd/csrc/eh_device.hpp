@@ -99,6 +99,11 @@ __device__ __forceinline__ void stats_init(Stats& s) {
   s.m = kNegBig; s.S = 0.f; s.U = 0.f; s.zb = -INFINITY; s.ib = 0x7fffffff;
 }
 
+// The index reported for a row: -1 if no logit ever compared greater than "nothing yet",
+// i.e. every logit of the row is NaN (a hidden state with a NaN or Inf in it).
+__device__ __forceinline__ int argmax_or_none(int ib) { return ib == 0x7fffffff ? -1 : ib; }
+__device__ __forceinline__ int stats_token(const Stats& s) { return argmax_or_none(s.ib); }
+
 // Associative merge: rescale both sides to the common maximum.
 __device__ __forceinline__ Stats stats_merge(const Stats& a, const Stats& b) {
   Stats r;

@@ -53,6 +53,7 @@ struct eh_ctx {
   unsigned long long* dec_records = nullptr;  // [2 rounds][n_heads][decode_grid][16][5] {tag, payload} words
   int* dec_status = nullptr;                // sticky device-side failure flag
   unsigned dec_epoch = 0;
+  int spin_limit = 1 << 22;                 // polls of another workgroup's record before giving up
   unsigned long long* dec_trace = nullptr;  // [n_heads][16] timestamps of workgroup 0 (diagnostics)
   int dec_trace_on = 0;
   std::vector<void*> allocs;
@@ -79,6 +80,7 @@ struct DecodeParams {
   int n_heads_alloc;            // head stride of the record array
   unsigned epoch;               // this launch's tag, never 0
   int* status;
+  int spin_limit;               // polls before a wait on another workgroup gives up
   float* H;
   float* lse;
   int* argmax;       // evaluation mode outputs [n_rows]
@@ -124,5 +126,17 @@ hipError_t calibrate_run(CalibScratch& sc, const float* H, const int* pred, cons
                          const double* eps, int n_eps, float* tau_out, long long* n_exit_out, hipStream_t s);
 // Enqueues the decode kernel.
 hipError_t decode_launch(const eh_ctx* ctx, const DecodeParams& p, hipStream_t s);
+
+}  // namespace eh
+
+#ifdef EH_DIAGNOSTICS
+// Diagnostics build only (-DEH_DIAGNOSTICS; not part of the library's interface): with
+// enable != 0 later decode launches make workgroup 0 record 16 wall-clock stamps (100 MHz
+// ticks) per head; host_out (host, nullable, n entries) first receives what was recorded
+// so far (synchronises the device).
+extern "C" eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n);
+#endif
+
+namespace eh {
 
 }  // namespace eh

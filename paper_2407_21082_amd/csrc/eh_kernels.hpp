@@ -422,7 +422,7 @@ static __global__ __launch_bounds__(64) void finalize_kernel(const Stats* __rest
     stats_finalize(s, h, l);
     if (H) H[o] = h;
     if (lse) lse[o] = l;
-    if (argmax) argmax[o] = s.ib;
+    if (argmax) argmax[o] = stats_token(s);
   }
 }
 
@@ -459,7 +459,7 @@ static __global__ __launch_bounds__(64) void finalize_metrics_kernel(
     stats_finalize(s, h, l);
     if (H) H[o] = h;
     if (lse) lse[o] = l;
-    if (argmax) argmax[o] = s.ib;
+    if (argmax) argmax[o] = stats_token(s);
     const float p1 = 1.0f / s.S;  // NaN statistics give NaN metrics
     if (max_prob) max_prob[o] = p1;
     if (margin) margin[o] = p1 * (1.0f - fast_exp2((z2 - s.zb) * kLog2e));
@@ -509,7 +509,7 @@ __global__ __launch_bounds__(kLnThreads) void cascade_post_kernel(
       if (n_evals) atomicAdd(n_evals, 1ull);
       if (is_last || H < tau) {  // NaN never passes the test
         exit_layer[r] = head;
-        token[r] = s.ib;
+        token[r] = stats_token(s);
       } else {
         pos = atomicAdd(n_active_next, 1);
         active_next[pos] = r;
@@ -618,8 +618,8 @@ static __global__ __launch_bounds__(256) void verify_post_kernel(
       if (oz > zb || (oz == zb && oi < ib)) { zb = oz; ib = oi; }
     }
     if (lane == 0) {
-      verify_tgt[j] = ib;
-      if (target) target[p] = ib;
+      verify_tgt[j] = argmax_or_none(ib);
+      if (target) target[p] = argmax_or_none(ib);
     }
   }
   __syncthreads();
@@ -654,6 +654,11 @@ static __global__ void draft_step_kernel(int* __restrict__ state, const int* __r
                                          int* __restrict__ draft, int* __restrict__ exit_layers) {
   if (state[0] == 0) return;
   const int e = *exit_layer, tk = *token;
+  if (e < 0) {  // the cascade of this position gave up (reported by eh_check): stop, append nothing
+    state[0] = 0;
+    state[2] = 3;
+    return;
+  }
   if (e >= last_head) {  // no exit head was confident: the model's own prediction is the fallback
     state[0] = 0;
     state[2] = 2;

@@ -13,18 +13,26 @@ from workloads import generators as G
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "eh.h")).read()
+def _declared(header="eh.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(eh_[a-z_]+|dssd_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(eh_[a-z0-9_]+|dssd_[a-z_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():
     names = _declared()
     assert set(names) == set(B.EXPORTS)
-    for n in names:
+    probes = _declared("eh_probe.h")
+    assert set(probes) == set(B.PROBE_EXPORTS)
+    for n in names + probes:
         assert hasattr(B.lib, n), f"libeh.so does not export {n}"
     assert "gfx950" in B.eh_version()
+    # nothing else with the library's prefixes is exported (diagnostic hooks stay out of the default build)
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", B.LIB_PATH], stdout=subprocess.PIPE, text=True, check=True).stdout
+    exported = {l.split()[-1] for l in out.splitlines() if " T " in l}
+    ours = {n for n in exported if n.startswith(("eh_", "dssd_"))}
+    assert ours == set(names) | set(probes), ours ^ (set(names) | set(probes))
 
 
 def _cfg(**kw):

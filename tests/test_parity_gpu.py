@@ -221,9 +221,11 @@ def test_c0_tiny_full(B):
 
 
 # --------------------------------------------------------------- config 1
+@pytest.mark.timeout(900)
 def test_c1_decode_steps(B):
-    """Batch-1 cascades over 2048 seeded decode steps; the oracle checks a
-    sample of 48 steps in full (every head), plus range properties on all."""
+    """Batch-1 cascades over 2048 seeded decode steps, every one of them checked against the
+    oracle (every head on every step: exit layer, token, and the entropy of each head up to
+    the exit)."""
     w = G.CONFIGS["c1_decode"]
     heads = G.make_heads(w, DEV)
     steps = w.steps
@@ -239,13 +241,10 @@ def test_c1_decode_steps(B):
     torch.cuda.synchronize()
     assert ((ex >= 0) & (ex < w.n_heads)).all() and ((tok >= 0) & (tok < w.V)).all()
     assert int(nev.item()) == int((ex.long() + 1).sum().item())
-    sample = torch.arange(0, steps, steps // 48, device=DEV)[:48]
-    full = P.oracle_all_heads(heads, hid.h, True, rows=sample)
+    full = P.oracle_all_heads(heads, hid.h, True)
     log = []
-    flips = P.compare_cascade("c1", ex[sample], tok[sample], Hout[sample].T.contiguous(), full[0],
-                              full[2], full[3], tau, log)
-    print(f"c1: mean evals/step {nev.item() / steps:.2f}; sample exits {ex[sample].tolist()}; "
-          f"flips {flips}; log {log}")
+    flips = P.compare_cascade("c1", ex, tok, Hout.T.contiguous(), full[0], full[2], full[3], tau, log)
+    print(f"c1: mean evals/step {nev.item() / steps:.2f}; all {steps} steps checked; flips {flips}; log {log}")
     assert len(set(ex.tolist())) >= 8          # exits are spread over many depths
     B.eh_destroy(ctx)
 
@@ -281,6 +280,11 @@ def test_c2_batched_calibration(B):
     for l in range(w.n_heads):
         assert torch.equal(Hb[l], per_head[l][0]) and torch.equal(Lb[l], per_head[l][1])
         assert torch.equal(Ab[l], per_head[l][2])
+    for _ in range(3):                                        # and the same bits on every repeat
+        Hr, Lr, Ar = torch.zeros_like(Hb), torch.zeros_like(Lb), torch.zeros_like(Ab)
+        B.eh_eval_heads(ctx, 0, w.n_heads, hid.h, R, Hr, Lr, Ar)
+        torch.cuda.synchronize()
+        assert torch.equal(Hr, Hb) and torch.equal(Lr, Lb) and torch.equal(Ar, Ab)
     Pm = torch.full((w.n_heads, R), float("nan"), device=DEV)
     Mg = torch.full((w.n_heads, R), float("nan"), device=DEV)
     H2, L2, A2 = torch.zeros_like(Hb), torch.zeros_like(Lb), torch.zeros_like(Ab)
@@ -337,6 +341,16 @@ def test_c3_dynamic_exit_with_compaction(B, big):
     exl = ex.cpu().numpy()
     frac = [(exl < l).mean() for l in (8, 16, 24)]
     print(f"c3 exited fraction by layers 8/16/24: {frac}; evals {nev.item()}; log {log}")
+    # run to run the results are the same bits (the next head's row list is filled in arrival order,
+    # which must not show in any output)
+    for _ in range(3):
+        ex2 = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+        tok2 = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+        Hout2 = torch.zeros((w.n_heads, R), device=DEV)
+        B.eh_cascade(ctx, hid.h, R, ex2, tok2, Hout2, None)
+        torch.cuda.synchronize()
+        assert torch.equal(ex, ex2) and torch.equal(tok, tok2)
+        assert torch.equal(Hout.view(torch.int32), Hout2.view(torch.int32))
     assert abs(frac[0] - 0.10) < 0.05 and abs(frac[1] - 0.40) < 0.05 and abs(frac[2] - 0.70) < 0.05
     big["tau3"] = tau
     B.eh_destroy(ctx)
@@ -448,7 +462,7 @@ def test_calibrate_large_set_properties(B, small_ctx):
     cnt = np.bincount(inv, minlength=len(vals)).cumsum()                   # tokens with H <= value
     cor = np.bincount(inv, weights=t[ok], minlength=len(vals)).cumsum()    # correct ones among them
     for i, e in enumerate(EPS_SWEEP):
-        good = cor >= e * cnt
+        good = cor / cnt >= e                                              # the section's quotient, in double
         if not good.any():
             assert np.isneginf(tau[i]) and n[i] == 0
             continue
@@ -458,9 +472,6 @@ def test_calibrate_large_set_properties(B, small_ctx):
 
 
 # --------------------------------------------------------------- the other two confidence metrics
-               # accumulation error well under 8e-4 at these sizes
-
-
 @pytest.mark.parametrize("V,d,R", [(1000, 128, 5), (777, 512, 37), (3000, 256, 161), (1500, 160, 700), (1, 64, 3)])
 def test_eval_heads_metrics(B, V, d, R):
     w = G.Workload("metrics", d=d, V=V, n_heads=3, rows=R, dtype="bf16", seed=V + d + R)
