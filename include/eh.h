@@ -116,6 +116,26 @@ eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride
                   float* H, float* lse, int32_t* argmax, void* stream);
 
 /*
+ * eh_eval for callers that cannot allocate or free device memory around the call: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments, same results (the same kernels, at any row count: this call does not use the
+ * persistent kernel), but the call's workspace -- the normalised activations and the partial
+ * statistics of the workgroups -- is a 16 MiB array that is part of the library's image on
+ * each GPU, not memory of the context, and the call performs no allocation of any kind.
+ *
+ * n_rows        0 <= n_rows, not bounded by max_rows but by the array: EH_ERR_WORKSPACE if
+ *               (ceil32(n_rows) / 16 + 32) * ceil(d / k) KiB + 10 KiB * ceil32(n_rows)
+ *               exceeds 16 MiB (k = 32 for bf16, 16 for fp32): up to 1024 rows at d = 2048 bf16, 896 at
+ *               d = 2560.
+ * Every call on a GPU, from any context, shares that GPU's array and finds the last call's
+ * contents in it (nothing in it has to start at zero): calls that overlap in time on one GPU
+ * race, so order them on one stream or by events.
+ */
+eh_status eh_eval_noalloc(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride,
+                          const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows,
+                          float* H, float* lse, int32_t* argmax, void* stream);
+
+/*
  * Several heads on the same positions in one call (Section 3.4.1, "Calibration of
  * Confidence Thresholds": the confidence of every head is needed at every token of
  * the calibration set).  Same results as eh_eval for heads head0 .. head0 +

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
                 4: "EH_ERR_RANGE", 5: "EH_ERR_HIP", 6: "EH_ERR_WORKSPACE"}
 
 # every symbol include/eh.h declares
-EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses",
+EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_noalloc", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses",
            "eh_calibrate", "eh_check", "eh_set_spin_limit", "eh_last_error", "eh_version"]
 # the measurement entry points include/eh_probe.h declares
 PROBE_EXPORTS = ["eh_probe_read_weights", "eh_probe_mfma"]
@@ -53,6 +53,7 @@ def _load() -> C.CDLL:
     lib.eh_create.argtypes = [C.POINTER(_Config), C.POINTER(vp)]
     lib.eh_destroy.argtypes = [vp]
     lib.eh_eval.argtypes = [vp, i32, vp, i64, vp, vp, i32, vp, vp, vp, vp]
+    lib.eh_eval_noalloc.argtypes = [vp, i32, vp, i64, vp, vp, i32, vp, vp, vp, vp]
     lib.eh_eval_heads.argtypes = [vp, i32, i32, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.eh_eval_heads_metrics.argtypes = [vp, i32, i32, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp]
     lib.eh_exit_decide.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
@@ -72,7 +73,7 @@ def _load() -> C.CDLL:
     lib.eh_last_error.restype = C.c_char_p
     lib.eh_version.argtypes = []
     lib.eh_version.restype = C.c_char_p
-    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade",
+    for name in ("eh_create", "eh_destroy", "eh_eval", "eh_eval_noalloc", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade",
                  "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses", "eh_calibrate", "eh_check", "eh_set_spin_limit"):
         getattr(lib, name).restype = C.c_int
     return lib
@@ -159,6 +160,16 @@ def eh_eval(ctx: EhContext, head: int, h: torch.Tensor, n_rows: int, H: Optional
     stride = h.stride(-2) if row_stride is None and h.dim() >= 2 else (row_stride or ctx.d)
     _check(lib.eh_eval(ctx.handle, head, _ptr(h), stride, _ptr(row_idx), _ptr(n_rows_dev), n_rows,
                        _ptr(H), _ptr(lse), _ptr(argmax), _stream(stream)), ctx.handle)
+
+
+def eh_eval_noalloc(ctx: EhContext, head: int, h: torch.Tensor, n_rows: int, H: Optional[torch.Tensor],
+                    lse: Optional[torch.Tensor], argmax: Optional[torch.Tensor],
+                    row_idx: Optional[torch.Tensor] = None, n_rows_dev: Optional[torch.Tensor] = None,
+                    row_stride: Optional[int] = None, stream=None) -> None:
+    """eh_eval on the library's static workspace (no allocation of any kind in the call)."""
+    stride = h.stride(-2) if row_stride is None and h.dim() >= 2 else (row_stride or ctx.d)
+    _check(lib.eh_eval_noalloc(ctx.handle, head, _ptr(h), stride, _ptr(row_idx), _ptr(n_rows_dev), n_rows,
+                               _ptr(H), _ptr(lse), _ptr(argmax), _stream(stream)), ctx.handle)
 
 
 def eh_eval_heads(ctx: EhContext, head0: int, n_heads_eval: int, h_layers: torch.Tensor, n_rows: int,

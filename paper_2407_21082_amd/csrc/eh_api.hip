@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -16,9 +17,35 @@
 
 using namespace eh;
 
+// Workspace of eh_eval_noalloc: one array per GPU, part of the library's image on that GPU
+// from the moment the library is loaded there until the process ends.  Host code never uses
+// this name as an address: eh_create looks the array's device address up once per device
+// (scratch_address) and everything is done through that pointer.
+constexpr size_t kNoAllocScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
 namespace {
 
 thread_local std::string g_create_error = "";
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on `device`, which must be the current device.
+hipError_t scratch_address(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 constexpr int kMaxNB = 10;           // token blocks (of 16) one stream launch covers
 constexpr int kStreamGrid = 512;     // workgroups of the stream kernel (2 per CU)
@@ -74,13 +101,13 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 template <typename DT, bool AO>
 void launch_stream(int nbc, const eh_ctx* c, int head, int nb0, const int* n_rows_dev, int n_rows,
-                   int R_pad, hipStream_t s) {
+                   int R_pad, hipStream_t s, const frag_t* yf, Stats* partials) {
   const frag_t* Wf = c->Wf[head];
   const float* bias = c->bias.empty() ? nullptr : c->bias[head];
   dim3 g(kStreamGrid), b(256);
 #define EH_LAUNCH(NB)                                                                           \
-  hipLaunchKernelGGL((stream_kernel<DT, NB, AO>), g, b, 0, s, Wf, c->yf, bias, c->VT, c->KS, c->V, \
-                     nb0, n_rows_dev, n_rows, R_pad, c->partials)
+  hipLaunchKernelGGL((stream_kernel<DT, NB, AO>), g, b, 0, s, Wf, yf, bias, c->VT, c->KS, c->V, \
+                     nb0, n_rows_dev, n_rows, R_pad, partials)
   if (nbc <= 1) EH_LAUNCH(1);
   else if (nbc <= 2) EH_LAUNCH(2);
   else if (nbc <= 4) EH_LAUNCH(4);
@@ -91,10 +118,14 @@ void launch_stream(int nbc, const eh_ctx* c, int head, int nb0, const int* n_row
 }
 
 // LayerNorm + projection + statistics for one head; results to (H, lse, argmax).
+// yf / partials: the activation workspace and the per-workgroup partial statistics to use
+// (the context's own, or another buffer of at least the same layout for n_rows rows).
 template <bool AO>
 eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const int* row_idx,
                    const int* n_rows_dev, int n_rows, float* H, float* lse, int* argmax,
-                   hipStream_t s) {
+                   hipStream_t s, frag_t* yf = nullptr, Stats* partials = nullptr) {
+  if (!yf) yf = c->yf;
+  if (!partials) partials = c->partials;
   const bool bf = c->dtype == EH_BF16;
   // heads without bias go to the batched kernels: bf16 in blocks of 32 rows
   // (32x32x16 matrix instructions), f32 in blocks of 16
@@ -105,28 +136,28 @@ eh_status run_head(eh_ctx* c, int head, const void* h, int64_t row_stride, const
     dim3 g(R_pad), b(kLnThreads);
     if (bf && RB == 32)
       hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 32>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
-                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
+                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, yf);
     else if (bf)
       hipLaunchKernelGGL((ln_pack_kernel<DtBf16, 16>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
-                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
+                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, yf);
     else
       hipLaunchKernelGGL((ln_pack_kernel<DtF32, 16>), g, b, 0, s, h, row_stride, row_idx, n_rows_dev,
-                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, c->yf);
+                         n_rows, R_pad, c->d, c->KS, c->gamma[head], c->beta[head], c->eps, yf);
   }
   int n_parts = kStreamGrid;
   if (batched && bf) {
-    EH_HIP(c, gemm32_launch(c, head, n_rows_dev, n_rows, AO, c->yf, c->partials, nullptr, &n_parts, s));
+    EH_HIP(c, gemm32_launch(c, head, n_rows_dev, n_rows, AO, yf, partials, nullptr, &n_parts, s));
   } else if (batched) {
-    EH_HIP(c, gemm_launch(c, head, n_rows_dev, n_rows, AO, c->yf, c->partials, &n_parts, s));
+    EH_HIP(c, gemm_launch(c, head, n_rows_dev, n_rows, AO, yf, partials, &n_parts, s));
   } else {
     const int NBtot = R_pad / 16;
     for (int nb0 = 0; nb0 < NBtot; nb0 += kMaxNB) {
       const int nbc = std::min(kMaxNB, NBtot - nb0);
-      if (bf) launch_stream<DtBf16, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
-      else launch_stream<DtF32, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s);
+      if (bf) launch_stream<DtBf16, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s, yf, partials);
+      else launch_stream<DtF32, AO>(nbc, c, head, nb0, n_rows_dev, n_rows, R_pad, s, yf, partials);
     }
   }
-  hipLaunchKernelGGL(finalize_kernel, dim3(n_rows), dim3(64), 0, s, c->partials, n_parts, R_pad,
+  hipLaunchKernelGGL(finalize_kernel, dim3(n_rows), dim3(64), 0, s, partials, n_parts, R_pad,
                      n_rows_dev, n_rows, AO ? nullptr : H, AO ? nullptr : lse, argmax, (int64_t)0, (int64_t)0);
   EH_HIP(c, hipGetLastError());
   return EH_OK;
@@ -213,6 +244,7 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
     return fail(nullptr, EH_ERR_HIP, msg);
   };
   hipError_t e;
+  if ((e = scratch_address(c->device, &c->static_scratch)) != hipSuccess) return bail(e, "hipGetSymbolAddress(scratch)");
   const size_t wf_frags = (size_t)c->VT * c->KS * kWave;
   const int Vp = c->VT * 16;
   c->Wf.resize(c->n_heads); c->gamma.resize(c->n_heads); c->beta.resize(c->n_heads);
@@ -326,6 +358,36 @@ eh_status eh_eval(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride
   }
   return run_head<false>(ctx, head, h, h_row_stride, row_idx, n_rows_dev, n_rows, H, lse, argmax,
                          (hipStream_t)stream);
+}
+
+eh_status eh_eval_noalloc(eh_ctx* ctx, int32_t head, const void* h, int64_t h_row_stride,
+                          const int32_t* row_idx, const int32_t* n_rows_dev, int32_t n_rows, float* H,
+                          float* lse, int32_t* argmax, void* stream) {
+  if (!ctx) return EH_ERR_NULL;
+  if (head < 0 || head >= ctx->n_heads) return fail(ctx, EH_ERR_RANGE, "head out of range");
+  if (n_rows < 0) return fail(ctx, EH_ERR_SHAPE, "n_rows is negative");
+  if (n_rows == 0) return EH_OK;
+  if (!h) return fail(ctx, EH_ERR_NULL, "h is NULL");
+  if (h_row_stride < ctx->d) return fail(ctx, EH_ERR_SHAPE, "row stride smaller than d");
+  const int esz = ctx->dtype == EH_BF16 ? 2 : 4;
+  if (!aligned16(h) || (h_row_stride * esz) % 16 != 0)
+    return fail(ctx, EH_ERR_SHAPE, "hidden rows must be 16-byte aligned");
+  // layout of the static array for this call: activations of the rows (padded to blocks of 32,
+  // plus the 32 blocks of 16 the batched kernels may read beyond them), then one partial
+  // statistics record per (workgroup, row)
+  const size_t R_pad = ((size_t)n_rows + 31) & ~(size_t)31;
+  const size_t y_bytes = (R_pad / 16 + 32) * (size_t)ctx->KS * kWave * sizeof(frag_t);
+  const size_t part_off = (y_bytes + 255) & ~(size_t)255;
+  const size_t need = part_off + (size_t)kStreamGrid * R_pad * sizeof(Stats);
+  if ((size_t)n_rows > ((size_t)1 << 20) || need > kNoAllocScratchBytes)
+    return fail(ctx, EH_ERR_WORKSPACE,
+                "n_rows rows of d elements need " + std::to_string(need) + " bytes of workspace; the static one holds " +
+                    std::to_string(kNoAllocScratchBytes));
+  if (!ctx->static_scratch) return fail(ctx, EH_ERR_HIP, "the static workspace has no device address");
+  DeviceGuard guard(ctx->device);
+  unsigned char* base = (unsigned char*)ctx->static_scratch;
+  return run_head<false>(ctx, head, h, h_row_stride, row_idx, n_rows_dev, n_rows, H, lse, argmax,
+                         (hipStream_t)stream, (frag_t*)base, (Stats*)(base + part_off));
 }
 
 namespace {

@@ -56,6 +56,7 @@ struct eh_ctx {
   int spin_limit = 1 << 22;                 // polls of another workgroup's record before giving up
   unsigned long long* dec_trace = nullptr;  // [n_heads][16] timestamps of workgroup 0 (diagnostics)
   int dec_trace_on = 0;
+  void* static_scratch = nullptr;  // device address of the library's static workspace on this device
   std::vector<void*> allocs;
   std::string err = "";
 };
