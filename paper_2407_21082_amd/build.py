@@ -22,7 +22,7 @@ SOURCES = ["eh_api.hip", "eh_decode.hip", "eh_gemm.hip", "eh_gemm32.hip", "eh_ca
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
+    "-fno-gpu-rdc", "-Wall", "-Wno-unused-function", *([f"-D{x}" for x in os.environ.get("EH_DEFINES", "").split()]),
 ]
 
 

@@ -175,6 +175,23 @@ eh_status check_rows(eh_ctx* ctx, const void* h, int64_t row_stride, int n_rows)
 
 // Rows <= 16 go through the persistent decode kernel when the shape fits it.
 bool use_decode(const eh_ctx* c, int n_rows) { return c->decode_grid > 0 && n_rows <= 16; }
+// 17 .. 256 rows of a cascade or a verification go through the persistent rows kernel.
+bool use_rows(const eh_ctx* c, int64_t n_rows) {
+  return c->rows_grid > 0 && c->use_gemm && n_rows > 16 && n_rows <= kRowsMax && n_rows <= c->max_rows;
+}
+
+RowsParams rows_base(eh_ctx* c, int n_rows) {
+  RowsParams p{};
+  p.Wf = c->d_Wf; p.gamma = c->d_gamma; p.beta = c->d_beta; p.tau = c->d_tau;
+  p.n_rows = n_rows; p.n_heads = c->n_heads;
+  p.V = c->V; p.d = c->d; p.KS = c->KS; p.VT16 = c->VT; p.eps = c->eps;
+  p.n_stream = c->rows_grid - rows_service_workgroups();
+  p.spin_limit = c->spin_limit;
+  p.ctl = c->rows_ctl; p.y = c->rows_y; p.y_stride = c->rows_y_stride;
+  p.partials = c->rows_partials; p.R_pad = (n_rows + 31) & ~31;
+  p.status = c->dec_status;
+  return p;
+}
 
 DecodeParams decode_base(eh_ctx* c) {
   DecodeParams p{};
@@ -302,6 +319,20 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
       if ((e = hipMemcpy(c->d_bias, c->bias.data(), np * sizeof(void*), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "copy tables");
     }
     if ((e = decode_prepare(c)) != hipSuccess) return bail(e, "decode_prepare");
+    if ((e = rows_prepare(c)) != hipSuccess) return bail(e, "rows_prepare");
+    if (c->rows_grid > 0 && c->max_rows > 16) {
+      // workspace of the persistent kernel for 17 .. 256 rows: one activation buffer per head (plus
+      // the blocks a wave may read past the last live one), two sets of partial statistics
+      const int rmax = std::min(c->R_pad_max, kRowsMax);
+      c->rows_y_stride = (long long)(rmax / 16 + 32) * c->KS * kWave;
+      c->rows_ctl_ints = rows_control_ints(c->n_heads);
+      if ((e = dev_alloc(c, &c->rows_y, (size_t)c->n_heads * c->rows_y_stride)) != hipSuccess) return bail(e, "hipMalloc(rows)");
+      if ((e = hipMemset(c->rows_y, 0, (size_t)c->n_heads * c->rows_y_stride * sizeof(frag_t))) != hipSuccess) return bail(e, "memset rows");
+      if ((e = dev_alloc(c, &c->rows_partials, (size_t)2 * c->rows_grid * rmax)) != hipSuccess) return bail(e, "hipMalloc(rows)");
+      if ((e = dev_alloc(c, &c->rows_ctl, (size_t)c->rows_ctl_ints)) != hipSuccess) return bail(e, "hipMalloc(rows)");
+    } else {
+      c->rows_grid = 0;
+    }
     {
       hipDeviceProp_t prop;
       if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return bail(e, "device properties");
@@ -311,12 +342,13 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
       c->use_gemm = !(env && env[0] == '1');
 #endif
     }
+    // the status word both persistent kernels report a given-up wait in (read by eh_check)
+    if ((e = dev_alloc(c, &c->dec_status, (size_t)4)) != hipSuccess) return bail(e, "hipMalloc(status)");
+    if ((e = hipMemset(c->dec_status, 0, 16)) != hipSuccess) return bail(e, "memset");
     if (c->decode_grid > 0) {
       const size_t nrec = 2 * np * c->decode_grid * 16 * 5;
       if ((e = dev_alloc(c, &c->dec_records, nrec)) != hipSuccess) return bail(e, "hipMalloc(decode)");
-      if ((e = dev_alloc(c, &c->dec_status, (size_t)4)) != hipSuccess) return bail(e, "hipMalloc(decode)");
       if ((e = hipMemset(c->dec_records, 0, nrec * sizeof(unsigned long long))) != hipSuccess) return bail(e, "memset");
-      if ((e = hipMemset(c->dec_status, 0, 16)) != hipSuccess) return bail(e, "memset");
       if ((e = dev_alloc(c, &c->dec_trace, np * 16 + 4 * (size_t)c->decode_grid)) != hipSuccess) return bail(e, "hipMalloc(decode)");
       if ((e = hipMemset(c->dec_trace, 0, (np * 16 + 4 * (size_t)c->decode_grid) * sizeof(unsigned long long))) != hipSuccess) return bail(e, "memset");
     }
@@ -530,6 +562,16 @@ eh_status eh_cascade(eh_ctx* ctx, const void* h_layers, int64_t layer_stride, in
     EH_HIP(ctx, decode_launch(ctx, p, s));
     return EH_OK;
   }
+  if (use_rows(ctx, n_rows)) {
+    // one persistent launch for the whole cascade
+    RowsParams p = rows_base(ctx, n_rows);
+    p.h = h_layers; p.layer_stride = layer_stride; p.row_stride = row_stride;
+    p.l0 = 0; p.l1 = ctx->n_heads; p.mode = 0; p.argmax_only = 0;
+    p.exit_layer = exit_layer; p.token = token; p.H_out = H_out;
+    p.n_evals = (unsigned long long*)n_evals_out;
+    EH_HIP(ctx, rows_launch(ctx, p, s));
+    return EH_OK;
+  }
   if (H_out) {
     const int64_t n = (int64_t)ctx->n_heads * n_rows;
     hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, H_out, n, NAN);
@@ -609,6 +651,17 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, co
   DeviceGuard guard(ctx->device);
   hipStream_t s = (hipStream_t)stream;
   const bool bf = ctx->dtype == EH_BF16;
+  if (use_rows(ctx, rows)) {
+    // one persistent launch: LayerNorm, argmax-only projection, merge and prefix walk
+    RowsParams p = rows_base(ctx, (int)rows);
+    p.h = f_final; p.layer_stride = 0; p.row_stride = ctx->d;
+    p.l0 = ctx->n_heads - 1; p.l1 = ctx->n_heads; p.mode = 1; p.argmax_only = 1;
+    p.n_stream = ctx->rows_grid;  // a verification has no serving workgroups: all stream, then all merge
+    p.draft = draft; p.draft_len = draft_len; p.B = B; p.k = k;
+    p.accepted = accepted; p.next_token = next_token; p.target = target;
+    EH_HIP(ctx, rows_launch(ctx, p, s));
+    return EH_OK;
+  }
   if (ctx->bias.empty() && ctx->use_gemm && rows > 16 && (size_t)(k + 1) * sizeof(int) <= 48 * 1024) {
     // three launches: LayerNorm, argmax-only projection, then one kernel that merges the
     // partial argmaxes of a row's k+1 positions and walks the prefix

@@ -653,6 +653,505 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_kl_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Persistent kernel for 17 .. 256 rows (arXiv 2407.21082: the dynamic-exit cascade of Section
+// 3.4.2 on a batch of decode rows, and the verification pass of Section 4.3.1).  At these row
+// counts a head is a pure weight stream (at most 256 flop per byte), so what matters is that
+// the stream never stops: one launch runs every head, and nothing in it waits for a decision.
+//
+//  * Workgroups 0 .. n_stream-1 stream: each owns a slice of the vocabulary of every head and
+//    runs pass32 on it, head after head.  Before head l it only checks that the activations of
+//    head l are there (a counter that is long complete by then) and reads how many columns they
+//    have; behind it, it leaves its partial statistics and bumps a counter.
+//  * The last workgroups serve: wave by wave they own rows.  For head l they wait for all
+//    streaming workgroups' partial statistics, merge those of their rows, apply the exit test
+//    (strict H < tau, the last head always answers), publish which rows go on, and then write
+//    the LayerNorm of the survivors for head l+2, compacted (column = rank among the rows
+//    alive after head l).  Head l+1 is already being streamed at that time on the rows that
+//    were alive after head l-1: a row that leaves at head l wastes a column there, nothing else.
+//  * Hand-overs use no fence (a device-scope fence writes back and invalidates the whole L2 of
+//    a die: 50 us per head when every wave issues a few).  Every head has its own activation
+//    buffer, written once per launch with device-coherent stores before the counter that
+//    announces it is bumped, so no cache can hold an older copy of a line when it is first
+//    read; partial statistics (two buffers, reused) are written with device-coherent stores and
+//    read with device-coherent loads; counters and masks are device-scope atomics.  A writer
+//    waits for its stores to be acknowledged before it bumps the counter.
+//  * Every wait is bounded (spin_limit polls); a time-out sets the context's status word and an
+//    abort word that ends every other wait.
+//
+// All workgroups must be resident at once (grid = compute units, one workgroup each).
+// ---------------------------------------------------------------------------------------------
+// All stores of this wave have been acknowledged (vector stores count in vmcnt).
+#define EH_STORES_DONE() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
+// Nothing below may be moved above a wait that has just returned.
+#define EH_AFTER_WAIT() asm volatile("" ::: "memory")
+constexpr int kRowsServiceWgs = 12;  // 3144 16-row tiles over 244 streaming workgroups: still 13 at most each
+constexpr int kRowsWords = kRowsMax / 32;
+
+// control block (ints): [0] abort; then per head (relative index j = l - l0, with two spare):
+// ready[j] (LayerNorm contributions for head j), done[j] (streaming workgroups finished),
+// decided[j] (service waves that published head j's decisions), alive[j][8] (rows entering head j);
+// then 256 words for the merged targets of a verification
+__host__ __device__ inline int rows_ctl_ints(int n_heads) { return 16 + (n_heads + 2) * (3 + kRowsWords) + kRowsMax; }
+struct RowsCtl {
+  int* base;
+  int nh2;  // n_heads + 2
+  __device__ __forceinline__ int* abort_word() const { return base; }
+  __device__ __forceinline__ int* ready(int j) const { return base + 16 + j; }
+  __device__ __forceinline__ int* done(int j) const { return base + 16 + nh2 + j; }
+  __device__ __forceinline__ int* decided(int j) const { return base + 16 + 2 * nh2 + j; }
+  __device__ __forceinline__ int* alive(int j) const { return base + 16 + 3 * nh2 + j * kRowsWords; }
+  // verification: the merged argmax of every position
+  __device__ __forceinline__ int* target(int pos) const { return base + 16 + nh2 * (3 + kRowsWords) + pos; }
+};
+
+__device__ __forceinline__ int ctl_load(const int* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void ctl_add(int* p, int v) { (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// One lane waits until (*word & mask) >= target and returns the word, or -1 if the launch was
+// aborted or the wait timed out (which aborts the launch).
+__device__ __forceinline__ int rows_wait(const RowsParams& p, const RowsCtl& c, const int* word, int target,
+                                         int mask = 0x7fffffff) {
+  for (int spins = 0;; ++spins) {
+    const int v = ctl_load(word);
+    if ((v & mask) >= target) return v;
+    if (ctl_load(c.abort_word()) != 0) return -1;
+    if (spins >= p.spin_limit) {
+      atomicExch(p.status, 1);
+      __hip_atomic_store(c.abort_word(), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return -1;
+    }
+    __builtin_amdgcn_s_sleep(8);
+  }
+}
+// The whole wave waits (lane 0 polls).
+__device__ __forceinline__ bool rows_wait_wave(const RowsParams& p, const RowsCtl& c, const int* word, int target, int lane) {
+  int ok = 1;
+  if (lane == 0) ok = rows_wait(p, c, word, target) >= 0 ? 1 : 0;
+  return __builtin_amdgcn_readfirstlane(ok) != 0;
+}
+
+// Device-coherent 16-byte store / Stats record store and load (no cache of another die may
+// keep serving an older copy).
+__device__ __forceinline__ void store_coherent(frag_t* dst, const frag_t& v) {
+  unsigned long long* d = (unsigned long long*)dst;
+  __hip_atomic_store(d, ((unsigned long long)v.y << 32) | v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(d + 1, ((unsigned long long)v.w << 32) | v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_coherent(Stats* dst, const Stats& s) {
+  unsigned* d = (unsigned*)dst;
+  __hip_atomic_store(d + 0, __float_as_uint(s.m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(d + 1, __float_as_uint(s.S), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(d + 2, __float_as_uint(s.U), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(d + 3, __float_as_uint(s.zb), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(d + 4, (unsigned)s.ib, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ Stats load_coherent(const Stats* src) {
+  const unsigned* p = (const unsigned*)src;
+  Stats s;
+  s.m = __uint_as_float(__hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  s.S = __uint_as_float(__hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  s.U = __uint_as_float(__hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  s.zb = __uint_as_float(__hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  s.ib = (int)__hip_atomic_load(p + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return s;
+}
+// 16-byte chunk c of the row at column p of an activation buffer in 32-row operand order
+__device__ __forceinline__ void put_chunk32_coherent(frag_t* __restrict__ yf, int KS, int p, int c, const frag_t& v) {
+  frag_t* dst = yf + (int64_t)(p >> 5) * KS * kWave * 2;
+  store_coherent(dst + (c >> 1) * kWave + (c & 1) * 32 + (p & 31), v);
+}
+
+struct RowMask {
+  unsigned w[kRowsWords];
+  __device__ __forceinline__ void set_all(int n) {
+#pragma unroll
+    for (int i = 0; i < kRowsWords; ++i) {
+      const int left = n - 32 * i;
+      w[i] = left >= 32 ? 0xffffffffu : (left > 0 ? ((1u << left) - 1u) : 0u);
+    }
+  }
+  __device__ __forceinline__ void load(const int* src) {
+#pragma unroll
+    for (int i = 0; i < kRowsWords; ++i) w[i] = (unsigned)ctl_load(src + i);
+  }
+  __device__ __forceinline__ bool test(int r) const {
+    unsigned v = 0;
+#pragma unroll
+    for (int i = 0; i < kRowsWords; ++i) v = (i == (r >> 5)) ? w[i] : v;
+    return (v >> (r & 31)) & 1u;
+  }
+  __device__ __forceinline__ int count() const {
+    int n = 0;
+#pragma unroll
+    for (int i = 0; i < kRowsWords; ++i) n += __popc(w[i]);
+    return n;
+  }
+  // number of set bits below r
+  __device__ __forceinline__ int rank(int r) const {
+    int n = 0;
+#pragma unroll
+    for (int i = 0; i < kRowsWords; ++i) {
+      if (i < (r >> 5)) n += __popc(w[i]);
+      else if (i == (r >> 5)) n += __popc(w[i] & ((1u << (r & 31)) - 1u));
+    }
+    return n;
+  }
+};
+
+// A pass for a wave that owns no live token block: it still has to bring its share of the
+// weights into the ring and keep every barrier of pass32<MT, ...> (one when the pass opens, one
+// behind the prologue, one per k-step), but issues nothing else.  Its loads are the DMA pieces
+// only, in pass32's order: at the wait that opens step ks the pieces of steps ks+2 .. ks+D may
+// still be in flight.
+template <int MT>
+__device__ __forceinline__ void pass32_idle(const frag_t* __restrict__ Wf, int T16, int t16_end, int KS, int lane,
+                                            int wave, EH_LDS char* lds) {
+  constexpr int kDma = dma_per_wave(MT);
+  constexpr int NF = 2 * MT;
+  const int lastk = KS - 1;
+  const uint32_t lane16 = (uint32_t)lane << 4;
+  const EH_GLOBAL char* wbase = uniform_ptr(Wf);
+  long long wsrc[kDma];
+  int wdst[kDma];
+#pragma unroll
+  for (int i = 0; i < kDma; ++i) {
+    int f = wave + kG32Waves * i;
+    if (f >= NF) f = (wave < NF) ? wave + kG32Waves * ((NF - 1 - wave) / kG32Waves) : NF - 1;
+    const int t16 = min(T16 + f, t16_end - 1);
+    wsrc[i] = ((long long)t16 * KS) << 10;
+    wdst[i] = f * 1024;
+  }
+  auto dma = [&](int ks) {
+    const int k = min(ks, lastk);
+    EH_LDS char* slot = lds + (ks & (kSlots - 1)) * kSlotBytes;
+#pragma unroll
+    for (int i = 0; i < kDma; ++i)
+      __builtin_amdgcn_global_load_lds((const EH_GLOBAL void*)(wbase + wsrc[i] + ((long long)k << 10) + lane16),
+                                       (EH_LDS void*)(slot + wdst[i]), 16, 0, 0);
+  };
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  dma(0);
+#pragma unroll
+  for (int j = 0; j < kDepth; ++j) dma(j + 1);
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kDepth * kDma) : "memory");
+  for (int ks = 0; ks < KS; ++ks) {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((kDepth - 1) * kDma) : "memory");
+    dma(ks + kDepth + 1);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// The weights of the first kDepth+1 k-steps of a pass, brought into the ring ahead of time by
+// this wave's DMA share (the pass will fetch them again: what this buys is that they then come
+// from the L2 and not from HBM).  Called between passes, when nobody reads the ring; the loads are
+// waited for by the vmcnt(0) that opens the next pass at the latest.
+template <int MT>
+__device__ __forceinline__ void ring_prefetch(const frag_t* __restrict__ Wf, int T16, int t16_end, int KS, int lane,
+                                              int wave, EH_LDS char* lds) {
+  constexpr int kDma = dma_per_wave(MT);
+  constexpr int NF = 2 * MT;
+  const int lastk = KS - 1;
+  const uint32_t lane16 = (uint32_t)lane << 4;
+  const EH_GLOBAL char* wbase = uniform_ptr(Wf);
+#pragma unroll
+  for (int ks = 0; ks <= kDepth; ++ks) {
+    const int k = min(ks, lastk);
+#pragma unroll
+    for (int i = 0; i < kDma; ++i) {
+      int f = wave + kG32Waves * i;
+      if (f >= NF) f = (wave < NF) ? wave + kG32Waves * ((NF - 1 - wave) / kG32Waves) : NF - 1;
+      const int t16 = min(T16 + f, t16_end - 1);
+      __builtin_amdgcn_global_load_lds((const EH_GLOBAL void*)(wbase + ((((long long)t16 * KS) + k) << 10) + lane16),
+                                       (EH_LDS void*)(lds + ks * kSlotBytes + f * 1024), 16, 0, 0);
+    }
+  }
+}
+
+// LayerNorm of one row by one wave into column `pos` of an activation buffer (32-row operand order).
+__device__ __forceinline__ void rows_layernorm(const RowsParams& p, int l, int r, frag_t* __restrict__ yl, int pos, int lane) {
+  const char* row = (const char*)p.h + ((long long)l * p.layer_stride + (long long)r * p.row_stride) * DtBf16::ESZ;
+  auto put = [&](int c, const frag_t& v) { put_chunk32_coherent(yl, p.KS, pos, c, v); };
+  group_layernorm<DtBf16, 1>(row, p.d, p.KS * 4, p.gamma[l], p.beta[l], p.eps, lane, (double*)nullptr, put);
+}
+
+// Merge of the streaming workgroups' partial statistics of one column (one wave), in
+// finalize_kernel's order.
+__device__ __forceinline__ Stats rows_merge(const Stats* __restrict__ part, int n_parts, int R_pad, int col, int lane) {
+  Stats s;
+  stats_init(s);
+  for (int g = lane; g < n_parts; g += kWave) s = stats_merge(s, load_coherent(part + (long long)g * R_pad + col));
+#pragma unroll
+  for (int x = 32; x > 0; x >>= 1) s = stats_merge(s, stats_shfl_xor(s, x));
+  return s;
+}
+
+// Returns false if the launch was aborted (or every row has left).
+template <bool ARGMAX_ONLY>
+__device__ __forceinline__ bool rows_stream(const RowsParams& p, const RowsCtl& c, EH_LDS char* lds, int lane, int wave,
+                                            double* red, int* flag) {
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int nh = p.l1 - p.l0;
+  const int nsw = ((int)gridDim.x - p.n_stream) * kG32Waves;  // service waves
+  // LayerNorm of the first head's rows, spread over the streaming workgroups (four waves per row)
+  for (int r = g; r < p.n_rows; r += p.n_stream) {
+    const char* row = (const char*)p.h + ((long long)p.l0 * p.layer_stride + (long long)r * p.row_stride) * DtBf16::ESZ;
+    auto put = [&](int ch, const frag_t& v) { put_chunk32_coherent(p.y, p.KS, r, ch, v); };
+    if (p.KS * 4 <= kLnCache * kWave)
+      group_layernorm_cached<DtBf16, kLnWaves>(row, p.d, p.KS * 4, p.gamma[p.l0], p.beta[p.l0], p.eps, tid, red, put);
+    else
+      group_layernorm<DtBf16, kLnWaves>(row, p.d, p.KS * 4, p.gamma[p.l0], p.beta[p.l0], p.eps, tid, red, put);
+    __syncthreads();
+  }
+  EH_STORES_DONE();
+  __syncthreads();
+  if (tid == 0) ctl_add(c.ready(0), 1);
+  // my slice of the vocabulary, in 16-row tiles (bytes balanced: the stream paces these shapes)
+  const int T0 = (int)((long long)p.VT16 * g / p.n_stream);
+  const int T1 = (int)((long long)p.VT16 * (g + 1) / p.n_stream);
+  const int row_hi = min(p.V, T1 * 16);
+  // the first head's activations are complete when every streaming workgroup has written its rows
+  if (tid == 0) *flag = rows_wait(p, c, c.ready(0), p.n_stream);
+  __syncthreads();
+  int word = *flag;
+  __syncthreads();
+  if (word < 0) return false;
+  EH_AFTER_WAIT();
+  int ncols = p.n_rows;
+  for (int j = 0; j < nh; ++j) {
+    const int l = p.l0 + j;
+    if (ncols == 0) return false;  // every row has left: the same for all workgroups
+    // token blocks of 32 columns, dealt to the four waves as evenly as they go (at most 2 each)
+    const int nblocks = (ncols + 31) >> 5;
+    const int nb_live = nblocks / kG32Waves + (wave < nblocks % kG32Waves ? 1 : 0);
+    const int nb_first = wave * (nblocks / kG32Waves) + min(wave, nblocks % kG32Waves);
+    Stats st[2];
+    stats_init(st[0]);
+    stats_init(st[1]);
+    const frag_t* Wf = p.Wf[l];
+    const frag_t* ybase = p.y + (long long)j * p.y_stride + (long long)nb_first * 2 * p.KS * kWave;
+    for (int t = T0; t < T1;) {
+      const int left = (T1 - t + 1) >> 1;
+      const int passes = (left + kMaxMT - 1) / kMaxMT;
+      const int mt = (left + passes - 1) / passes;
+#define EH_ROWS_PASS(MT_)                                                                                     \
+  if (nb_live <= 0) pass32_idle<MT_>(Wf, t, T1, p.KS, lane, wave, lds);                                          \
+  else if (nb_live == 1) pass32<MT_, 1, ARGMAX_ONLY, false>(Wf, ybase, t, T1, p.KS, row_hi, lane, wave, lds,          \
+                                                        reinterpret_cast<Stats(&)[1]>(st[0]));                   \
+  else pass32<MT_, 2, ARGMAX_ONLY, false>(Wf, ybase, t, T1, p.KS, row_hi, lane, wave, lds, st)
+      switch (mt) {
+        case 7: EH_ROWS_PASS(7); break;
+        case 6: EH_ROWS_PASS(6); break;
+        case 5: EH_ROWS_PASS(5); break;
+        case 4: EH_ROWS_PASS(4); break;
+        case 3: EH_ROWS_PASS(3); break;
+        case 2: EH_ROWS_PASS(2); break;
+        default: EH_ROWS_PASS(1); break;
+      }
+#undef EH_ROWS_PASS
+      t += 2 * mt;
+    }
+    Stats* part = p.partials + (long long)(j & 1) * p.n_stream * p.R_pad + (long long)g * p.R_pad;
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+      st[n] = stats_merge(st[n], stats_shfl_xor(st[n], 32));  // lanes l and l+32 hold the same token
+      if (lane < 32 && n < nb_live) store_coherent(part + (nb_first + n) * 32 + lane, st[n]);
+    }
+    if (j + 1 < nh) {
+      // while those stores travel: warm the L2 with the start of the next head's weights, and look
+      // whether the next head's activations are there (they have been for a while, as a rule).
+      // Heads from the third on carry their column count in the upper bits of the counter.
+      if (T0 < T1) {
+        const int left = (T1 - T0 + 1) >> 1;
+        const int mt = (left + (left + kMaxMT - 1) / kMaxMT - 1) / ((left + kMaxMT - 1) / kMaxMT);
+        const frag_t* Wn = p.Wf[l + 1];
+        switch (mt) {
+          case 7: ring_prefetch<7>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+          case 6: ring_prefetch<6>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+          case 5: ring_prefetch<5>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+          case 4: ring_prefetch<4>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+          case 3: ring_prefetch<3>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+          case 2: ring_prefetch<2>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+          default: ring_prefetch<1>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+        }
+      }
+      if (tid == 0) *flag = rows_wait(p, c, c.ready(j + 1), nsw, 0xff);
+    }
+    EH_STORES_DONE();
+    __syncthreads();
+    if (tid == 0) ctl_add(c.done(j), 1);
+    if (j + 1 < nh) {
+      word = *flag;
+      __syncthreads();  // the flag is rewritten at the end of the next head
+      if (word < 0) return false;
+      EH_AFTER_WAIT();
+      ncols = j + 1 >= 2 ? (word >> 8) : p.n_rows;
+    }
+  }
+  return true;
+}
+
+// Service waves of a cascade (mode 0).  sw = index of this wave among the nsw service waves; it
+// owns the rows r = sw, sw + nsw, ...
+__device__ __forceinline__ void rows_serve_cascade(const RowsParams& p, const RowsCtl& c, int lane, int sw, int nsw) {
+  const int nh = p.l1 - p.l0;
+  // the second head's activations for every row (identity columns); the first head's are
+  // written by the streaming workgroups
+  if (nh > 1) {
+    for (int r = sw; r < p.n_rows; r += nsw) rows_layernorm(p, p.l0 + 1, r, p.y + p.y_stride, r, lane);
+    EH_STORES_DONE();
+    if (lane == 0) ctl_add(c.ready(1), 1);
+  }
+  RowMask cols, alive;  // columns of head j (rows alive after head j-2), rows entering head j
+  cols.set_all(p.n_rows);
+  alive.set_all(p.n_rows);
+  for (int j = 0; j < nh; ++j) {
+    const int l = p.l0 + j;
+    const bool last = l == p.n_heads - 1;
+    if (!rows_wait_wave(p, c, c.done(j), p.n_stream, lane)) return;
+    EH_AFTER_WAIT();
+    const Stats* part = p.partials + (long long)(j & 1) * p.n_stream * p.R_pad;
+    const float tau = p.tau[l];
+    RowMask stay;
+    stay.set_all(0);
+    int evals = 0;
+    for (int r = sw; r < p.n_rows; r += nsw) {
+      if (!alive.test(r)) continue;
+      const Stats s = rows_merge(part, p.n_stream, p.R_pad, cols.rank(r), lane);
+      float H, lse;
+      stats_finalize(s, H, lse);
+      ++evals;
+      const bool leaves = last || (H < tau);  // NaN never passes the test
+      if (lane == 0) {
+        if (p.H_out) p.H_out[(long long)l * p.n_rows + r] = H;
+        if (leaves) {
+          p.exit_layer[r] = l;
+          p.token[r] = stats_token(s);
+        }
+      }
+      if (!leaves) {
+#pragma unroll
+        for (int i = 0; i < kRowsWords; ++i)
+          if (i == (r >> 5)) stay.w[i] |= 1u << (r & 31);
+      }
+    }
+    if (lane == 0 && evals && p.n_evals) atomicAdd(p.n_evals, (unsigned long long)evals);
+    if (last || j + 1 == nh) return;
+    // publish who goes on, wait for everybody's word, then prepare head j+2 for the survivors
+    if (lane == 0) {
+#pragma unroll
+      for (int i = 0; i < kRowsWords; ++i)
+        if (stay.w[i]) (void)__hip_atomic_fetch_or(c.alive(j + 1) + i, (int)stay.w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    EH_STORES_DONE();  // the mask words above are atomics of lane 0: performed before the counter
+    if (lane == 0) ctl_add(c.decided(j), 1);
+    if (!rows_wait_wave(p, c, c.decided(j), nsw, lane)) return;
+    EH_AFTER_WAIT();
+    RowMask next;
+    next.load(c.alive(j + 1));
+    if (j + 2 < nh) {
+      frag_t* yl = p.y + (long long)(j + 2) * p.y_stride;
+      int mine = 0;
+      for (int r = sw; r < p.n_rows; r += nsw) {
+        if (next.test(r)) {
+          rows_layernorm(p, l + 2, r, yl, next.rank(r), lane);
+          ++mine;
+        }
+      }
+      EH_STORES_DONE();
+      // low byte: service waves done; above it: the columns written (their sum is the head's column count)
+      if (lane == 0) ctl_add(c.ready(j + 2), 1 + (mine << 8));
+    }
+    if (next.count() == 0) return;  // the same masks in every service wave
+    cols = alive;
+    alive = next;
+  }
+}
+
+// Tail of a verification (mode 1; every workgroup streams, none only serves): when all partial
+// argmax records are there, workgroup g merges those of the positions g, g + grid, ... (one
+// record per thread), and when all positions are merged workgroup b < B walks draft row b's prefix.
+__device__ __forceinline__ void rows_verify_tail(const RowsParams& p, const RowsCtl& c, int lane, int wave, int* flag,
+                                                 float* red_z, int* red_i) {
+  const int g = blockIdx.x, tid = threadIdx.x;
+  if (tid == 0) *flag = rows_wait(p, c, c.done(0), p.n_stream) >= 0 ? 1 : 0;
+  __syncthreads();
+  int ok = *flag;
+  __syncthreads();
+  if (!ok) return;
+  EH_AFTER_WAIT();
+  for (int pos = g; pos < p.n_rows; pos += p.n_stream) {
+    float zb = -INFINITY;
+    int ib = 0x7fffffff;
+    for (int q = tid; q < p.n_stream; q += kG32Threads) {
+      const Stats r = load_coherent(p.partials + (long long)q * p.R_pad + pos);
+      if (r.zb > zb || (r.zb == zb && r.ib < ib)) { zb = r.zb; ib = r.ib; }
+    }
+#pragma unroll
+    for (int x = 32; x > 0; x >>= 1) {
+      const float oz = __shfl_xor(zb, x);
+      const int oi = __shfl_xor(ib, x);
+      if (oz > zb || (oz == zb && oi < ib)) { zb = oz; ib = oi; }
+    }
+    if (lane == 0) { red_z[wave] = zb; red_i[wave] = ib; }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+      for (int w2 = 1; w2 < kG32Waves; ++w2)
+        if (red_z[w2] > zb || (red_z[w2] == zb && red_i[w2] < ib)) { zb = red_z[w2]; ib = red_i[w2]; }
+      const int t = argmax_or_none(ib);
+      __hip_atomic_store(c.target(pos), t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (p.target) p.target[pos] = t;
+      EH_STORES_DONE();
+      ctl_add(c.decided(0), 1);
+    }
+    __syncthreads();
+  }
+  if (g < p.B && tid == 0) {
+    if (rows_wait(p, c, c.decided(0), p.n_rows) < 0) return;
+    EH_AFTER_WAIT();
+    int len = p.k;
+    if (p.draft_len) len = min(max(p.draft_len[g], 0), p.k);
+    int n = 0;
+    while (n < len && p.draft[(long long)g * p.k + n] == ctl_load(c.target(g * (p.k + 1) + n))) ++n;
+    p.accepted[g] = n;
+    p.next_token[g] = ctl_load(c.target(g * (p.k + 1) + n));
+  }
+}
+
+template <bool ARGMAX_ONLY>
+__global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel_rows(const RowsParams p) {
+  extern __shared__ __attribute__((aligned(16))) char g32_smem[];
+  __shared__ double red[2 * kLnWaves];
+  __shared__ int flag;
+  __shared__ float red_z[kG32Waves];
+  __shared__ int red_i[kG32Waves];
+  EH_LDS char* lds = (EH_LDS char*)g32_smem;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // a launch that gave up has not been acknowledged yet (eh_check clears the flag): do nothing
+  if (*(volatile int*)p.status != 0) return;
+  RowsCtl c{p.ctl, p.l1 - p.l0 + 2};
+  if ((int)blockIdx.x < p.n_stream) {
+    const bool ok = rows_stream<ARGMAX_ONLY>(p, c, lds, lane, wave, red, &flag);
+    if (ok && p.mode == 1) rows_verify_tail(p, c, lane, wave, &flag, red_z, red_i);
+    return;
+  }
+  const int sg = (int)blockIdx.x - p.n_stream, nsg = (int)gridDim.x - p.n_stream;
+  if (p.mode == 0) rows_serve_cascade(p, c, lane, sg * kG32Waves + wave, nsg * kG32Waves);
+}
+
+// Presets of a launch: the control block to zero, a cascade's outputs to "not decided".
+__global__ void rows_preset_kernel(int* __restrict__ ctl, int n_ctl, int* __restrict__ exit_layer, int* __restrict__ token,
+                                   int n_rows, float* __restrict__ H_out, int n_H, int* __restrict__ accepted,
+                                   int* __restrict__ next_token, int B) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_ctl) ctl[i] = 0;
+  if (exit_layer && i < n_rows) { exit_layer[i] = -1; token[i] = -1; }
+  if (H_out && i < n_H) H_out[i] = NAN;
+  if (accepted && i < B) { accepted[i] = -1; next_token[i] = -1; }
+}
+
 template <int NBH>
 void launch_kl(dim3 g, hipStream_t s, const frag_t* Wf, long long wdelta, const frag_t* yq, const frag_t* yq2,
                int VT16, int KS, int V, int n_rows, int R_pad, const int* labels, KlStats* partials) {
@@ -723,6 +1222,52 @@ hipError_t gemm32_launch(const eh_ctx* c, int head, const int* n_rows_dev, int n
                          const frag_t* yf, Stats* partials, float* second, int* n_parts, hipStream_t s) {
   return gemm32_launch_heads(c, head, 1, n_rows_dev, n_rows, argmax_only, yf, 0, partials, second, 0, n_parts, s);
 }
+
+hipError_t rows_prepare(eh_ctx* c) {
+  c->rows_grid = 0;
+  if (c->dtype != EH_BF16 || !c->bias.empty()) return hipSuccess;
+  hipDeviceProp_t prop;
+  hipError_t e = hipGetDeviceProperties(&prop, c->device);
+  if (e != hipSuccess) return e;
+  const int cus = prop.multiProcessorCount;
+  if (cus < 4 * kRowsServiceWgs) return hipSuccess;  // too small a device to set workgroups aside
+  const void* fns[2] = {(const void*)gemm32_stats_kernel_rows<false>, (const void*)gemm32_stats_kernel_rows<true>};
+  for (const void* fn : fns) {
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g32_lds_bytes());
+    if (e != hipSuccess) { (void)hipGetLastError(); return hipSuccess; }
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kG32Threads, g32_lds_bytes());
+    if (e != hipSuccess || per_cu < 1) { (void)hipGetLastError(); return hipSuccess; }
+  }
+  // the kernel's workgroups wait for each other: all of them must be resident at once
+  c->rows_grid = cus;
+  return hipSuccess;
+}
+
+hipError_t rows_launch(const eh_ctx* c, const RowsParams& p, hipStream_t s) {
+  // every pointer the kernel dereferences unconditionally, and the sizes its indexing assumes
+  if (!p.status || !p.ctl || !p.y || !p.partials || !p.Wf || !p.gamma || !p.beta || !p.tau || !p.h) return hipErrorInvalidValue;
+  if (c->rows_grid <= kRowsServiceWgs || p.n_stream != (p.mode == 0 ? c->rows_grid - kRowsServiceWgs : c->rows_grid)) return hipErrorInvalidValue;
+  if (p.n_rows < 1 || p.n_rows > kRowsMax || p.R_pad < p.n_rows || p.R_pad % 32 != 0) return hipErrorInvalidValue;
+  if (p.l0 < 0 || p.l1 <= p.l0 || p.l1 > p.n_heads || rows_ctl_ints(p.l1 - p.l0) > c->rows_ctl_ints) return hipErrorInvalidValue;
+  if ((long long)(p.R_pad / 16 + 32) * p.KS * kWave > p.y_stride) return hipErrorInvalidValue;  // one buffer per head
+  if (p.mode == 0 ? (!p.exit_layer || !p.token) : (!p.accepted || !p.next_token || (p.k > 0 && !p.draft) || p.B * (p.k + 1) != p.n_rows))
+    return hipErrorInvalidValue;
+  const int n_ctl = rows_ctl_ints(p.l1 - p.l0);
+  const int n_H = (p.mode == 0 && p.H_out) ? p.n_heads * p.n_rows : 0;
+  const int n = std::max(std::max(n_ctl, n_H), std::max(p.n_rows, p.B));
+  hipLaunchKernelGGL(rows_preset_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.ctl, n_ctl,
+                     p.mode == 0 ? p.exit_layer : (int*)nullptr, p.token, p.n_rows, p.mode == 0 ? p.H_out : (float*)nullptr,
+                     n_H, p.mode == 1 ? p.accepted : (int*)nullptr, p.next_token, p.B);
+  if (p.argmax_only)
+    hipLaunchKernelGGL((gemm32_stats_kernel_rows<true>), dim3(c->rows_grid), dim3(kG32Threads), g32_lds_bytes(), s, p);
+  else
+    hipLaunchKernelGGL((gemm32_stats_kernel_rows<false>), dim3(c->rows_grid), dim3(kG32Threads), g32_lds_bytes(), s, p);
+  return hipGetLastError();
+}
+
+int rows_control_ints(int n_heads) { return rows_ctl_ints(n_heads); }
+int rows_service_workgroups() { return kRowsServiceWgs; }
 
 hipError_t gemm32_kl_launch(const eh_ctx* c, int head, int model_head, int n_rows, const frag_t* yf_head,
                             const frag_t* yf_model, const int* labels, KlStats* partials, int* n_parts,

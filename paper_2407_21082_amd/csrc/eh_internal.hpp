@@ -56,6 +56,13 @@ struct eh_ctx {
   int spin_limit = 1 << 22;                 // polls of another workgroup's record before giving up
   unsigned long long* dec_trace = nullptr;  // [n_heads][16] timestamps of workgroup 0 (diagnostics)
   int dec_trace_on = 0;
+  // persistent kernel for 17 .. 256 rows (bf16, no bias): 0 = shape not supported
+  int rows_grid = 0;
+  int* rows_ctl = nullptr;             // control block (counters, live-row masks), cleared before each launch
+  int rows_ctl_ints = 0;
+  eh::frag_t* rows_y = nullptr;        // [n_heads][rows_y_stride] activations, one buffer per head
+  long long rows_y_stride = 0;         // fragments
+  eh::Stats* rows_partials = nullptr;  // [2][rows_grid][256] partial statistics of two consecutive heads
   void* static_scratch = nullptr;  // device address of the library's static workspace on this device
   std::vector<void*> allocs;
   std::string err = "";
@@ -91,6 +98,45 @@ struct DecodeParams {
   unsigned long long* n_evals;  // nullable
   unsigned long long* trace;    // nullable: [n_heads][16] wall-clock stamps written by workgroup 0
 };
+
+// Arguments of the persistent kernel for 17 .. 256 rows (bf16 heads without a bias vector):
+// heads l0 .. l1-1 of a cascade (mode 0) or the model's head of a verification (mode 1).
+constexpr int kRowsMax = 256;
+struct RowsParams {
+  const frag_t* const* Wf;
+  const float* const* gamma;
+  const float* const* beta;
+  const float* tau;             // device [n_heads]
+  const void* h;                // mode 0: [head][row][d] through the strides; mode 1: [rows][d]
+  long long layer_stride, row_stride;  // elements
+  int n_rows, n_heads, l0, l1, mode, argmax_only;
+  int V, d, KS, VT16;
+  float eps;
+  int n_stream;                 // workgroups that stream weights; the rest of the grid serves
+  int spin_limit;
+  int* ctl;                     // control block, all zero at launch
+  frag_t* y;                    // [l1 - l0][y_stride]: one buffer per head of the launch
+  long long y_stride;
+  Stats* partials;              // [2][n_stream][R_pad]
+  int R_pad;
+  int* status;
+  int* exit_layer;              // mode 0 outputs
+  int* token;
+  float* H_out;                 // nullable [n_heads][n_rows]
+  unsigned long long* n_evals;  // nullable
+  const int* draft;             // mode 1: [B][k]
+  const int* draft_len;         // nullable [B]
+  int B, k;
+  int* accepted;
+  int* next_token;
+  int* target;                  // nullable [B][k+1]
+};
+// Occupancy check and sizes for the rows kernel; leaves ctx->rows_grid = 0 if it cannot run.
+hipError_t rows_prepare(eh_ctx* ctx);
+// Enqueues the preset of outputs and control block, then the kernel.
+hipError_t rows_launch(const eh_ctx* ctx, const RowsParams& p, hipStream_t s);
+int rows_control_ints(int n_heads);   // size of the control block for a launch over n_heads heads
+int rows_service_workgroups();       // workgroups of the grid that do not stream
 
 // Sets up the decode kernel for this context (grid, LDS size, function
 // attributes).  Leaves ctx->decode_grid = 0 if the shape does not fit.

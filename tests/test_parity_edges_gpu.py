@@ -213,12 +213,18 @@ def test_cascade_is_strict_at_its_own_entropy(B, dtype, rows):
     w = G.Workload("strict", d=256, V=3000, n_heads=3, rows=rows, dtype=dtype, seed=rows + 40)
     heads = G.make_heads(w, DEV)
     hid = G.make_hidden(w, heads, DEV)
-    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [0.0, 0.0, 0.0], max_rows=rows)
+    # the library's own entropies of every head on every row: a cascade in which no exit head ever
+    # fires reports them all (the same kernels, hence the same floats, as the cascades below)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, [float("-inf"), float("-inf"), 0.0], max_rows=rows)
     Hg = torch.zeros((3, rows), device=DEV)
     Ag = torch.zeros((3, rows), dtype=torch.int32, device=DEV)
+    ex0 = torch.full((rows,), -1, dtype=torch.int32, device=DEV)
+    tok0 = torch.full((rows,), -1, dtype=torch.int32, device=DEV)
+    B.eh_cascade(ctx, hid.h, rows, ex0, tok0, Hg, None)
     for l in range(3):
-        B.eh_eval(ctx, l, hid.h[l], rows, Hg[l], None, Ag[l])
+        B.eh_eval(ctx, l, hid.h[l], rows, None, None, Ag[l])
     torch.cuda.synchronize()
+    assert (ex0 == 2).all() and torch.equal(tok0, Ag[2]) and torch.isfinite(Hg).all()
     B.eh_destroy(ctx)
     Hn, An = Hg.cpu().numpy(), Ag.cpu().numpy()
     r_star = int(np.argsort(Hn[0])[rows // 2])              # a row in the middle of head 0's entropies
@@ -240,8 +246,13 @@ def test_cascade_is_strict_at_its_own_entropy(B, dtype, rows):
         assert (want[r_star] == 0) == leaves
         np.testing.assert_array_equal(tok.cpu().numpy(), An[want, np.arange(rows)])
         Ho = Hout.cpu().numpy()
-        for r in range(rows):                                 # the same floats as eh_eval, NaN beyond the exit
-            assert (Ho[:want[r] + 1, r] == Hn[:want[r] + 1, r]).all() and np.isnan(Ho[want[r] + 1:, r]).all()
+        # head 0 sees the same columns in both cascades: the same floats.  Later heads see the
+        # survivors compacted, and a different number of token blocks per wave may round the last bit
+        # differently; beyond the exit nothing is evaluated.
+        assert (Ho[0] == Hn[0]).all()
+        for r in range(rows):
+            assert np.allclose(Ho[1:want[r] + 1, r], Hn[1:want[r] + 1, r], rtol=2e-6, atol=2e-6)
+            assert np.isnan(Ho[want[r] + 1:, r]).all()
         assert int(nev.item()) == int((want + 1).sum())
 
 
@@ -407,6 +418,52 @@ def test_persistent_kernel_gives_up_cleanly_and_recovers(B):
     assert all(np.array_equal(a, b, equal_nan=True) for a, b in zip(good, again))
     with pytest.raises(B.EhError):
         B.eh_set_spin_limit(ctx, -1)
+    B.eh_destroy(ctx)
+
+
+@pytest.mark.parametrize("mode", ["cascade", "verify"])
+def test_rows_kernel_gives_up_cleanly_and_recovers(B, mode):
+    """The same for the persistent kernel behind 17 .. 256 rows (cascade and verification)."""
+    w = G.Workload("giveup", d=256, V=20000, n_heads=5, rows=48, dtype="bf16", seed=8, kappa=0.6)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, G.tau_linear(w), max_rows=48)
+    f_final = hid.h[4].reshape(6, 8, w.d).contiguous()
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(1)
+    draft = torch.randint(0, w.V, (6, 7), generator=gen).to(torch.int32).to(DEV)
+
+    def run():
+        if mode == "cascade":
+            a = torch.full((48,), -7, dtype=torch.int32, device=DEV)
+            b = torch.full((48,), -7, dtype=torch.int32, device=DEV)
+            B.eh_cascade(ctx, hid.h, 48, a, b, None, None)
+        else:
+            a = torch.full((6,), -7, dtype=torch.int32, device=DEV)
+            b = torch.full((6,), -7, dtype=torch.int32, device=DEV)
+            B.dssd_verify(ctx, f_final, draft, None, a, b, None)
+        torch.cuda.synchronize()
+        return a.cpu().numpy(), b.cpu().numpy()
+
+    good = run()
+    B.eh_check(ctx)
+    assert (good[0] >= 0).all() and (good[1] >= 0).all()
+    B.eh_set_spin_limit(ctx, 0)
+    failures = 0
+    for _ in range(3):
+        a, b = run()
+        try:
+            B.eh_check(ctx)
+        except B.EhError as e:
+            failures += 1
+            assert e.status == 5
+        for i in range(len(a)):                               # finished rows are right, the others preset
+            assert (a[i], b[i]) in ((-1, -1), (good[0][i], good[1][i]))
+    assert failures >= 1, "zero polls never made a workgroup give up"
+    B.eh_set_spin_limit(ctx, 1 << 22)
+    again = run()
+    B.eh_check(ctx)
+    assert np.array_equal(good[0], again[0]) and np.array_equal(good[1], again[1])
     B.eh_destroy(ctx)
 
 
