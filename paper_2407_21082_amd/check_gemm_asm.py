@@ -10,7 +10,7 @@ compile-time count of younger loads.  That is only sound if, in the generated co
   * no path reaches the end of the program with such a load still in flight.
 
 This module proves both properties on the assembly text: for every `global_load_dwordx4`
-into VGPRs it walks every path of the kernel's control-flow graph forward from the load,
+into VGPRs (and every `ds_read_b128`) that comes from an inline-asm statement it walks every path of the kernel's control-flow graph forward from the load,
 counting vector-memory loads issued after it (loads return in order, so
 `s_waitcnt vmcnt(N)` guarantees the load has landed once at least N younger ones were
 issued), and reports any instruction that names one of the load's destination registers
@@ -67,11 +67,19 @@ class Program:
     def __init__(self, lines):
         self.ins = []        # instruction text (mnemonic + operands, comments stripped)
         self.note = []       # the comment that followed it on its line ("" if none)
+        self.by_hand = []    # the instruction comes from an inline-asm statement of the source
         self.label_at = {}   # label -> index of the next instruction
+        in_asm = False
         for line in lines:
             m = LABEL_RE.match(line)
             if m:
                 self.label_at[m.group(1)] = len(self.ins)
+                continue
+            if "#ASMSTART" in line:
+                in_asm = True
+                continue
+            if "#ASMEND" in line:
+                in_asm = False
                 continue
             t, _, note = line.partition(";")
             t = t.strip()
@@ -79,6 +87,7 @@ class Program:
                 continue
             self.ins.append(t)
             self.note.append(note.strip())
+            self.by_hand.append(in_asm)
         n = len(self.ins)
         self.succ = [None] * n
         for i, t in enumerate(self.ins):
@@ -139,7 +148,10 @@ def check_kernel(lines, max_report=5, classes=(VM_LOADS, LDS_LOADS)):
             wait_n.append(int(m.group(1)) if m else None)
         for i, t in enumerate(ins):
             m = cls.load_re.match(t)
-            if not m:
+            # loads the compiler emitted itself are tracked by its own wait counts (it may even
+            # reuse a destination whose value is dead: loads return in order); the hand-counted
+            # ones are those of the source's inline-asm statements
+            if not m or not prog.by_hand[i]:
                 continue
             n_loads += 1
             dest = set(range(int(m.group(1)), int(m.group(2)) + 1))

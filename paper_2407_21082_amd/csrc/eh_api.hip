@@ -185,10 +185,10 @@ RowsParams rows_base(eh_ctx* c, int n_rows) {
   p.Wf = c->d_Wf; p.gamma = c->d_gamma; p.beta = c->d_beta; p.tau = c->d_tau;
   p.n_rows = n_rows; p.n_heads = c->n_heads;
   p.V = c->V; p.d = c->d; p.KS = c->KS; p.VT16 = c->VT; p.eps = c->eps;
-  p.n_stream = c->rows_grid - rows_service_workgroups();
+  p.n_stream = c->rows_grid - rows_service_workgroups(n_rows);
   p.spin_limit = c->spin_limit;
   p.ctl = c->rows_ctl; p.y = c->rows_y; p.y_stride = c->rows_y_stride;
-  p.partials = c->rows_partials; p.R_pad = (n_rows + 31) & ~31;
+  p.part4 = c->rows_part4; p.parti = c->rows_parti; p.R_pad = (n_rows + 31) & ~31;
   p.status = c->dec_status;
   return p;
 }
@@ -328,7 +328,8 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
       c->rows_ctl_ints = rows_control_ints(c->n_heads);
       if ((e = dev_alloc(c, &c->rows_y, (size_t)c->n_heads * c->rows_y_stride)) != hipSuccess) return bail(e, "hipMalloc(rows)");
       if ((e = hipMemset(c->rows_y, 0, (size_t)c->n_heads * c->rows_y_stride * sizeof(frag_t))) != hipSuccess) return bail(e, "memset rows");
-      if ((e = dev_alloc(c, &c->rows_partials, (size_t)2 * c->rows_grid * rmax)) != hipSuccess) return bail(e, "hipMalloc(rows)");
+      if ((e = dev_alloc(c, &c->rows_part4, (size_t)2 * c->rows_grid * rmax)) != hipSuccess) return bail(e, "hipMalloc(rows)");
+      if ((e = dev_alloc(c, &c->rows_parti, (size_t)2 * c->rows_grid * rmax)) != hipSuccess) return bail(e, "hipMalloc(rows)");
       if ((e = dev_alloc(c, &c->rows_ctl, (size_t)c->rows_ctl_ints)) != hipSuccess) return bail(e, "hipMalloc(rows)");
     } else {
       c->rows_grid = 0;
@@ -818,6 +819,14 @@ eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const i
 }
 
 #ifdef EH_DIAGNOSTICS
+// Diagnostics build: the 128 time-stamp words the last rows-kernel launch over n_heads heads left.
+extern "C" eh_status eh_rows_trace(eh_ctx* ctx, int32_t n_heads, int32_t* host_out) {
+  if (!ctx || !ctx->rows_ctl || !host_out) return EH_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  EH_HIP(ctx, hipDeviceSynchronize());
+  EH_HIP(ctx, hipMemcpy(host_out, ctx->rows_ctl + rows_control_ints(n_heads) - 128, 128 * sizeof(int), hipMemcpyDeviceToHost));
+  return EH_OK;
+}
 eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n) {
   if (!ctx) return EH_ERR_NULL;
   if (!ctx->dec_trace) return fail(ctx, EH_ERR_RANGE, "this context has no decode kernel");

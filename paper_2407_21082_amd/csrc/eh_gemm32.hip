@@ -681,79 +681,94 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_kl_kernel(
 //
 // All workgroups must be resident at once (grid = compute units, one workgroup each).
 // ---------------------------------------------------------------------------------------------
+#ifdef EH_DIAGNOSTICS
+// Diagnostics build: workgroup `who`'s first lane stamps the 100 MHz wall clock into the words
+// behind the control block (slot 2*i, 2*i+1 = low, high).
+#define EH_ROWS_STAMP(i) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || (int)blockIdx.x == p.n_stream)) { \
+    const unsigned long long t_ = wall_clock64(); int* d_ = p.ctl + rows_ctl_ints(p.l1 - p.l0) + (blockIdx.x == 0 ? 0 : 64) + 2 * (i); \
+    d_[0] = (int)(unsigned)t_; d_[1] = (int)(unsigned)(t_ >> 32); } } while (0)
+#else
+#define EH_ROWS_STAMP(i) ((void)0)
+#endif
 // All stores of this wave have been acknowledged (vector stores count in vmcnt).
 #define EH_STORES_DONE() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
 // Nothing below may be moved above a wait that has just returned.
 #define EH_AFTER_WAIT() asm volatile("" ::: "memory")
-constexpr int kRowsServiceWgs = 12;  // 3144 16-row tiles over 244 streaming workgroups: still 13 at most each
+constexpr int kRowsServiceWgs = 12;  // 3144 16-row tiles over 244 streaming workgroups: 13 at most each, as over 256
 constexpr int kRowsWords = kRowsMax / 32;
 
 // control block (ints): [0] abort; then per head (relative index j = l - l0, with two spare):
 // ready[j] (LayerNorm contributions for head j), done[j] (streaming workgroups finished),
 // decided[j] (service waves that published head j's decisions), alive[j][8] (rows entering head j);
 // then 256 words for the merged targets of a verification
-__host__ __device__ inline int rows_ctl_ints(int n_heads) { return 16 + (n_heads + 2) * (3 + kRowsWords) + kRowsMax; }
+constexpr int kSpread = 16;  // words a counter is spread over: 250 adds to one word take 6 us to drain
+__host__ __device__ inline int rows_ctl_ints(int n_heads) { return 16 + (n_heads + 2) * (3 * kSpread + 2 * kRowsWords) + kRowsMax; }
 struct RowsCtl {
   int* base;
   int nh2;  // n_heads + 2
   __device__ __forceinline__ int* abort_word() const { return base; }
-  __device__ __forceinline__ int* ready(int j) const { return base + 16 + j; }
-  __device__ __forceinline__ int* done(int j) const { return base + 16 + nh2 + j; }
-  __device__ __forceinline__ int* decided(int j) const { return base + 16 + 2 * nh2 + j; }
-  __device__ __forceinline__ int* alive(int j) const { return base + 16 + 3 * nh2 + j * kRowsWords; }
+  // counters are kSpread words each: a contributor adds to word (its index % kSpread), a waiter sums them
+  __device__ __forceinline__ int* ready(int j) const { return base + 16 + j * kSpread; }
+  __device__ __forceinline__ int* done(int j) const { return base + 16 + (nh2 + j) * kSpread; }
+  __device__ __forceinline__ int* decided(int j) const { return base + 16 + (2 * nh2 + j) * kSpread; }
+  // rows entering head j: 8 64-bit words {rows decided by head j-1 : those of them that stay}
+  __device__ __forceinline__ int* alive64(int j) const { return base + 16 + 3 * nh2 * kSpread + j * 2 * kRowsWords; }
   // verification: the merged argmax of every position
-  __device__ __forceinline__ int* target(int pos) const { return base + 16 + nh2 * (3 + kRowsWords) + pos; }
+  __device__ __forceinline__ int* target(int pos) const { return base + 16 + nh2 * (3 * kSpread + 2 * kRowsWords) + pos; }
 };
 
 __device__ __forceinline__ int ctl_load(const int* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void ctl_add(int* p, int v) { (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void ctl_add(int* counter, int who, int v) {
+  (void)__hip_atomic_fetch_add(counter + (who & (kSpread - 1)), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-// One lane waits until (*word & mask) >= target and returns the word, or -1 if the launch was
-// aborted or the wait timed out (which aborts the launch).
-__device__ __forceinline__ int rows_wait(const RowsParams& p, const RowsCtl& c, const int* word, int target,
+// A whole wave waits until the counter (the sum of its kSpread words) under `mask` reaches
+// `target`, and returns the sum; -1 if the launch was aborted or the wait timed out (which aborts
+// the launch).
+__device__ __forceinline__ int rows_wait(const RowsParams& p, const RowsCtl& c, const int* counter, int target, int lane,
                                          int mask = 0x7fffffff) {
   for (int spins = 0;; ++spins) {
-    const int v = ctl_load(word);
+    int v = lane < kSpread ? ctl_load(counter + lane) : 0;
+#pragma unroll
+    for (int x = kSpread / 2; x > 0; x >>= 1) v += __shfl_xor(v, x);
+    v = __builtin_amdgcn_readfirstlane(v);
     if ((v & mask) >= target) return v;
-    if (ctl_load(c.abort_word()) != 0) return -1;
+    if (__builtin_amdgcn_readfirstlane(ctl_load(c.abort_word())) != 0) return -1;
     if (spins >= p.spin_limit) {
-      atomicExch(p.status, 1);
-      __hip_atomic_store(c.abort_word(), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (lane == 0) {
+        atomicExch(p.status, 1);
+        __hip_atomic_store(c.abort_word(), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
       return -1;
     }
     __builtin_amdgcn_s_sleep(8);
   }
 }
-// The whole wave waits (lane 0 polls).
-__device__ __forceinline__ bool rows_wait_wave(const RowsParams& p, const RowsCtl& c, const int* word, int target, int lane) {
-  int ok = 1;
-  if (lane == 0) ok = rows_wait(p, c, word, target) >= 0 ? 1 : 0;
-  return __builtin_amdgcn_readfirstlane(ok) != 0;
-}
 
-// Device-coherent 16-byte store / Stats record store and load (no cache of another die may
-// keep serving an older copy).
+// Device-coherent accesses (no cache of another die keeps serving an older copy): 16-byte and
+// 4-byte stores, and loads that are only ISSUED here -- the caller waits (s_waitcnt vmcnt(0))
+// before it looks at the registers; the build checks that in the generated code.
 __device__ __forceinline__ void store_coherent(frag_t* dst, const frag_t& v) {
-  unsigned long long* d = (unsigned long long*)dst;
-  __hip_atomic_store(d, ((unsigned long long)v.y << 32) | v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(d + 1, ((unsigned long long)v.w << 32) | v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
 }
-__device__ __forceinline__ void store_coherent(Stats* dst, const Stats& s) {
-  unsigned* d = (unsigned*)dst;
-  __hip_atomic_store(d + 0, __float_as_uint(s.m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(d + 1, __float_as_uint(s.S), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(d + 2, __float_as_uint(s.U), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(d + 3, __float_as_uint(s.zb), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(d + 4, (unsigned)s.ib, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void store_coherent(int* dst, int v) {
+  asm volatile("global_store_dword %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
 }
-__device__ __forceinline__ Stats load_coherent(const Stats* src) {
-  const unsigned* p = (const unsigned*)src;
+__device__ __forceinline__ void issue_load_coherent(frag_t& dst, const frag_t* src) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(src) : "memory");
+}
+__device__ __forceinline__ void issue_load_coherent(int& dst, const int* src) {
+  asm volatile("global_load_dword %0, %1, off sc1" : "=v"(dst) : "v"(src) : "memory");
+}
+#define EH_LOADS_DONE() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
+// A partial statistics record travels as (m, S, U, zb) in one array and ib in another.
+__device__ __forceinline__ frag_t stats_head(const Stats& s) {
+  return mk_frag(__float_as_uint(s.m), __float_as_uint(s.S), __float_as_uint(s.U), __float_as_uint(s.zb));
+}
+__device__ __forceinline__ Stats stats_from(const frag_t& h, int ib) {
   Stats s;
-  s.m = __uint_as_float(__hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-  s.S = __uint_as_float(__hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-  s.U = __uint_as_float(__hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-  s.zb = __uint_as_float(__hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-  s.ib = (int)__hip_atomic_load(p + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  s.m = __uint_as_float(h.x); s.S = __uint_as_float(h.y); s.U = __uint_as_float(h.z); s.zb = __uint_as_float(h.w);
+  s.ib = ib;
   return s;
 }
 // 16-byte chunk c of the row at column p of an activation buffer in 32-row operand order
@@ -872,18 +887,73 @@ __device__ __forceinline__ void ring_prefetch(const frag_t* __restrict__ Wf, int
 __device__ __forceinline__ void rows_layernorm(const RowsParams& p, int l, int r, frag_t* __restrict__ yl, int pos, int lane) {
   const char* row = (const char*)p.h + ((long long)l * p.layer_stride + (long long)r * p.row_stride) * DtBf16::ESZ;
   auto put = [&](int c, const frag_t& v) { put_chunk32_coherent(yl, p.KS, pos, c, v); };
-  group_layernorm<DtBf16, 1>(row, p.d, p.KS * 4, p.gamma[l], p.beta[l], p.eps, lane, (double*)nullptr, put);
+  if (p.KS * 4 <= kLnCache * kWave)  // the row fits the wave's registers: one trip to memory, not three
+    group_layernorm_cached<DtBf16, 1>(row, p.d, p.KS * 4, p.gamma[l], p.beta[l], p.eps, lane, (double*)nullptr, put);
+  else
+    group_layernorm<DtBf16, 1>(row, p.d, p.KS * 4, p.gamma[l], p.beta[l], p.eps, lane, (double*)nullptr, put);
 }
 
 // Merge of the streaming workgroups' partial statistics of one column (one wave), in
-// finalize_kernel's order.
-__device__ __forceinline__ Stats rows_merge(const Stats* __restrict__ part, int n_parts, int R_pad, int col, int lane) {
+// finalize_kernel's order.  All records are requested before any is looked at: a device-coherent
+// load is a trip to memory, and one after the other they took 40 us per row.
+__device__ __forceinline__ Stats rows_merge(const frag_t* __restrict__ part4, const int* __restrict__ parti, int n_parts,
+                                            int R_pad, int col, int lane) {
+  constexpr int kPer = (1024 + kWave - 1) / kWave;  // records per lane at most (n_parts <= 1024)
   Stats s;
   stats_init(s);
-  for (int g = lane; g < n_parts; g += kWave) s = stats_merge(s, load_coherent(part + (long long)g * R_pad + col));
+  for (int g0 = 0; g0 < n_parts; g0 += 4 * kWave) {
+    frag_t h[4];
+    int ib[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int g = min(g0 + lane + i * kWave, n_parts - 1);
+      issue_load_coherent(h[i], part4 + (long long)g * R_pad + col);
+      issue_load_coherent(ib[i], parti + (long long)g * R_pad + col);
+    }
+    EH_LOADS_DONE();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      asm volatile("" : "+v"(h[i]), "+v"(ib[i]));
+      if (g0 + lane + i * kWave < n_parts) s = stats_merge(s, stats_from(h[i], ib[i]));
+    }
+  }
+  (void)kPer;
 #pragma unroll
   for (int x = 32; x > 0; x >>= 1) s = stats_merge(s, stats_shfl_xor(s, x));
   return s;
+}
+
+// The same for two columns at once (one wait for the records of both).
+__device__ __forceinline__ void rows_merge2(const frag_t* __restrict__ part4, const int* __restrict__ parti, int n_parts,
+                                            int R_pad, int col0, int col1, int lane, Stats& s0, Stats& s1) {
+  stats_init(s0);
+  stats_init(s1);
+  for (int g0 = 0; g0 < n_parts; g0 += 4 * kWave) {
+    frag_t h[2][4];
+    int ib[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int g = min(g0 + lane + i * kWave, n_parts - 1);
+      issue_load_coherent(h[0][i], part4 + (long long)g * R_pad + col0);
+      issue_load_coherent(ib[0][i], parti + (long long)g * R_pad + col0);
+      issue_load_coherent(h[1][i], part4 + (long long)g * R_pad + col1);
+      issue_load_coherent(ib[1][i], parti + (long long)g * R_pad + col1);
+    }
+    EH_LOADS_DONE();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      asm volatile("" : "+v"(h[0][i]), "+v"(ib[0][i]), "+v"(h[1][i]), "+v"(ib[1][i]));
+      if (g0 + lane + i * kWave < n_parts) {
+        s0 = stats_merge(s0, stats_from(h[0][i], ib[0][i]));
+        s1 = stats_merge(s1, stats_from(h[1][i], ib[1][i]));
+      }
+    }
+  }
+#pragma unroll
+  for (int x = 32; x > 0; x >>= 1) {
+    s0 = stats_merge(s0, stats_shfl_xor(s0, x));
+    s1 = stats_merge(s1, stats_shfl_xor(s1, x));
+  }
 }
 
 // Returns false if the launch was aborted (or every row has left).
@@ -893,6 +963,27 @@ __device__ __forceinline__ bool rows_stream(const RowsParams& p, const RowsCtl& 
   const int g = blockIdx.x, tid = threadIdx.x;
   const int nh = p.l1 - p.l0;
   const int nsw = ((int)gridDim.x - p.n_stream) * kG32Waves;  // service waves
+  // my slice of the vocabulary, in 16-row tiles (bytes balanced: the stream paces these shapes)
+  const int T0 = (int)((long long)p.VT16 * g / p.n_stream);
+  const int T1 = (int)((long long)p.VT16 * (g + 1) / p.n_stream);
+  const int row_hi = min(p.V, T1 * 16);
+  const int mt_first = T0 < T1 ? (((T1 - T0 + 1) >> 1) + (((T1 - T0 + 1) >> 1) + kMaxMT - 1) / kMaxMT - 1) / ((((T1 - T0 + 1) >> 1) + kMaxMT - 1) / kMaxMT) : 0;
+  // tiles per pass of a head's first pass; its first weights are brought towards the L2 while
+  // something else is going on (here: the LayerNorm of the first head)
+  auto warm = [&](const frag_t* Wn) {
+    switch (mt_first) {
+      case 7: ring_prefetch<7>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+      case 6: ring_prefetch<6>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+      case 5: ring_prefetch<5>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+      case 4: ring_prefetch<4>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+      case 3: ring_prefetch<3>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+      case 2: ring_prefetch<2>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+      case 1: ring_prefetch<1>(Wn, T0, T1, p.KS, lane, wave, lds); break;
+      default: break;
+    }
+  };
+  EH_ROWS_STAMP(0);
+  warm(p.Wf[p.l0]);
   // LayerNorm of the first head's rows, spread over the streaming workgroups (four waves per row)
   for (int r = g; r < p.n_rows; r += p.n_stream) {
     const char* row = (const char*)p.h + ((long long)p.l0 * p.layer_stride + (long long)r * p.row_stride) * DtBf16::ESZ;
@@ -905,19 +996,20 @@ __device__ __forceinline__ bool rows_stream(const RowsParams& p, const RowsCtl& 
   }
   EH_STORES_DONE();
   __syncthreads();
-  if (tid == 0) ctl_add(c.ready(0), 1);
-  // my slice of the vocabulary, in 16-row tiles (bytes balanced: the stream paces these shapes)
-  const int T0 = (int)((long long)p.VT16 * g / p.n_stream);
-  const int T1 = (int)((long long)p.VT16 * (g + 1) / p.n_stream);
-  const int row_hi = min(p.V, T1 * 16);
+  if (tid == 0) ctl_add(c.ready(0), g, 1);
+  EH_ROWS_STAMP(1);
   // the first head's activations are complete when every streaming workgroup has written its rows
-  if (tid == 0) *flag = rows_wait(p, c, c.ready(0), p.n_stream);
+  if (wave == 0) {
+    const int v = rows_wait(p, c, c.ready(0), p.n_stream, lane);
+    if (lane == 0) *flag = v;
+  }
   __syncthreads();
   int word = *flag;
   __syncthreads();
   if (word < 0) return false;
   EH_AFTER_WAIT();
   int ncols = p.n_rows;
+  EH_ROWS_STAMP(2);
   for (int j = 0; j < nh; ++j) {
     const int l = p.l0 + j;
     if (ncols == 0) return false;  // every row has left: the same for all workgroups
@@ -951,35 +1043,30 @@ __device__ __forceinline__ bool rows_stream(const RowsParams& p, const RowsCtl& 
 #undef EH_ROWS_PASS
       t += 2 * mt;
     }
-    Stats* part = p.partials + (long long)(j & 1) * p.n_stream * p.R_pad + (long long)g * p.R_pad;
+    if (j < 8) EH_ROWS_STAMP(3 + 2 * j);
+    const long long part_at = (long long)(j & 1) * p.n_stream * p.R_pad + (long long)g * p.R_pad;
 #pragma unroll
     for (int n = 0; n < 2; ++n) {
       st[n] = stats_merge(st[n], stats_shfl_xor(st[n], 32));  // lanes l and l+32 hold the same token
-      if (lane < 32 && n < nb_live) store_coherent(part + (nb_first + n) * 32 + lane, st[n]);
+      if (lane < 32 && n < nb_live) {
+        store_coherent(p.part4 + part_at + (nb_first + n) * 32 + lane, stats_head(st[n]));
+        store_coherent(p.parti + part_at + (nb_first + n) * 32 + lane, st[n].ib);
+      }
     }
     if (j + 1 < nh) {
       // while those stores travel: warm the L2 with the start of the next head's weights, and look
       // whether the next head's activations are there (they have been for a while, as a rule).
       // Heads from the third on carry their column count in the upper bits of the counter.
-      if (T0 < T1) {
-        const int left = (T1 - T0 + 1) >> 1;
-        const int mt = (left + (left + kMaxMT - 1) / kMaxMT - 1) / ((left + kMaxMT - 1) / kMaxMT);
-        const frag_t* Wn = p.Wf[l + 1];
-        switch (mt) {
-          case 7: ring_prefetch<7>(Wn, T0, T1, p.KS, lane, wave, lds); break;
-          case 6: ring_prefetch<6>(Wn, T0, T1, p.KS, lane, wave, lds); break;
-          case 5: ring_prefetch<5>(Wn, T0, T1, p.KS, lane, wave, lds); break;
-          case 4: ring_prefetch<4>(Wn, T0, T1, p.KS, lane, wave, lds); break;
-          case 3: ring_prefetch<3>(Wn, T0, T1, p.KS, lane, wave, lds); break;
-          case 2: ring_prefetch<2>(Wn, T0, T1, p.KS, lane, wave, lds); break;
-          default: ring_prefetch<1>(Wn, T0, T1, p.KS, lane, wave, lds); break;
-        }
+      warm(p.Wf[l + 1]);
+      if (wave == 0) {
+        const int v = rows_wait(p, c, c.ready(j + 1), nsw, lane, 0xff);
+        if (lane == 0) *flag = v;
       }
-      if (tid == 0) *flag = rows_wait(p, c, c.ready(j + 1), nsw, 0xff);
     }
     EH_STORES_DONE();
     __syncthreads();
-    if (tid == 0) ctl_add(c.done(j), 1);
+    if (tid == 0) ctl_add(c.done(j), g, 1);
+    if (j < 8) EH_ROWS_STAMP(4 + 2 * j);
     if (j + 1 < nh) {
       word = *flag;
       __syncthreads();  // the flag is rewritten at the end of the next head
@@ -991,33 +1078,139 @@ __device__ __forceinline__ bool rows_stream(const RowsParams& p, const RowsCtl& 
   return true;
 }
 
+// LayerNorm of one row by one wave from operands fetched earlier (raw: the row's 16-byte chunks
+// lane + 64*i; gam / bet: gamma and beta of the same chunks), in group_layernorm_cached's order.
+constexpr int kSvcChunks = kLnCache;  // chunks of a row per lane: d <= 8 * 64 * 8
+struct SvcRow {
+  frag_t raw[kSvcChunks];
+};
+__device__ __forceinline__ void svc_load_row(const RowsParams& p, int l, int r, int lane, SvcRow& out) {
+  const char* row = (const char*)p.h + ((long long)l * p.layer_stride + (long long)r * p.row_stride) * DtBf16::ESZ;
+  const int live_chunks = p.d / DtBf16::EPL;
+#pragma unroll
+  for (int i = 0; i < kSvcChunks; ++i) {
+    const int c = lane + i * kWave;
+    out.raw[i] = mk_frag(0, 0, 0, 0);
+    if (c < live_chunks) out.raw[i] = *(const frag_t*)(row + (long long)c * 16);
+  }
+}
+// The row's normalised chunks replace the raw ones in `row` (chunk lane + 64*i; zero beyond d).
+__device__ __forceinline__ void svc_layernorm(const RowsParams& p, int l, SvcRow& row, int lane) {
+  const int live_chunks = p.d / DtBf16::EPL, n_chunks = p.KS * 4;
+  const float* __restrict__ gamma = p.gamma[l];
+  const float* __restrict__ beta = p.beta[l];
+  double s = 0.0;
+#pragma unroll
+  for (int i = 0; i < kSvcChunks; ++i) {
+    if (lane + i * kWave < live_chunks) {
+      float x[8];
+      decode_elems<DtBf16>(row.raw[i], x);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += (double)x[e];
+    }
+  }
+  const double mu = wave_sum(s) / (double)p.d;
+  double v = 0.0;
+#pragma unroll
+  for (int i = 0; i < kSvcChunks; ++i) {
+    if (lane + i * kWave < live_chunks) {
+      float x[8];
+      decode_elems<DtBf16>(row.raw[i], x);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const double cdev = (double)x[e] - mu;
+        v += cdev * cdev;
+      }
+    }
+  }
+  const double rstd = 1.0 / sqrt(wave_sum(v) / (double)p.d + (double)p.eps);
+#pragma unroll
+  for (int i = 0; i < kSvcChunks; ++i) {
+    const int c = lane + i * kWave;
+    if (c < n_chunks) {
+      frag_t o = mk_frag(0, 0, 0, 0);
+      if (c < live_chunks) {
+        float x[8];
+        decode_elems<DtBf16>(row.raw[i], x);
+        // gamma and beta start on 256-byte boundaries (allocations of the context)
+        const f32x4 g0 = *(const f32x4*)(gamma + c * 8), g1 = *(const f32x4*)(gamma + c * 8 + 4);
+        const f32x4 b0 = *(const f32x4*)(beta + c * 8), b1 = *(const f32x4*)(beta + c * 8 + 4);
+        double y[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          y[e] = (double)g0[e] * (((double)x[e] - mu) * rstd) + (double)b0[e];
+          y[e + 4] = (double)g1[e] * (((double)x[e + 4] - mu) * rstd) + (double)b1[e];
+        }
+        o = pack_elems<DtBf16>(y);
+      }
+      row.raw[i] = o;
+    }
+  }
+}
+// Writes a row normalised by svc_layernorm to column `pos` of an activation buffer.
+__device__ __forceinline__ void svc_store(const RowsParams& p, const SvcRow& row, frag_t* __restrict__ yl, int pos, int lane) {
+  const int n_chunks = p.KS * 4;
+#pragma unroll
+  for (int i = 0; i < kSvcChunks; ++i) {
+    const int c = lane + i * kWave;
+    if (c < n_chunks) put_chunk32_coherent(yl, p.KS, pos, c, row.raw[i]);
+  }
+}
+
 // Service waves of a cascade (mode 0).  sw = index of this wave among the nsw service waves; it
-// owns the rows r = sw, sw + nsw, ...
+// owns the rows r = sw, sw + nsw, ...  A head's turn is a chain of trips to memory (partial
+// statistics in, decisions out, everybody's decisions in, activations out), and the streaming
+// workgroups wait if it takes longer than a head's stream, so: the LayerNorm of head l+2 is computed for the wave's (first two) live rows
+// BEFORE the wait for head l's statistics -- it does not depend on them, only whether and where it is
+// stored does -- all
+// partial records of (up to two) rows are requested at once, and a row's decision travels as one
+// 64-bit word {decided | stays} so that no second counter is needed.
 __device__ __forceinline__ void rows_serve_cascade(const RowsParams& p, const RowsCtl& c, int lane, int sw, int nsw) {
   const int nh = p.l1 - p.l0;
+  const bool fits = p.KS * 4 <= kSvcChunks * kWave;  // a row fits one wave's registers
   // the second head's activations for every row (identity columns); the first head's are
   // written by the streaming workgroups
   if (nh > 1) {
     for (int r = sw; r < p.n_rows; r += nsw) rows_layernorm(p, p.l0 + 1, r, p.y + p.y_stride, r, lane);
     EH_STORES_DONE();
-    if (lane == 0) ctl_add(c.ready(1), 1);
+    if (lane == 0) ctl_add(c.ready(1), sw, 1);
   }
   RowMask cols, alive;  // columns of head j (rows alive after head j-2), rows entering head j
   cols.set_all(p.n_rows);
   alive.set_all(p.n_rows);
+  const int r0 = sw, r1 = sw + nsw;  // the two rows of the fast path
   for (int j = 0; j < nh; ++j) {
     const int l = p.l0 + j;
     const bool last = l == p.n_heads - 1;
-    if (!rows_wait_wave(p, c, c.done(j), p.n_stream, lane)) return;
+    const bool more = !last && j + 2 < nh;  // head j+2 exists: its LayerNorm is this turn's job
+    const bool a0 = r0 < p.n_rows && alive.test(r0), a1 = r1 < p.n_rows && alive.test(r1);
+    SvcRow row0, row1;
+    if (j == 2) EH_ROWS_STAMP(6);
+    if (more && fits) {
+      if (a0) svc_load_row(p, l + 2, r0, lane, row0);
+      if (a1) svc_load_row(p, l + 2, r1, lane, row1);
+      if (a0) svc_layernorm(p, l + 2, row0, lane);
+      if (a1) svc_layernorm(p, l + 2, row1, lane);
+    }
+    if (j == 2) EH_ROWS_STAMP(0);
+    if (rows_wait(p, c, c.done(j), p.n_stream, lane) < 0) return;
     EH_AFTER_WAIT();
-    const Stats* part = p.partials + (long long)(j & 1) * p.n_stream * p.R_pad;
+    if (j == 2) EH_ROWS_STAMP(1);
+    const long long part_at = (long long)(j & 1) * p.n_stream * p.R_pad;
     const float tau = p.tau[l];
-    RowMask stay;
+    RowMask stay, mine;  // rows of mine that go on / that were decided this turn
     stay.set_all(0);
+    mine.set_all(0);
     int evals = 0;
-    for (int r = sw; r < p.n_rows; r += nsw) {
+    Stats s01[2];
+    const bool both = a0 && a1;  // the first two rows together: one trip to memory for both
+    if (both)
+      rows_merge2(p.part4 + part_at, p.parti + part_at, p.n_stream, p.R_pad, cols.rank(r0), cols.rank(r1), lane, s01[0], s01[1]);
+    for (int r = sw, k = 0; r < p.n_rows; r += nsw, ++k) {
       if (!alive.test(r)) continue;
-      const Stats s = rows_merge(part, p.n_stream, p.R_pad, cols.rank(r), lane);
+      Stats s;
+      if (both && k < 2) s = s01[k];
+      else s = rows_merge(p.part4 + part_at, p.parti + part_at, p.n_stream, p.R_pad, cols.rank(r), lane);
       float H, lse;
       stats_finalize(s, H, lse);
       ++evals;
@@ -1029,38 +1222,67 @@ __device__ __forceinline__ void rows_serve_cascade(const RowsParams& p, const Ro
           p.token[r] = stats_token(s);
         }
       }
-      if (!leaves) {
 #pragma unroll
-        for (int i = 0; i < kRowsWords; ++i)
-          if (i == (r >> 5)) stay.w[i] |= 1u << (r & 31);
+      for (int i = 0; i < kRowsWords; ++i) {
+        if (i == (r >> 5)) {
+          mine.w[i] |= 1u << (r & 31);
+          if (!leaves) stay.w[i] |= 1u << (r & 31);
+        }
       }
     }
     if (lane == 0 && evals && p.n_evals) atomicAdd(p.n_evals, (unsigned long long)evals);
+    if (j == 2) EH_ROWS_STAMP(2);
     if (last || j + 1 == nh) return;
-    // publish who goes on, wait for everybody's word, then prepare head j+2 for the survivors
+    // publish: one 64-bit word per 32 rows, {decided rows : rows that stay}, so a reader that sees
+    // a row decided sees whether it stays
+    unsigned long long* words = (unsigned long long*)c.alive64(j + 1);
     if (lane == 0) {
 #pragma unroll
       for (int i = 0; i < kRowsWords; ++i)
-        if (stay.w[i]) (void)__hip_atomic_fetch_or(c.alive(j + 1) + i, (int)stay.w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (mine.w[i])
+          (void)__hip_atomic_fetch_or(words + i, ((unsigned long long)mine.w[i] << 32) | stay.w[i], __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
     }
-    EH_STORES_DONE();  // the mask words above are atomics of lane 0: performed before the counter
-    if (lane == 0) ctl_add(c.decided(j), 1);
-    if (!rows_wait_wave(p, c, c.decided(j), nsw, lane)) return;
-    EH_AFTER_WAIT();
+    // wait until every row that entered this head has been decided
     RowMask next;
-    next.load(c.alive(j + 1));
+    for (int spins = 0;; ++spins) {
+      unsigned long long v = 0;
+      if (lane < kRowsWords) v = __hip_atomic_load(words + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      bool okw = true;
+#pragma unroll
+      for (int i = 0; i < kRowsWords; ++i) {
+        const unsigned long long vi = __shfl(v, i);
+        next.w[i] = (unsigned)vi;
+        okw = okw && ((unsigned)(vi >> 32) == alive.w[i]);
+      }
+      if (okw) break;
+      if (__builtin_amdgcn_readfirstlane(ctl_load(c.abort_word())) != 0) return;
+      if (spins >= p.spin_limit) {
+        if (lane == 0) {
+          atomicExch(p.status, 1);
+          __hip_atomic_store(c.abort_word(), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+      }
+      __builtin_amdgcn_s_sleep(4);
+    }
+    EH_AFTER_WAIT();
+    if (j == 2) EH_ROWS_STAMP(3);
     if (j + 2 < nh) {
       frag_t* yl = p.y + (long long)(j + 2) * p.y_stride;
-      int mine = 0;
+      int written = 0;
       for (int r = sw; r < p.n_rows; r += nsw) {
-        if (next.test(r)) {
-          rows_layernorm(p, l + 2, r, yl, next.rank(r), lane);
-          ++mine;
-        }
+        if (!next.test(r)) continue;
+        if (fits && r == r0) svc_store(p, row0, yl, next.rank(r), lane);
+        else if (fits && r == r1) svc_store(p, row1, yl, next.rank(r), lane);
+        else rows_layernorm(p, l + 2, r, yl, next.rank(r), lane);
+        ++written;
       }
+      if (j == 2) EH_ROWS_STAMP(4);
       EH_STORES_DONE();
+      if (j == 2) EH_ROWS_STAMP(5);
       // low byte: service waves done; above it: the columns written (their sum is the head's column count)
-      if (lane == 0) ctl_add(c.ready(j + 2), 1 + (mine << 8));
+      if (lane == 0) ctl_add(c.ready(j + 2), sw, 1 + (written << 8));
     }
     if (next.count() == 0) return;  // the same masks in every service wave
     cols = alive;
@@ -1074,18 +1296,35 @@ __device__ __forceinline__ void rows_serve_cascade(const RowsParams& p, const Ro
 __device__ __forceinline__ void rows_verify_tail(const RowsParams& p, const RowsCtl& c, int lane, int wave, int* flag,
                                                  float* red_z, int* red_i) {
   const int g = blockIdx.x, tid = threadIdx.x;
-  if (tid == 0) *flag = rows_wait(p, c, c.done(0), p.n_stream) >= 0 ? 1 : 0;
+  if (wave == 0) {
+    const int v = rows_wait(p, c, c.done(0), p.n_stream, lane);
+    if (lane == 0) *flag = v >= 0 ? 1 : 0;
+  }
   __syncthreads();
   int ok = *flag;
   __syncthreads();
   if (!ok) return;
   EH_AFTER_WAIT();
+  EH_ROWS_STAMP(20);
   for (int pos = g; pos < p.n_rows; pos += p.n_stream) {
     float zb = -INFINITY;
     int ib = 0x7fffffff;
-    for (int q = tid; q < p.n_stream; q += kG32Threads) {
-      const Stats r = load_coherent(p.partials + (long long)q * p.R_pad + pos);
-      if (r.zb > zb || (r.zb == zb && r.ib < ib)) { zb = r.zb; ib = r.ib; }
+    for (int q0 = 0; q0 < p.n_stream; q0 += 4 * kG32Threads) {  // all records requested before any is used
+      frag_t h[4];
+      int ri[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int q = min(q0 + tid + i * kG32Threads, p.n_stream - 1);
+        issue_load_coherent(h[i], p.part4 + (long long)q * p.R_pad + pos);
+        issue_load_coherent(ri[i], p.parti + (long long)q * p.R_pad + pos);
+      }
+      EH_LOADS_DONE();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        asm volatile("" : "+v"(h[i]), "+v"(ri[i]));
+        const float rz = __uint_as_float(h[i].w);
+        if (q0 + tid + i * kG32Threads < p.n_stream && (rz > zb || (rz == zb && ri[i] < ib))) { zb = rz; ib = ri[i]; }
+      }
     }
 #pragma unroll
     for (int x = 32; x > 0; x >>= 1) {
@@ -1103,19 +1342,36 @@ __device__ __forceinline__ void rows_verify_tail(const RowsParams& p, const Rows
       __hip_atomic_store(c.target(pos), t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (p.target) p.target[pos] = t;
       EH_STORES_DONE();
-      ctl_add(c.decided(0), 1);
+      ctl_add(c.decided(0), pos, 1);
     }
     __syncthreads();
   }
-  if (g < p.B && tid == 0) {
-    if (rows_wait(p, c, c.decided(0), p.n_rows) < 0) return;
+  EH_ROWS_STAMP(21);
+  if (g < p.B && wave == 0) {
+    // the first wave walks draft row g's prefix: all targets are fetched at once (one device-scope
+    // round trip per 64 positions, not one per position), the first mismatch is a ballot away
+    if (rows_wait(p, c, c.decided(0), p.n_rows, lane) < 0) return;
     EH_AFTER_WAIT();
     int len = p.k;
     if (p.draft_len) len = min(max(p.draft_len[g], 0), p.k);
-    int n = 0;
-    while (n < len && p.draft[(long long)g * p.k + n] == ctl_load(c.target(g * (p.k + 1) + n))) ++n;
-    p.accepted[g] = n;
-    p.next_token[g] = ctl_load(c.target(g * (p.k + 1) + n));
+    for (int j0 = 0; j0 <= p.k; j0 += kWave) {
+      const int j = j0 + lane;
+      int t = 0, d = -1;
+      if (j <= p.k) t = ctl_load(c.target(g * (p.k + 1) + j));
+      if (j < len) d = p.draft[(long long)g * p.k + j];
+      const bool stop = j <= p.k && !(j < len && d == t);  // position j is not an accepted draft token
+      const unsigned long long m = __ballot(stop);
+      if (m) {  // the prefix ends in this group of positions (position k always stops)
+        const int first = __builtin_ctzll(m);
+        const int tok = __shfl(t, first);
+        if (lane == 0) {
+          p.accepted[g] = j0 + first;
+          p.next_token[g] = tok;
+        }
+        EH_ROWS_STAMP(22);
+        break;
+      }
+    }
   }
 }
 
@@ -1246,10 +1502,10 @@ hipError_t rows_prepare(eh_ctx* c) {
 
 hipError_t rows_launch(const eh_ctx* c, const RowsParams& p, hipStream_t s) {
   // every pointer the kernel dereferences unconditionally, and the sizes its indexing assumes
-  if (!p.status || !p.ctl || !p.y || !p.partials || !p.Wf || !p.gamma || !p.beta || !p.tau || !p.h) return hipErrorInvalidValue;
-  if (c->rows_grid <= kRowsServiceWgs || p.n_stream != (p.mode == 0 ? c->rows_grid - kRowsServiceWgs : c->rows_grid)) return hipErrorInvalidValue;
+  if (!p.status || !p.ctl || !p.y || !p.part4 || !p.parti || !p.Wf || !p.gamma || !p.beta || !p.tau || !p.h) return hipErrorInvalidValue;
+  if (c->rows_grid <= kRowsServiceWgs || p.n_stream != (p.mode == 0 ? c->rows_grid - rows_service_workgroups(p.n_rows) : c->rows_grid)) return hipErrorInvalidValue;
   if (p.n_rows < 1 || p.n_rows > kRowsMax || p.R_pad < p.n_rows || p.R_pad % 32 != 0) return hipErrorInvalidValue;
-  if (p.l0 < 0 || p.l1 <= p.l0 || p.l1 > p.n_heads || rows_ctl_ints(p.l1 - p.l0) > c->rows_ctl_ints) return hipErrorInvalidValue;
+  if (p.l0 < 0 || p.l1 <= p.l0 || p.l1 > p.n_heads || rows_ctl_ints(p.l1 - p.l0) + 128 > c->rows_ctl_ints) return hipErrorInvalidValue;
   if ((long long)(p.R_pad / 16 + 32) * p.KS * kWave > p.y_stride) return hipErrorInvalidValue;  // one buffer per head
   if (p.mode == 0 ? (!p.exit_layer || !p.token) : (!p.accepted || !p.next_token || (p.k > 0 && !p.draft) || p.B * (p.k + 1) != p.n_rows))
     return hipErrorInvalidValue;
@@ -1266,8 +1522,8 @@ hipError_t rows_launch(const eh_ctx* c, const RowsParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-int rows_control_ints(int n_heads) { return rows_ctl_ints(n_heads); }
-int rows_service_workgroups() { return kRowsServiceWgs; }
+int rows_control_ints(int n_heads) { return rows_ctl_ints(n_heads) + 128; }  // + 128 words of time stamps (diagnostics build)
+int rows_service_workgroups(int) { return kRowsServiceWgs; }
 
 hipError_t gemm32_kl_launch(const eh_ctx* c, int head, int model_head, int n_rows, const frag_t* yf_head,
                             const frag_t* yf_model, const int* labels, KlStats* partials, int* n_parts,

@@ -62,7 +62,8 @@ struct eh_ctx {
   int rows_ctl_ints = 0;
   eh::frag_t* rows_y = nullptr;        // [n_heads][rows_y_stride] activations, one buffer per head
   long long rows_y_stride = 0;         // fragments
-  eh::Stats* rows_partials = nullptr;  // [2][rows_grid][256] partial statistics of two consecutive heads
+  eh::frag_t* rows_part4 = nullptr;    // [2][rows_grid][256] partial statistics of two consecutive heads: (m, S, U, zb)
+  int* rows_parti = nullptr;           // [2][rows_grid][256]: ib
   void* static_scratch = nullptr;  // device address of the library's static workspace on this device
   std::vector<void*> allocs;
   std::string err = "";
@@ -117,7 +118,8 @@ struct RowsParams {
   int* ctl;                     // control block, all zero at launch
   frag_t* y;                    // [l1 - l0][y_stride]: one buffer per head of the launch
   long long y_stride;
-  Stats* partials;              // [2][n_stream][R_pad]
+  frag_t* part4;                // [2][n_stream][R_pad]: (m, S, U, zb) of the partial statistics of two consecutive heads
+  int* parti;                   // [2][n_stream][R_pad]: their ib
   int R_pad;
   int* status;
   int* exit_layer;              // mode 0 outputs
@@ -136,7 +138,7 @@ hipError_t rows_prepare(eh_ctx* ctx);
 // Enqueues the preset of outputs and control block, then the kernel.
 hipError_t rows_launch(const eh_ctx* ctx, const RowsParams& p, hipStream_t s);
 int rows_control_ints(int n_heads);   // size of the control block for a launch over n_heads heads
-int rows_service_workgroups();       // workgroups of the grid that do not stream
+int rows_service_workgroups(int n_rows);  // workgroups of a cascade's grid that do not stream
 
 // Sets up the decode kernel for this context (grid, LDS size, function
 // attributes).  Leaves ctx->decode_grid = 0 if the shape does not fit.
