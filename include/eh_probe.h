@@ -9,7 +9,8 @@
  * and 4.3.1, which stream every head's weights once), and the matrix-core
  * instruction stream of the batched kernel on registers only (the bound of the
  * calibration pass of Section 3.4.1).  They compute nothing of the method and are
- * called by bench.py only.  Conventions as in eh.h: status codes, asynchronous on
+ * called by bench.py only; a third entry point reports how often eh_calibrate had to
+ * fall back to its full sort, for the tests and the bench line of that call.  Conventions as in eh.h: status codes, asynchronous on
  * `stream`, device pointers on the context's device.
  */
 #ifndef EH_PROBE_H_
@@ -52,6 +53,14 @@ eh_status eh_probe_read_weights(eh_ctx* ctx, int32_t how, int32_t per_head, int3
  */
 eh_status eh_probe_mfma(eh_ctx* ctx, int32_t iters, int32_t random_operands, float* sink, double* flops_out,
                         void* stream);
+
+/*
+ * calls_out    host: the number of eh_calibrate calls on this context so far that the
+ *              refinement by counting could not serve (its tables of kept bins were too
+ *              small for the data, or EH_CALIBRATE_SORT=1 is set in the environment) and
+ *              that the full sort answered instead.  Either way the results are the same.
+ */
+eh_status eh_probe_calibrate_sorted(eh_ctx* ctx, int64_t* calls_out);
 
 #ifdef __cplusplus
 }

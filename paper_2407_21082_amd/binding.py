@@ -25,7 +25,7 @@ STATUS_NAMES = {0: "EH_OK", 1: "EH_ERR_NULL", 2: "EH_ERR_SHAPE", 3: "EH_ERR_DTYP
 EXPORTS = ["eh_create", "eh_destroy", "eh_eval", "eh_eval_noalloc", "eh_eval_heads", "eh_eval_heads_metrics", "eh_exit_decide", "eh_cascade", "dssd_verify", "dssd_draft", "dssd_tally", "eh_head_losses",
            "eh_calibrate", "eh_check", "eh_set_spin_limit", "eh_last_error", "eh_version"]
 # the measurement entry points include/eh_probe.h declares
-PROBE_EXPORTS = ["eh_probe_read_weights", "eh_probe_mfma"]
+PROBE_EXPORTS = ["eh_probe_read_weights", "eh_probe_mfma", "eh_probe_calibrate_sorted"]
 
 
 class EhError(RuntimeError):
@@ -276,6 +276,13 @@ def eh_probe_mfma(ctx: EhContext, iters: int, random_operands: bool, sink: torch
     _check(lib.eh_probe_mfma(ctx.handle, iters, 1 if random_operands else 0, _ptr(sink), C.byref(f),
                              _stream(stream)), ctx.handle)
     return f.value
+
+
+def eh_probe_calibrate_sorted(ctx: EhContext) -> int:
+    """How many eh_calibrate calls on this context the full sort had to serve."""
+    n = C.c_int64(0)
+    _check(lib.eh_probe_calibrate_sorted(ctx.handle, C.byref(n)), ctx.handle)
+    return n.value
 
 
 def dssd_verify(ctx: EhContext, f_final: torch.Tensor, draft: torch.Tensor,

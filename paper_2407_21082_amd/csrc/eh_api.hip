@@ -94,6 +94,7 @@ void free_all(eh_ctx* ctx) {
   for (void* p : ctx->allocs) (void)hipFree(p);
   ctx->allocs.clear();
   if (ctx->calib.buf) (void)hipFree(ctx->calib.buf);
+  if (ctx->calib.host_flag) (void)hipHostFree(ctx->calib.host_flag);
   ctx->calib = CalibScratch();
 }
 

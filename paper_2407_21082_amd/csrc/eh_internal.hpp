@@ -12,6 +12,8 @@
 struct CalibScratch {
   void* buf = nullptr;
   size_t bytes = 0;
+  int* host_flag = nullptr;   // pinned: the refinement's "tables too small" word
+  long long n_sorted = 0;     // calls that the full sort served
 };
 
 struct eh_ctx {

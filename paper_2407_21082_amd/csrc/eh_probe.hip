@@ -228,4 +228,10 @@ eh_status eh_probe_mfma(eh_ctx* ctx, int32_t iters, int32_t random_operands, flo
   return EH_OK;
 }
 
+eh_status eh_probe_calibrate_sorted(eh_ctx* ctx, int64_t* calls_out) {
+  if (!ctx || !calls_out) return EH_ERR_NULL;
+  *calls_out = (int64_t)ctx->calib.n_sorted;
+  return EH_OK;
+}
+
 }  // extern "C"

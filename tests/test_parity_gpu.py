@@ -430,6 +430,78 @@ def test_calibrate_matches_oracle(B, small_ctx, M, ties, nan_every):
         assert (tau[i] == np.float32(want_tau)) and int(n[i]) == want_n, (M, e, tau[i], want_tau, n[i], want_n)
 
 
+@pytest.mark.parametrize("M,ties,nan_every", [(257, False, 0), (3000, True, 5), (40000, False, 11)])
+def test_calibrate_by_sorting_gives_the_same(B, small_ctx, M, ties, nan_every, monkeypatch):
+    """eh_calibrate has two ways to the same answer: counting in three levels of bins, and,
+    for data whose proportion hovers at a level over many bins, a full sort.  The sort is
+    forced here (the library reads EH_CALIBRATE_SORT at every call) and held to the oracle,
+    and to what the call returns without it, bit for bit."""
+    H, pred, ref = G.make_calibration_case(M, DEV, seed=M + 1, V=50, ties=ties, nan_every=nan_every)
+    eps = [0.0, 0.01] + EPS_SWEEP
+    before = B.eh_probe_calibrate_sorted(small_ctx)
+    tau, n = _calibrate(B, small_ctx, H, pred, ref, eps)
+    mid = B.eh_probe_calibrate_sorted(small_ctx)
+    monkeypatch.setenv("EH_CALIBRATE_SORT", "1")
+    tau_s, n_s = _calibrate(B, small_ctx, H, pred, ref, eps)
+    monkeypatch.delenv("EH_CALIBRATE_SORT")
+    assert B.eh_probe_calibrate_sorted(small_ctx) == mid + 1 and mid - before in (0, 1)
+    np.testing.assert_array_equal(tau, tau_s)
+    np.testing.assert_array_equal(n, n_s)
+    if M <= 3000:
+        Hc = H.cpu().numpy().astype(np.float64)
+        t = O.correctness(pred.cpu().numpy(), ref.cpu().numpy())
+        for i, e in enumerate(eps):
+            want_tau, want_n = O.calibrate_threshold(Hc, t, e)
+            assert (tau_s[i] == np.float32(want_tau)) and int(n_s[i]) == want_n, (M, e, tau_s[i], want_tau)
+
+
+def _calibrate_by_counting(H, t, eps):
+    """The definition by exact counting (tokens and correct tokens at or below every distinct
+    entropy value, from sorted arrays): the unique answer for every level, at any size."""
+    ok = ~np.isnan(H)
+    vals, inv = np.unique(H[ok], return_inverse=True)                      # ascending entropy values
+    cnt = np.bincount(inv, minlength=len(vals)).cumsum()                   # tokens with H <= value
+    cor = np.bincount(inv, weights=t[ok], minlength=len(vals)).cumsum()    # correct ones among them
+    out = []
+    for e in eps:
+        good = cor / cnt >= e                                              # the section's quotient, in double
+        if not good.any():
+            out.append((-np.inf, 0))
+        else:
+            k = np.nonzero(good)[0].max()                                  # largest qualifying value
+            out.append((np.float32(vals[k]), int(cnt[k])))
+    return out
+
+
+@pytest.mark.parametrize("spread", ["uniform", "one_binade", "wide"])
+def test_calibrate_hovering_proportion(B, small_ctx, spread):
+    """Predictions that are right half of the time whatever the entropy: at the level 0.5 the
+    proportion stays within a hair of the level over the whole range of thresholds, which is
+    what the counting refinement cannot prune.  The call must still return the exact answer
+    (the full sort serves it), and levels away from 0.5 must not need the sort."""
+    M = 1 << 18
+    gen = torch.Generator(device=DEV).manual_seed(77)
+    u = torch.rand(M, generator=gen, device=DEV)
+    if spread == "uniform":
+        H = u * 8.0
+    elif spread == "one_binade":
+        H = 4.0 + u * 3.9
+    else:
+        H = torch.exp(u * 60.0 - 50.0)
+    H = H.to(torch.float32).contiguous()
+    ref = torch.zeros(M, dtype=torch.int32, device=DEV)
+    pred = (torch.rand(M, generator=gen, device=DEV) < 0.5).to(torch.int32)
+    Hc = H.cpu().numpy().astype(np.float64)
+    t = O.correctness(pred.cpu().numpy(), ref.cpu().numpy())
+    for eps, may_sort in (([0.5, 0.4999, 0.5001], True), ([0.3, 0.45, 0.55, 0.9, 1.0], False)):
+        before = B.eh_probe_calibrate_sorted(small_ctx)
+        tau, n = _calibrate(B, small_ctx, H, pred, ref, eps)
+        sorted_calls = B.eh_probe_calibrate_sorted(small_ctx) - before
+        assert may_sort or sorted_calls == 0, (spread, eps)
+        for i, (want_tau, want_n) in enumerate(_calibrate_by_counting(Hc, t, eps)):
+            assert tau[i] == want_tau and n[i] == want_n, (spread, eps[i], tau[i], want_tau, n[i], want_n)
+
+
 def test_calibrate_degenerate_inputs(B, small_ctx):
     H = torch.tensor([0.5, 0.25, 2.0, 0.0, -0.0], device=DEV)
     same = torch.zeros(5, dtype=torch.int32, device=DEV)
@@ -448,26 +520,19 @@ def test_calibrate_degenerate_inputs(B, small_ctx):
     assert np.isneginf(tau).all() and list(n) == [0]
 
 
-def test_calibrate_large_set_properties(B, small_ctx):
+@pytest.mark.parametrize("ties", [True, False])
+def test_calibrate_large_set_properties(B, small_ctx, ties):
     """2^22 tokens, beyond what the quadratic oracle can do: the definition is evaluated by
-    exact counting instead (tokens and correct tokens at or below every distinct entropy
-    value, from sorted arrays), which gives the unique answer for every level."""
+    exact counting instead, with tied entropies and without."""
     M = 1 << 22
-    H, pred, ref = G.make_calibration_case(M, DEV, seed=3, ties=True, nan_every=1001)
+    H, pred, ref = G.make_calibration_case(M, DEV, seed=3, ties=ties, nan_every=1001)
+    before = B.eh_probe_calibrate_sorted(small_ctx)
     tau, n = _calibrate(B, small_ctx, H, pred, ref, EPS_SWEEP)
+    assert B.eh_probe_calibrate_sorted(small_ctx) == before, "data of this kind must not need the full sort"
     Hc = H.cpu().numpy().astype(np.float64)
     t = O.correctness(pred.cpu().numpy(), ref.cpu().numpy())
-    ok = ~np.isnan(Hc)
-    vals, inv = np.unique(Hc[ok], return_inverse=True)                     # ascending entropy values
-    cnt = np.bincount(inv, minlength=len(vals)).cumsum()                   # tokens with H <= value
-    cor = np.bincount(inv, weights=t[ok], minlength=len(vals)).cumsum()    # correct ones among them
-    for i, e in enumerate(EPS_SWEEP):
-        good = cor / cnt >= e                                              # the section's quotient, in double
-        if not good.any():
-            assert np.isneginf(tau[i]) and n[i] == 0
-            continue
-        k = np.nonzero(good)[0].max()                                      # largest qualifying value
-        assert tau[i] == np.float32(vals[k]) and n[i] == cnt[k], (e, tau[i], vals[k])
+    for i, (want_tau, want_n) in enumerate(_calibrate_by_counting(Hc, t, EPS_SWEEP)):
+        assert tau[i] == want_tau and n[i] == want_n, (EPS_SWEEP[i], tau[i], want_tau, n[i], want_n)
     assert (np.diff(tau) <= 0).all()
 
 
