@@ -325,9 +325,15 @@ eh_status eh_head_losses(eh_ctx* ctx, int32_t head, const void* h_head, int64_t 
  * eps          host [n_eps] double, each in [0, 1]; 0 <= n_eps <= 64
  * tau_out      device [n_eps] float
  * n_exit_out   NULL or device [n_eps] int64: tokens with H <= tau
- * Asynchronous on `stream`.  Uses about 20 * M bytes of scratch memory that the
- * context keeps until eh_destroy; a call with a larger M than any before grows it,
- * which synchronises the device.
+ * The call waits for `stream` before it returns: it finds the thresholds by counting
+ * the tokens into bins in three levels, keeping at each level only the bins that can
+ * still hold an answer, and reads one word back to learn whether its tables of kept
+ * bins were large enough.  They are unless the proportion stays within a hair of a
+ * level over a wide range of thresholds (or M > 2^27); the call then sorts all tokens
+ * instead.  The results are the same either way, and are complete in tau_out and
+ * n_exit_out when the call returns.  Uses about 5.2 * M bytes + 8 MiB of scratch
+ * memory (20 * M when it sorts) that the context keeps until eh_destroy; a call that
+ * needs more than any before grows it, which synchronises the device.
  */
 eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const int32_t* ref, int64_t M,
                        const double* eps, int32_t n_eps, float* tau_out, int64_t* n_exit_out,

@@ -146,7 +146,7 @@ constexpr int kBins3 = 256;        // single keys of one kept level-2 bin
 constexpr int kCap1 = 128;         // kept bins of level 1, all epsilon together
 constexpr int kCap2 = 1024;        // kept bins of level 2
 constexpr int kChunk = 2048;       // tokens four waves take at a time: 4 x 8 x 64 (a workgroup of 1024: four times that)
-constexpr int kStage = 8 * kChunk;  // tokens of kept bins a workgroup holds back before it appends them
+constexpr int kStageWave = 1024;    // tokens of kept bins a wave holds back before it appends them
 constexpr int kSegment = 32768;    // tokens behind one row of level-1 partial counts (16-bit counters)
 constexpr int64_t kRefineMax = (int64_t)1 << 27;  // larger sets go to the sort (4096 partial rows)
 
@@ -207,8 +207,9 @@ struct Pair {
 __device__ __forceinline__ Pair operator+(Pair a, Pair b) { return Pair{a.c + b.c, a.r + b.r}; }
 __device__ __forceinline__ Pair pair_of(uint64_t v) { return Pair{(uint32_t)v, (uint32_t)(v >> 32)}; }
 
-// Exclusive prefix of one Pair per thread over the 256 threads of a workgroup.
-__device__ __forceinline__ Pair block_exclusive(Pair v, Pair* sh /* [4] */) {
+// Exclusive prefix of one Pair per thread over the 256 threads of a workgroup; *total_c
+// receives the sum of the first members.
+__device__ __forceinline__ Pair block_exclusive(Pair v, Pair* sh /* [4] */, int* total_c = nullptr) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   Pair inc = v;
 #pragma unroll
@@ -221,6 +222,7 @@ __device__ __forceinline__ Pair block_exclusive(Pair v, Pair* sh /* [4] */) {
   __syncthreads();
   Pair off{0, 0};
   for (int k = 0; k < wave; ++k) off = off + sh[k];
+  if (total_c) *total_c = (int)(sh[0].c + sh[1].c + sh[2].c + sh[3].c);
   return Pair{off.c + inc.c - v.c, off.r + inc.r - v.r};
 }
 __device__ __forceinline__ int block_max(int v, int* sh /* [4] */) {
@@ -339,25 +341,32 @@ __global__ __launch_bounds__(1024) void calib_pack_kernel(const float* __restric
   }
 }
 
-// One chunk of tokens, 8 per lane (kChunk for a workgroup of 256): f(valid, key offset from
-// the range's base, correct), `valid` false for a NaN entropy or a token past the end.
-template <class F>
-__device__ __forceinline__ void chunk_tokens(const float* __restrict__ H, int64_t M, const CalibWork& w,
-                                             uint32_t base, int64_t chunk, F&& f) {
+// The tokens a lane holds of one trip: 8, from 8 consecutive groups of 64 (a workgroup of 1024
+// takes 8192 consecutive tokens per trip).
+struct Trip {
+  float h[8];
+  unsigned long long ok[8];
+};
+__device__ __forceinline__ Trip load_trip(const float* __restrict__ H, int64_t M, const CalibWork& w, int64_t trip) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t n_groups = (M + 63) >> 6;
-  constexpr int U = 8;
-  float h[U];
-  unsigned long long ok[U];
+  Trip t;
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int64_t g = chunk * (blockDim.x / 64 * U) + wave * U + u;
+  for (int u = 0; u < 8; ++u) {
+    const int64_t g = trip * (blockDim.x / 64 * 8) + wave * 8 + u;
     const int64_t i = (g << 6) + lane;
-    h[u] = i < M ? H[i] : NAN;
-    ok[u] = g < n_groups ? w.bits[g] : 0ull;
+    t.h[u] = i < M ? H[i] : NAN;
+    t.ok[u] = g < n_groups ? w.bits[g] : 0ull;
   }
+  return t;
+}
+// f(u, valid, key offset from the range's base, correct) for the lane's 8 tokens; `valid` is
+// false for a NaN entropy or a token past the end.
+template <class F>
+__device__ __forceinline__ void for_trip(const Trip& t, uint32_t base, F&& f) {
+  const int lane = threadIdx.x & 63;
 #pragma unroll
-  for (int u = 0; u < U; ++u) f(h[u] == h[u], ascending_key(h[u]) - base, (unsigned)((ok[u] >> lane) & 1ull));
+  for (int u = 0; u < 8; ++u) f(u, t.h[u] == t.h[u], ascending_key(t.h[u]) - base, (unsigned)((t.ok[u] >> lane) & 1ull));
 }
 
 // Pass 1: one workgroup (of 1024) per segment of kSegment tokens counts into 16 + 16 bit bins
@@ -369,10 +378,10 @@ __global__ __launch_bounds__(1024) void calib_count1_kernel(const float* __restr
   const Cut c = cut_of(w);
   if (!c.empty)
     for (int k = 0; k < kSegment / (4 * kChunk); ++k)
-      chunk_tokens(H, M, w, c.base, (int64_t)blockIdx.x * (kSegment / (4 * kChunk)) + k,
-                   [&](bool valid, uint32_t off, unsigned ok) {
-                     if (valid) atomicAdd(&bins[off >> c.s & (kBins1 - 1)], 1u + (ok << 16));
-                   });
+      for_trip(load_trip(H, M, w, (int64_t)blockIdx.x * (kSegment / (4 * kChunk)) + k), c.base,
+               [&](int, bool valid, uint32_t off, unsigned ok) {
+                 if (valid) atomicAdd(&bins[off >> c.s & (kBins1 - 1)], 1u + (ok << 16));
+               });
   __syncthreads();
   uint32_t* out = w.part1 + (size_t)blockIdx.x * kBins1;
   for (int b = threadIdx.x; b < kBins1; b += 1024) out[b] = bins[b];
@@ -425,29 +434,65 @@ __device__ __forceinline__ void keep_bin(uint64_t* sel, int* slot, int* n_kept, 
   }
 }
 
+// What the levels hand on, per epsilon: the kept bins in the order in which the next level
+// walks them, with the counts below each, so that no later kernel has to scan a table again.
+constexpr int kList2 = 256;  // kept level-2 bins of one epsilon
+struct EpsWalk {
+  int n1;                  // kept level-1 bins, ascending
+  int bin1[kCap1];
+  Pair below1[kCap1];
+  int n2;                  // kept level-2 bins, descending: the order of the final walk
+  uint32_t at2[kList2];    // index into sel2 / slot2: row of the level-1 bin * kBins2 + bin
+  uint32_t hi2[kList2];    // the key bits above level 3: level-1 bin << b2 | bin
+  Pair below2[kList2];
+};
+
 // Level 1, one workgroup per epsilon.
-__global__ __launch_bounds__(256) void calib_keep1_kernel(CalibWork w, EpsList eps) {
+__global__ __launch_bounds__(256) void calib_keep1_kernel(CalibWork w, EpsList eps, EpsWalk* __restrict__ walks) {
   __shared__ NodeShared sh;
+  __shared__ int bin[kCap1];
   constexpr int PER = kBins1 / 256;
   const int e = blockIdx.x;
+  EpsWalk& walk = walks[e];
   Pair pre[PER];
   unsigned may;
   const int top = node_scan<PER, true>(w.h1, kBins1, Pair{0, 0}, eps.v[e], pre, may, sh);
   const int b0 = threadIdx.x * PER;
+  unsigned mine = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) mine |= (unsigned)((may >> j & 1u) && b0 + j >= top) << j;
+  int total;
+  int k = (int)block_exclusive(Pair{(uint32_t)__popc(mine), 0u}, sh.scan, &total).c;
 #pragma unroll
   for (int j = 0; j < PER; ++j)
-    if ((may >> j & 1u) && b0 + j >= top)
-      keep_bin(&w.sel1[b0 + j], &w.slot1[b0 + j], &w.n_kept[0], kCap1, w.overflow, e);
+    if ((mine >> j & 1u) && k < kCap1) {
+      bin[k] = b0 + j;
+      walk.bin1[k] = b0 + j;
+      walk.below1[k] = pre[j];
+      ++k;
+    }
+  if (threadIdx.x == 0) {
+    walk.n1 = total < kCap1 ? total : kCap1;
+    if (total > kCap1) *w.overflow = 0;
+  }
+  __syncthreads();
+  // one bin per thread: the atomics of a workgroup are in flight together
+  if ((int)threadIdx.x < total && threadIdx.x < kCap1) {
+    const int b = bin[threadIdx.x];
+    keep_bin(&w.sel1[b], &w.slot1[b], &w.n_kept[0], kCap1, w.overflow, e);
+  }
 }
 
 // Pass 2: tokens of kept level-1 bins are counted by their next b2 bits and set aside for
 // pass 3.  One workgroup of 1024 per segment, as in pass 1.
 __global__ __launch_bounds__(1024) void calib_count2_kernel(const float* __restrict__ H, int64_t M, CalibWork w) {
   __shared__ __align__(16) signed char slot[kBins1];  // rows are below kCap1 = 128
-  __shared__ uint32_t stage[kStage];
-  __shared__ int n_stage, at;
-  if (*w.overflow == 0) return;
-  {  // both loads of the table in flight at once
+  __shared__ uint32_t stage[16][kStageWave];  // a region per wave: no barrier while the tokens stream
+  __shared__ int n_wave[16], at;
+  // everything the kernel needs before the tokens is asked for at once: the latency is paid once
+  const int ov = *w.overflow;
+  const Cut c = cut_of(w);
+  {
     constexpr int N = kBins1 / 4 / 1024;
     int4 v[N];
 #pragma unroll
@@ -459,90 +504,171 @@ __global__ __launch_bounds__(1024) void calib_count2_kernel(const float* __restr
       ((char4*)slot)[k * 1024 + threadIdx.x] = c4;
     }
   }
-  if (threadIdx.x == 0) n_stage = 0;
   __syncthreads();
-  const Cut c = cut_of(w);
-  if (c.empty) return;
+  if (ov == 0 || c.empty) return;
   const uint32_t ms = (1u << c.s) - 1u;
-  const int lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t* mine = stage[wave];
+  int n = 0;  // uniform over the wave
   constexpr int kTrips = kSegment / (4 * kChunk);
   for (int k = 0; k < kTrips; ++k) {
-    chunk_tokens(H, M, w, c.base, (int64_t)blockIdx.x * kTrips + k, [&](bool valid, uint32_t off, unsigned ok) {
-      const int row = valid ? slot[off >> c.s & (kBins1 - 1)] : -1;
+    const Trip t = load_trip(H, M, w, (int64_t)blockIdx.x * kTrips + k);
+    int rows[8];  // all eight table look-ups of a trip in flight together
+    for_trip(t, c.base, [&](int u, bool valid, uint32_t off, unsigned) {
+      rows[u] = valid ? slot[off >> c.s & (kBins1 - 1)] : -1;
+    });
+    for_trip(t, c.base, [&](int u, bool, uint32_t off, unsigned ok) {
+      const int row = rows[u];
+      const unsigned long long on = __ballot(row >= 0);
+      if (!on) return;  // uniform over the wave
       const uint32_t within = off & ms;
       add_counted(w.h2, (uint32_t)row * kBins2 + (within >> c.b3), row >= 0, ok);
-      const unsigned long long on = __ballot(row >= 0);
-      if (on) {  // uniform over the wave
+      if (n + 64 > kStageWave) {  // a wave whose tokens are mostly kept: it appends what it holds by itself
         int first = 0;
-        if (lane == __builtin_ctzll(on)) first = atomicAdd(&n_stage, __popcll(on));
-        first = __shfl(first, __builtin_ctzll(on));
-        if (row >= 0) stage[first + __popcll(on & ((1ull << lane) - 1ull))] = (ok << 31) | ((uint32_t)row << 20) | within;
+        if (lane == 0) first = atomicAdd(&w.n_kept[2], n);
+        first = __shfl(first, 0);
+        for (int i = lane; i < n; i += 64) w.kept[first + i] = mine[i];
+        n = 0;
       }
+      if (row >= 0) mine[n + __popcll(on & ((1ull << lane) - 1ull))] = (ok << 31) | ((uint32_t)row << 20) | within;
+      n += __popcll(on);
     });
-    lds_barrier();
-    const int n = n_stage;
-    const bool flush = n > kStage - 4 * kChunk || k == kTrips - 1;  // uniform
-    if (flush && n && threadIdx.x == 0) at = atomicAdd(&w.n_kept[2], n);
-    lds_barrier();  // everyone has read n_stage, and `at` is there
-    if (flush && n) {
-      for (int i = threadIdx.x; i < n; i += 1024) w.kept[at + i] = stage[i];
-      if (threadIdx.x == 0) n_stage = 0;
-      lds_barrier();
-    }
   }
+  // the workgroup appends what its waves still hold with one reservation
+  if (lane == 0) n_wave[wave] = n;
+  lds_barrier();
+  if (threadIdx.x == 0) {
+    int total = 0;
+    for (int k = 0; k < 16; ++k) total += n_wave[k];
+    at = total ? atomicAdd(&w.n_kept[2], total) : 0;
+  }
+  lds_barrier();
+  int first = at;
+  for (int k = 0; k < wave; ++k) first += n_wave[k];
+  for (int i = lane; i < n; i += 64) w.kept[first + i] = mine[i];
 }
 
-// The kept level-1 bins of one epsilon, in ascending order, with the counts below each.
-struct KeptList {
-  int n;
-  int bin[kCap1];
-  Pair below[kCap1];
-};
-__device__ __forceinline__ void list_kept1(const CalibWork& w, int e, KeptList& list, NodeShared& sh) {
-  constexpr int PER = kBins1 / 256;
-  Pair pre[PER];
-  unsigned may;
-  (void)node_scan<PER, false>(w.h1, kBins1, Pair{0, 0}, 0.0, pre, may, sh);
-  const int b0 = threadIdx.x * PER;
-  unsigned mine = 0;
+// One node for one wave: nb <= 64 * PER bins, lane l looks at bins [PER * l, PER * (l + 1)).
+// As node_scan with JUDGE; the counts up to and including the bin returned come back in at_top.
+template <int PER>
+__device__ __forceinline__ int wave_node_scan(const uint64_t* __restrict__ t, int nb, Pair below, double eps,
+                                              Pair (&pre)[PER], unsigned& may, Pair& at_top) {
+  const int lane = threadIdx.x & 63;
+  const int b0 = lane * PER;
+  Pair v[PER];
+  Pair sum{0, 0};
 #pragma unroll
-  for (int j = 0; j < PER; ++j) mine |= (unsigned)(w.sel1[b0 + j] >> e & 1ull) << j;
-  const Pair at = block_exclusive(Pair{(uint32_t)__popc(mine), 0u}, sh.scan);
-  int k = (int)at.c;
+  for (int j = 0; j < PER; ++j) {
+    v[j] = b0 + j < nb ? pair_of(t[b0 + j]) : Pair{0, 0};
+    sum = sum + v[j];
+  }
+  Pair inc = sum;
 #pragma unroll
-  for (int j = 0; j < PER; ++j)
-    if ((mine >> j & 1u) && k < kCap1) {
-      list.bin[k] = b0 + j;
-      list.below[k] = pre[j];
-      ++k;
-    }
-  if (threadIdx.x == 255) list.n = k < kCap1 ? k : kCap1;
-  __syncthreads();
-}
-
-// Level 2, one workgroup per epsilon: down the kept level-1 bins until a top candidate qualifies.
-__global__ __launch_bounds__(256) void calib_keep2_kernel(CalibWork w, EpsList eps) {
-  __shared__ NodeShared sh;
-  __shared__ KeptList list;
-  constexpr int PER = kBins2 / 256;
-  if (*w.overflow == 0) return;
-  const int e = blockIdx.x;
-  const Cut c = cut_of(w);
-  list_kept1(w, e, list, sh);
-  const int b0 = threadIdx.x * PER;
-  for (int i = list.n - 1; i >= 0; --i) {
-    const int row = w.slot1[list.bin[i]];
-    Pair pre[PER];
-    unsigned may;
-    const int top = node_scan<PER, true>(w.h2 + (size_t)row * kBins2, 1 << c.b2, list.below[i], eps.v[e], pre, may, sh);
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t c = __shfl_up(inc.c, o), r = __shfl_up(inc.r, o);
+    if (lane >= o) inc = inc + Pair{c, r};
+  }
+  Pair run{below.c + inc.c - sum.c, below.r + inc.r - sum.r};
+  may = 0;
+  int top = -1;
+  Pair top_incl{0, 0};
 #pragma unroll
-    for (int j = 0; j < PER; ++j)
-      if ((may >> j & 1u) && b0 + j >= top) {
-        const size_t at = (size_t)row * kBins2 + b0 + j;
-        keep_bin(&w.sel2[at], &w.slot2[at], &w.n_kept[1], kCap2, w.overflow, e);
+  for (int j = 0; j < PER; ++j) {
+    pre[j] = run;
+    const Pair incl = run + v[j];
+    if (v[j].c) {
+      const double bound = v[j].r ? (double)incl.r / (double)(run.c + v[j].r) : (double)run.r / (double)(run.c + 1u);
+      if (bound >= eps) may |= 1u << j;
+      if ((double)incl.r / (double)incl.c >= eps) {
+        top = b0 + j;
+        top_incl = incl;
       }
-    if (top >= 0) break;  // uniform: every smaller key is below one that qualifies
+    }
+    run = incl;
   }
+  int best = top;
+#pragma unroll
+  for (int o = 32; o; o >>= 1) {
+    const int u = __shfl_xor(best, o);
+    best = u > best ? u : best;
+  }
+  const int owner = best >= 0 ? best / PER : 0;
+  at_top = Pair{(uint32_t)__shfl((int)top_incl.c, owner), (uint32_t)__shfl((int)top_incl.r, owner)};
+  return best;
+}
+
+// Level 2, one workgroup per epsilon: down the kept level-1 bins, four at a time (a wave
+// each), until a top candidate qualifies.
+__global__ __launch_bounds__(256) void calib_keep2_kernel(CalibWork w, EpsList eps, EpsWalk* __restrict__ walks) {
+  __shared__ int top_w[4], cnt_w[4];
+  __shared__ uint32_t at2[kList2];
+  constexpr int PER = kBins2 / 64;
+  const int ov = *w.overflow;
+  const Cut c = cut_of(w);
+  const int e = blockIdx.x;
+  EpsWalk& walk = walks[e];
+  const int n1 = walk.n1;
+  if (ov == 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int n2 = 0;  // uniform over the workgroup
+  for (int r = 0; 4 * r < n1; ++r) {
+    const int i = n1 - 1 - (4 * r + wave);  // uniform over the wave
+    int top = -1, cnt = 0, before = 0, row = 0, bin1 = 0;
+    unsigned keep = 0;
+    Pair pre[PER];
+    if (i >= 0) {
+      bin1 = walk.bin1[i];
+      row = w.slot1[bin1];
+      unsigned may;
+      Pair at_top;
+      top = wave_node_scan<PER>(w.h2 + (size_t)row * kBins2, 1 << c.b2, walk.below1[i], eps.v[e], pre, may, at_top);
+#pragma unroll
+      for (int j = 0; j < PER; ++j) keep |= (unsigned)((may >> j & 1u) && lane * PER + j >= top) << j;
+      int inc = __popc(keep);
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int u = __shfl_up(inc, o);
+        if (lane >= o) inc += u;
+      }
+      before = inc - __popc(keep);
+      cnt = __shfl(inc, 63);
+    }
+    if (lane == 0) {
+      top_w[wave] = top;
+      cnt_w[wave] = cnt;
+    }
+    __syncthreads();
+    int stop = 4, first = n2, all = 0;
+    for (int k = 3; k >= 0; --k)
+      if (top_w[k] >= 0) stop = k;
+    for (int k = 0; k < 4 && k <= stop; ++k) {
+      if (k < wave) first += cnt_w[k];
+      all += cnt_w[k];
+    }
+    if (i >= 0 && wave <= stop) {  // the bins of this node, from the top
+      int at = first + cnt - 1 - before;
+#pragma unroll
+      for (int j = 0; j < PER; ++j)
+        if (keep >> j & 1u) {
+          if (at < kList2) {
+            at2[at] = (uint32_t)row * kBins2 + lane * PER + j;
+            walk.at2[at] = (uint32_t)row * kBins2 + lane * PER + j;
+            walk.hi2[at] = ((uint32_t)bin1 << c.b2) | (uint32_t)(lane * PER + j);
+            walk.below2[at] = pre[j];
+          }
+          --at;
+        }
+    }
+    n2 += all;
+    __syncthreads();  // top_w and cnt_w are rewritten in the next round
+    if (stop < 4) break;  // uniform: every smaller key is below one that qualifies
+  }
+  if (threadIdx.x == 0) {
+    walk.n2 = n2 < kList2 ? n2 : kList2;
+    if (n2 > kList2) *w.overflow = 0;
+  }
+  for (int k = threadIdx.x; k < n2 && k < kList2; k += 256)
+    keep_bin(&w.sel2[at2[k]], &w.slot2[at2[k]], &w.n_kept[1], kCap2, w.overflow, e);
 }
 
 // Pass 3: the tokens set aside whose level-2 bin is kept are counted by their last b3 bits,
@@ -562,52 +688,43 @@ __global__ __launch_bounds__(256) void calib_count3_kernel(CalibWork w) {
 }
 
 // Level 3, one workgroup per epsilon: the first single key, from the top, that qualifies.
-__global__ __launch_bounds__(256) void calib_pick_kernel(CalibWork w, EpsList eps, float* __restrict__ tau,
-                                                         long long* __restrict__ n_exit) {
-  __shared__ NodeShared sh;
-  __shared__ KeptList list;
-  __shared__ int sub[kBins2];
-  __shared__ Pair sub_below[kBins2];
-  __shared__ int n_sub;
-  constexpr int PER = kBins2 / 256;
-  if (*w.overflow == 0) return;
-  const int e = blockIdx.x;
+// Four kept level-2 bins at a time, a wave each.
+__global__ __launch_bounds__(256) void calib_pick_kernel(CalibWork w, EpsList eps, const EpsWalk* __restrict__ walks,
+                                                         float* __restrict__ tau, long long* __restrict__ n_exit) {
+  __shared__ int top_w[4];
+  __shared__ uint32_t cnt_w[4];
+  constexpr int PER = kBins3 / 64;
+  const int ov = *w.overflow;
   const Cut c = cut_of(w);
-  list_kept1(w, e, list, sh);
-  const int b0 = threadIdx.x * PER;
-  for (int i = list.n - 1; i >= 0; --i) {
-    const int row1 = w.slot1[list.bin[i]];
-    Pair pre[PER];
-    unsigned may;
-    (void)node_scan<PER, false>(w.h2 + (size_t)row1 * kBins2, 1 << c.b2, list.below[i], 0.0, pre, may, sh);
-    unsigned mine = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) mine |= (unsigned)(w.sel2[(size_t)row1 * kBins2 + b0 + j] >> e & 1ull) << j;
-    const Pair at = block_exclusive(Pair{(uint32_t)__popc(mine), 0u}, sh.scan);
-    int k = (int)at.c;
-#pragma unroll
-    for (int j = 0; j < PER; ++j)
-      if (mine >> j & 1u) {
-        sub[k] = b0 + j;
-        sub_below[k] = pre[j];
-        ++k;
-      }
-    if (threadIdx.x == 255) n_sub = k;
+  const int e = blockIdx.x;
+  const EpsWalk& walk = walks[e];
+  const int n2 = walk.n2;
+  if (ov == 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int r = 0; 4 * r < n2; ++r) {
+    const int q = 4 * r + wave;  // uniform over the wave
+    int top = -1;
+    Pair at_top{0, 0};
+    if (q < n2) {
+      const int row = w.slot2[walk.at2[q]];
+      Pair pre[PER];
+      unsigned may;
+      top = wave_node_scan<PER>(w.h3 + (size_t)row * kBins3, 1 << c.b3, walk.below2[q], eps.v[e], pre, may, at_top);
+    }
+    if (lane == 0) {
+      top_w[wave] = top;
+      cnt_w[wave] = at_top.c;
+    }
     __syncthreads();
-    for (int q = n_sub - 1; q >= 0; --q) {
-      const int row = w.slot2[(size_t)row1 * kBins2 + sub[q]];
-      Pair one[1];
-      const int top = node_scan<1, true>(w.h3 + (size_t)row * kBins3, 1 << c.b3, sub_below[q], eps.v[e], one, may, sh);
-      if (top >= 0) {
+    for (int k = 0; k < 4; ++k)
+      if (top_w[k] >= 0) {  // uniform
         if (threadIdx.x == 0) {
-          const uint32_t key = c.base + (((uint32_t)list.bin[i] << c.s) | ((uint32_t)sub[q] << c.b3) | (uint32_t)top);
-          tau[e] = ascending_entropy(key);
-          if (n_exit) n_exit[e] = (long long)sh.at_top.c;
+          tau[e] = ascending_entropy(c.base + ((walk.hi2[4 * r + k] << c.b3) | (uint32_t)top_w[k]));
+          if (n_exit) n_exit[e] = (long long)cnt_w[k];
         }
         return;
       }
-    }
-    __syncthreads();  // sub[] is rewritten for the next bin
+    __syncthreads();
   }
   if (threadIdx.x == 0) {
     tau[e] = -INFINITY;
@@ -692,7 +809,7 @@ hipError_t calibrate_refine(CalibScratch& sc, const float* H, const int* pred, c
   const size_t kept_cap = (size_t)M;
   const size_t zero_words = 4 + 2 * ((size_t)kBins1 + kBins1 + 2 * (size_t)kCap1 * kBins2 + (size_t)kCap2 * kBins3);
   const size_t ones_words = 4 + (size_t)kBins1 + (size_t)kCap1 * kBins2;
-  e = calib_reserve(sc, (2 * n_groups + n_segments * kBins1 + kept_cap + 8 + zero_words + ones_words) * 4 + 256);
+  e = calib_reserve(sc, (2 * n_groups + n_segments * kBins1 + kept_cap + 8 + zero_words + ones_words) * 4 + kMaxEps * sizeof(EpsWalk) + 256);
   if (e != hipSuccess) return e;
   CalibWork w;
   uint32_t* p = (uint32_t*)sc.buf;
@@ -723,16 +840,18 @@ hipError_t calibrate_refine(CalibScratch& sc, const float* H, const int* pred, c
   w.slot1 = (int*)p;
   p += kBins1;
   w.slot2 = (int*)p;
+  p += (size_t)kCap1 * kBins2;
+  EpsWalk* walks = (EpsWalk*)p;
   hipLaunchKernelGGL(calib_preset_kernel, dim3((unsigned)((zero_words + ones_words + 255) / 256)), dim3(256), 0, s,
                      (int*)zero0, (int64_t)zero_words, (int*)ones0, (int64_t)ones_words);
   hipLaunchKernelGGL(calib_pack_kernel, dim3((unsigned)n_segments), dim3(1024), 0, s, H, pred, ref, M, w);
   hipLaunchKernelGGL(calib_count1_kernel, dim3((unsigned)n_segments), dim3(1024), 0, s, H, M, w);
   hipLaunchKernelGGL(calib_sum1_kernel, dim3(kBins1 / 256, 16), dim3(256), 0, s, w, (int)n_segments);
-  hipLaunchKernelGGL(calib_keep1_kernel, dim3(el.n), dim3(256), 0, s, w, el);
+  hipLaunchKernelGGL(calib_keep1_kernel, dim3(el.n), dim3(256), 0, s, w, el, walks);
   hipLaunchKernelGGL(calib_count2_kernel, dim3((unsigned)n_segments), dim3(1024), 0, s, H, M, w);
-  hipLaunchKernelGGL(calib_keep2_kernel, dim3(el.n), dim3(256), 0, s, w, el);
+  hipLaunchKernelGGL(calib_keep2_kernel, dim3(el.n), dim3(256), 0, s, w, el, walks);
   hipLaunchKernelGGL(calib_count3_kernel, dim3(256), dim3(256), 0, s, w);
-  hipLaunchKernelGGL(calib_pick_kernel, dim3(el.n), dim3(256), 0, s, w, el, tau_out, n_exit_out);
+  hipLaunchKernelGGL(calib_pick_kernel, dim3(el.n), dim3(256), 0, s, w, el, walks, tau_out, n_exit_out);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   e = hipMemcpyAsync(sc.host_flag, w.overflow, sizeof(int), hipMemcpyDeviceToHost, s);
