@@ -204,19 +204,29 @@ def bench_draft(args, torch, B, G, dev):
     heads = G.make_heads(w, dev)
     hid = G.make_hidden(w, heads, dev, rows=n_dec)               # [n_heads, n_dec, d]
     tau = G.tau_linear(w)
-    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=1)
+    # Two regimes per bench step, over the same windows: the workload's own thresholds, under
+    # which a window soon meets a position no exit head is confident about (the drafter falls
+    # back to the full model), and thresholds whose deepest exit head always exits, under which
+    # every window drafts until the buffer is full.
+    tau_full = list(tau)
+    tau_full[w.n_heads - 2] = float("inf")
+    regimes = [("calibrated", tau), ("deepest_exit_head_always_confident", tau_full)]
+    ctxs = [B.eh_create(heads.W, heads.gamma, heads.beta, t, max_rows=1) for _, t in regimes]
     hp = hid.h.permute(1, 0, 2)                                  # [position, head, d]
     wins = [hp[i * limit:(i + 1) * limit] for i in range(n_win)]
-    draft = torch.zeros((n_win, limit), dtype=torch.int32, device=dev)
-    layers = torch.zeros((n_win, limit), dtype=torch.int32, device=dev)
-    ln = torch.zeros(n_win, dtype=torch.int32, device=dev)
-    reason = torch.zeros(n_win, dtype=torch.int32, device=dev)
-    fb = torch.zeros(n_win, dtype=torch.int32, device=dev)
-    nev = torch.zeros(1, dtype=torch.int64, device=dev)
+    nr = len(regimes)
+    draft = torch.zeros((nr, n_win, limit), dtype=torch.int32, device=dev)
+    layers = torch.zeros((nr, n_win, limit), dtype=torch.int32, device=dev)
+    ln = torch.zeros((nr, n_win), dtype=torch.int32, device=dev)
+    reason = torch.zeros((nr, n_win), dtype=torch.int32, device=dev)
+    fb = torch.zeros((nr, n_win), dtype=torch.int32, device=dev)
+    nev = torch.zeros((nr, 1), dtype=torch.int64, device=dev)
 
     def step():
-        for i in range(n_win):
-            B.dssd_draft(ctx, wins[i], limit, -1, draft[i], ln[i:i + 1], layers[i], reason[i:i + 1], fb[i:i + 1], nev)
+        for r, ctx in enumerate(ctxs):
+            for i in range(n_win):
+                B.dssd_draft(ctx, wins[i], limit, -1, draft[r, i], ln[r, i:i + 1], layers[r, i], reason[r, i:i + 1],
+                             fb[r, i:i + 1], nev[r])
 
     for _ in range(args.warmup):
         step()
@@ -233,11 +243,19 @@ def bench_draft(args, torch, B, G, dev):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ev_s = ev0.elapsed_time(ev1) * 1e-3
-    B.eh_check(ctx)
-    evals = int(nev.item())
+    for ctx in ctxs:
+        B.eh_check(ctx)
+    evals = int(nev.sum().item())
     drafted = int(ln.sum().item())
     fallbacks = int((reason == 2).sum().item())
     live = (drafted + fallbacks) * args.steps                   # cascades that did work
+    per_regime = {}
+    for r, (name, _) in enumerate(regimes):
+        stops = torch.bincount(reason[r].long(), minlength=4).tolist()
+        per_regime[name] = {"drafted_tokens_per_step": int(ln[r].sum().item()),
+                            "evals_per_step": int(nev[r].item()) // args.steps,
+                            "windows_by_stop_reason": {"limit": stops[0], "eos": stops[1], "fallback": stops[2],
+                                                       "exhausted": stops[3]}}
     esz = 2
     bytes_per_eval = w.d * w.V * esz + w.d * esz + 12
     # the cascades that run are the dominant kernel; the launches behind a stop return at once.
@@ -277,15 +295,16 @@ def bench_draft(args, torch, B, G, dev):
         cpu = {"value": c_evals / cdt, "unit": "evals/s", "cores": oracle_threads(), "kind": "oracle",
                "sample": f"first {c_wins} windows of the same workload ({c_evals} evaluations, {cdt:.1f} s; "
                          "fp64 numpy cascade per position, then the drafting rule)"}
-    B.eh_destroy(ctx)
+    for ctx in ctxs:
+        B.eh_destroy(ctx)
     line = {"metric": "exit_head_evals_per_sec", "value": evals / dt, "unit": "evals/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": f"f3_draft: d=1024 V=50304 24 heads batch-1 bf16, {n_win} drafting windows of "
-                                   f"{limit} positions per bench step, draft until the buffer is full or no exit head "
-                                   "is confident",
-                       "windows": n_win, "limit": limit, "drafted_tokens_per_step": drafted,
-                       "fallback_windows": fallbacks, "drafted_tokens_per_sec": drafted * args.steps / dt,
+                                   f"{limit} positions per bench step under each of two sets of thresholds, draft "
+                                   "until the buffer is full or no exit head is confident",
+                       "windows": n_win, "limit": limit, "regimes": per_regime,
+                       "drafted_tokens_per_sec": drafted * args.steps / dt,
                        "mean_evals_per_live_position": evals / live},
             "roofline": roof, "cpu_baseline": cpu, "setup_s": round(time.time() - t_setup, 1)}
     print(json.dumps(line), flush=True)
