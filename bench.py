@@ -44,12 +44,12 @@ HBM_PEAK_GBS = 8000.0
 # measured bytes per launch / algorithmic bytes per launch of the same launches
 # (profiles/c1_decode_persistent_kernel.md).  Reported as that ratio times this run's
 # algorithmic bytes per launch.
-TRAFFIC_RATIO_C1 = (1.9281e9 + 1.42e6) / 1.7635e9
+TRAFFIC_RATIO_C1 = (1.9298e9 + 1.43e6) / 1.7635e9
 # The same for the batched projection kernel (profiles/c2_calib_gemm32_kernel.md,
 # profiles/c3_dynexit_c4_verify_kernels.md): measured HBM bytes per head.
-TRAFFIC_BYTES_C2 = 269.4e6 + 1.31e6        # 206 MB of weights, read 1.3 times by the two token groups
-TRAFFIC_RATIO_C3 = (263.3e6 + 0.28e6) / 257.7e6
-TRAFFIC_RATIO_C4 = (268.8e6 + 0.82e6) / 258.3e6
+TRAFFIC_BYTES_C2 = 271.4e6 + 1.31e6        # 206 MB of weights, read 1.3 times by the two token groups
+TRAFFIC_RATIO_C3 = (264.9e6 + 0.70e6) / 257.75e6
+TRAFFIC_RATIO_C4 = (272.4e6 + 2.32e6) / 258.29e6
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -591,7 +591,8 @@ def run_c3(args, torch, B, G, dev, steps, warmup, cpu_leg, keep=None):
     avg_s = ev_s / launches
     roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C3 * bytes_per_launch,
-            "kernel": "the projection of one head on the live rows (time per head = cascade time / heads run)",
+            "kernel": "eh::gemm32_stats_kernel_rows<false> (one launch = a whole cascade; one head on the live rows = "
+                      "cascade time / heads run)",
             "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
     cfg = {"workload": "c3_dynexit: d=2560 V=50304 32 heads x 64 rows bf16, rows exit at first H<tau, "
                        "compaction between heads",
@@ -647,8 +648,8 @@ def run_c4(args, torch, B, G, dev, steps, warmup, cpu_leg, heads=None):
     avg_s = ev_s / launches
     roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_RATIO_C4 * bytes_per_launch,
-            "kernel": "the argmax-only projection of one verification, 144 positions (time per verification = "
-                      "all launches of a dssd_verify call)",
+            "kernel": "eh::gemm32_stats_kernel_rows<true> (one launch = one verification: LayerNorm, argmax-only "
+                      "projection of 144 positions, prefix comparison; the time also holds the preset launch)",
             "avg_launch_us": avg_s * 1e6, "bytes_per_launch": bytes_per_launch, "launches": launches}
     cfg = {"workload": "c4_verify: d=2560 V=50304 final head, 16 rows x (8 drafts + 1) bf16, "
                        f"{calls_per_step} verifications per bench step over {n_copies} weight copies",
@@ -715,10 +716,12 @@ def run_ceiling(args, torch, B, G, dev):
             reps = max(3, args.steps)
             ms = event_ms(lambda: [B.eh_probe_mfma(ctx, iters, rnd, sink) for _ in range(reps)], torch)
             out[name] = flops * reps / (ms * 1e-3) / 1e12
+            if name == "random_4000":
+                ms_step = ms / reps
         B.eh_destroy(ctx)
         best = out["random_4000"]
         line = {"metric": "mfma_bf16_TFLOPs", "value": best, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-                "warmup": 1, "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                "warmup": 1, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
                 "dtype": "bf16", "data": "synthetic",
                 "config": {"workload": "mfma_ceiling: the batched kernel's 28 matrix instructions per k-step from registers "
                                        "only, one workgroup of 4 waves per compute unit; iterations and operands vary",
