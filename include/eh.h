@@ -20,14 +20,15 @@
  *     logit is NaN) and argmax / token / target -1; it never passes the exit test
  *     and so leaves at the last head.  This is defined behaviour, not an error.
  *     Weights, gamma and beta must be finite.
- *   - Calls with at most 16 rows (heads without a bias vector, d up to 2048 for
- *     bf16 / 1024 for fp32) run a persistent kernel whose workgroups wait for each
- *     other, one workgroup per compute unit: the stream must have the device to
- *     itself while such a call runs (no other kernel holding compute units on
- *     another stream or from another context).  eh_create checks that the grid
- *     fits the empty device.  Every wait is bounded (eh_set_spin_limit); a call
- *     that gives up sets a flag that eh_check reports and clears, rows it did not
- *     finish read -1 / NaN, and the context stays usable.
+ *   - Two kinds of call run a persistent kernel whose workgroups wait for each
+ *     other, one workgroup per compute unit: every call with at most 16 rows (heads
+ *     without a bias vector, d up to 2048 for bf16 / 1024 for fp32), and eh_cascade
+ *     and dssd_verify with 17 to 256 rows (bf16 heads without a bias vector).  The
+ *     stream must have the device to itself while such a call runs (no other kernel
+ *     holding compute units on another stream or from another context).  eh_create
+ *     checks that the grids fit the empty device.  Every wait is bounded
+ *     (eh_set_spin_limit); a call that gives up sets a flag that eh_check reports
+ *     and clears, rows it did not finish read -1 / NaN, and the context stays usable.
  */
 #ifndef EH_H_
 #define EH_H_
@@ -341,8 +342,9 @@ eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const i
 
 /*
  * Waits for `stream` and reports failures that only the device can see: the
- * persistent kernel behind calls with at most 16 rows waits for other workgroups
- * with a bounded spin, and a call that gave up sets a flag in the context.
+ * persistent kernels (calls with at most 16 rows; eh_cascade and dssd_verify with 17
+ * to 256 rows) wait for other workgroups with a bounded spin, and a call that gave
+ * up sets a flag in the context.
  * Returns EH_ERR_HIP if the flag is set (or if the synchronisation fails) and
  * clears it: outputs of rows the failed call did not finish hold -1 (exit_layer,
  * token, argmax) or NaN (H, lse), later calls run normally.
@@ -350,9 +352,9 @@ eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const i
 eh_status eh_check(eh_ctx* ctx, void* stream);
 
 /*
- * Bound of the persistent kernel's waits (Section 3.4.2 cascade with at most 16
- * rows): the number of polls of another workgroup's record after which a workgroup
- * gives up (each poll is followed by a short sleep; the default, 2^22, is several
+ * Bound of the persistent kernels' waits (the cascade of Section 3.4.2 and the
+ * verification of Section 4.3.1 at up to 256 rows): the number of polls of another
+ * workgroup's record or counter after which a workgroup gives up (each poll is followed by a short sleep; the default, 2^22, is several
  * seconds).  polls >= 0; 0 makes a workgroup give up at its first unanswered poll,
  * which is how the failure path is tested without hanging anything.
  */
