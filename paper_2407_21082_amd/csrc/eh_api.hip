@@ -332,6 +332,9 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
       if ((e = dev_alloc(c, &c->rows_part4, (size_t)2 * c->rows_grid * rmax)) != hipSuccess) return bail(e, "hipMalloc(rows)");
       if ((e = dev_alloc(c, &c->rows_parti, (size_t)2 * c->rows_grid * rmax)) != hipSuccess) return bail(e, "hipMalloc(rows)");
       if ((e = dev_alloc(c, &c->rows_ctl, (size_t)c->rows_ctl_ints)) != hipSuccess) return bail(e, "hipMalloc(rows)");
+      c->rows_vctl_ints = rows_control_ints(1);
+      if ((e = dev_alloc(c, &c->rows_vctl, (size_t)2 * c->rows_vctl_ints)) != hipSuccess) return bail(e, "hipMalloc(rows)");
+      if ((e = hipMemset(c->rows_vctl, 0, (size_t)2 * c->rows_vctl_ints * sizeof(int))) != hipSuccess) return bail(e, "memset rows");
     } else {
       c->rows_grid = 0;
     }
@@ -659,6 +662,12 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft, co
     p.h = f_final; p.layer_stride = 0; p.row_stride = ctx->d;
     p.l0 = ctx->n_heads - 1; p.l1 = ctx->n_heads; p.mode = 1; p.argmax_only = 1;
     p.n_stream = ctx->rows_grid;  // a verification has no serving workgroups: all stream, then all merge
+    // no preset launch in front of a verification: it runs on one of two control blocks in turn and
+    // clears the other for the call after it (calls on a context are serialised)
+    p.ctl = ctx->rows_vctl + (size_t)(ctx->rows_vturn & 1u) * ctx->rows_vctl_ints;
+    p.ctl_next = ctx->rows_vctl + (size_t)((ctx->rows_vturn + 1u) & 1u) * ctx->rows_vctl_ints;
+    p.n_ctl_next = ctx->rows_vctl_ints;
+    ++ctx->rows_vturn;
     p.draft = draft; p.draft_len = draft_len; p.B = B; p.k = k;
     p.accepted = accepted; p.next_token = next_token; p.target = target;
     EH_HIP(ctx, rows_launch(ctx, p, s));
@@ -825,7 +834,10 @@ extern "C" eh_status eh_rows_trace(eh_ctx* ctx, int32_t n_heads, int32_t* host_o
   if (!ctx || !ctx->rows_ctl || !host_out) return EH_ERR_NULL;
   DeviceGuard guard(ctx->device);
   EH_HIP(ctx, hipDeviceSynchronize());
-  EH_HIP(ctx, hipMemcpy(host_out, ctx->rows_ctl + rows_control_ints(n_heads) - 128, 128 * sizeof(int), hipMemcpyDeviceToHost));
+  const int* from = n_heads == 1 && ctx->rows_vturn > 0
+                        ? ctx->rows_vctl + (size_t)((ctx->rows_vturn - 1u) & 1u) * ctx->rows_vctl_ints + ctx->rows_vctl_ints - 128
+                        : ctx->rows_ctl + rows_control_ints(n_heads) - 128;
+  EH_HIP(ctx, hipMemcpy(host_out, from, 128 * sizeof(int), hipMemcpyDeviceToHost));
   return EH_OK;
 }
 eh_status eh_decode_trace(eh_ctx* ctx, int32_t enable, uint64_t* host_out, int32_t n) {
@@ -853,6 +865,7 @@ eh_status eh_check(eh_ctx* ctx, void* stream) {
     if (flag != 0) {
       // report once and re-arm: the failed call's unfinished rows hold -1 / NaN
       EH_HIP(ctx, hipMemset(ctx->dec_status, 0, sizeof(int)));
+      if (ctx->rows_vctl) EH_HIP(ctx, hipMemset(ctx->rows_vctl, 0, (size_t)2 * ctx->rows_vctl_ints * sizeof(int)));
       return fail(ctx, EH_ERR_HIP,
                   "the persistent kernel gave up waiting for another workgroup: the stream did not have the "
                   "device to itself (rows it did not finish hold -1 / NaN)");

@@ -1385,6 +1385,19 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel_rows(const
   EH_LDS char* lds = (EH_LDS char*)g32_smem;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (p.mode == 1) {
+    // A verification has no preset launch in front of it.  Its results start as "not done" (the
+    // thread that writes them here is the one that writes the real ones later), and the last
+    // workgroup clears the control block of the verification after this one: nobody uses that
+    // block now (the launch before this one did, and it is over).  Both happen before the
+    // status test, so that a launch that does nothing still leaves a clean block behind.
+    if ((int)blockIdx.x < p.B && threadIdx.x == 0) {
+      p.accepted[blockIdx.x] = -1;
+      p.next_token[blockIdx.x] = -1;
+    }
+    if (blockIdx.x == gridDim.x - 1)
+      for (int i = threadIdx.x; i < p.n_ctl_next; i += kG32Threads) p.ctl_next[i] = 0;
+  }
   // a launch that gave up has not been acknowledged yet (eh_check clears the flag): do nothing
   if (*(volatile int*)p.status != 0) return;
   RowsCtl c{p.ctl, p.l1 - p.l0 + 2};
@@ -1397,15 +1410,13 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel_rows(const
   if (p.mode == 0) rows_serve_cascade(p, c, lane, sg * kG32Waves + wave, nsg * kG32Waves);
 }
 
-// Presets of a launch: the control block to zero, a cascade's outputs to "not decided".
+// Presets of a cascade launch: the control block to zero, the outputs to "not decided".
 __global__ void rows_preset_kernel(int* __restrict__ ctl, int n_ctl, int* __restrict__ exit_layer, int* __restrict__ token,
-                                   int n_rows, float* __restrict__ H_out, int n_H, int* __restrict__ accepted,
-                                   int* __restrict__ next_token, int B) {
+                                   int n_rows, float* __restrict__ H_out, int n_H) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n_ctl) ctl[i] = 0;
-  if (exit_layer && i < n_rows) { exit_layer[i] = -1; token[i] = -1; }
+  if (i < n_rows) { exit_layer[i] = -1; token[i] = -1; }
   if (H_out && i < n_H) H_out[i] = NAN;
-  if (accepted && i < B) { accepted[i] = -1; next_token[i] = -1; }
 }
 
 template <int NBH>
@@ -1509,12 +1520,15 @@ hipError_t rows_launch(const eh_ctx* c, const RowsParams& p, hipStream_t s) {
   if ((long long)(p.R_pad / 16 + 32) * p.KS * kWave > p.y_stride) return hipErrorInvalidValue;  // one buffer per head
   if (p.mode == 0 ? (!p.exit_layer || !p.token) : (!p.accepted || !p.next_token || (p.k > 0 && !p.draft) || p.B * (p.k + 1) != p.n_rows))
     return hipErrorInvalidValue;
-  const int n_ctl = rows_ctl_ints(p.l1 - p.l0);
-  const int n_H = (p.mode == 0 && p.H_out) ? p.n_heads * p.n_rows : 0;
-  const int n = std::max(std::max(n_ctl, n_H), std::max(p.n_rows, p.B));
-  hipLaunchKernelGGL(rows_preset_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.ctl, n_ctl,
-                     p.mode == 0 ? p.exit_layer : (int*)nullptr, p.token, p.n_rows, p.mode == 0 ? p.H_out : (float*)nullptr,
-                     n_H, p.mode == 1 ? p.accepted : (int*)nullptr, p.next_token, p.B);
+  if (p.mode == 1) {
+    if (!p.ctl_next || p.n_ctl_next < rows_ctl_ints(1) || p.B > c->rows_grid) return hipErrorInvalidValue;
+  } else {
+    const int n_ctl = rows_ctl_ints(p.l1 - p.l0);
+    const int n_H = p.H_out ? p.n_heads * p.n_rows : 0;
+    const int n = std::max(std::max(n_ctl, n_H), p.n_rows);
+    hipLaunchKernelGGL(rows_preset_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.ctl, n_ctl, p.exit_layer, p.token,
+                       p.n_rows, p.H_out, n_H);
+  }
   if (p.argmax_only)
     hipLaunchKernelGGL((gemm32_stats_kernel_rows<true>), dim3(c->rows_grid), dim3(kG32Threads), g32_lds_bytes(), s, p);
   else

@@ -61,6 +61,9 @@ struct eh_ctx {
   // persistent kernel for 17 .. 256 rows (bf16, no bias): 0 = shape not supported
   int rows_grid = 0;
   int* rows_ctl = nullptr;             // control block (counters, live-row masks), cleared before each launch
+  int* rows_vctl = nullptr;            // two control blocks of a verification, used in turn: a launch clears the other one
+  int rows_vctl_ints = 0;              // size of one of them
+  unsigned rows_vturn = 0;             // verifications launched so far
   int rows_ctl_ints = 0;
   eh::frag_t* rows_y = nullptr;        // [n_heads][rows_y_stride] activations, one buffer per head
   long long rows_y_stride = 0;         // fragments
@@ -118,6 +121,8 @@ struct RowsParams {
   int n_stream;                 // workgroups that stream weights; the rest of the grid serves
   int spin_limit;
   int* ctl;                     // control block, all zero at launch
+  int* ctl_next;                // verification: the block of the next launch, cleared by this one (else NULL)
+  int n_ctl_next;
   frag_t* y;                    // [l1 - l0][y_stride]: one buffer per head of the launch
   long long y_stride;
   frag_t* part4;                // [2][n_stream][R_pad]: (m, S, U, zb) of the partial statistics of two consecutive heads
