@@ -725,8 +725,11 @@ __device__ __forceinline__ void ctl_add(int* counter, int who, int v) {
 // A whole wave waits until the counter (the sum of its kSpread words) under `mask` reaches
 // `target`, and returns the sum; -1 if the launch was aborted or the wait timed out (which aborts
 // the launch).
+// `naps`: sleeps of 64 x 8 clocks between two looks.  A wave with time to spare (the service
+// waves while a head streams) looks less often: every look is a trip to memory that competes with
+// the weight stream.
 __device__ __forceinline__ int rows_wait(const RowsParams& p, const RowsCtl& c, const int* counter, int target, int lane,
-                                         int mask = 0x7fffffff) {
+                                         int mask = 0x7fffffff, int naps = 1) {
   for (int spins = 0;; ++spins) {
     int v = lane < kSpread ? ctl_load(counter + lane) : 0;
 #pragma unroll
@@ -741,7 +744,7 @@ __device__ __forceinline__ int rows_wait(const RowsParams& p, const RowsCtl& c, 
       }
       return -1;
     }
-    __builtin_amdgcn_s_sleep(8);
+    for (int k = 0; k < naps; ++k) __builtin_amdgcn_s_sleep(8);
   }
 }
 
@@ -1193,7 +1196,7 @@ __device__ __forceinline__ void rows_serve_cascade(const RowsParams& p, const Ro
       if (a1) svc_layernorm(p, l + 2, row1, lane);
     }
     if (j == 2) EH_ROWS_STAMP(0);
-    if (rows_wait(p, c, c.done(j), p.n_stream, lane) < 0) return;
+    if (rows_wait(p, c, c.done(j), p.n_stream, lane, 0x7fffffff, 8) < 0) return;
     EH_AFTER_WAIT();
     if (j == 2) EH_ROWS_STAMP(1);
     const long long part_at = (long long)(j & 1) * p.n_stream * p.R_pad;
