@@ -23,7 +23,8 @@
  *   - Two kinds of call run a persistent kernel whose workgroups wait for each
  *     other, one workgroup per compute unit: every call with at most 16 rows (heads
  *     without a bias vector, d up to 2048 for bf16 / 1024 for fp32), and eh_cascade
- *     and dssd_verify with 17 to 256 rows (bf16 heads without a bias vector).  The
+ *     and dssd_verify with up to 256 rows that the first kind does not serve (bf16
+ *     heads without a bias vector: 17 to 256 rows, and fewer at d above 2048).  The
  *     stream must have the device to itself while such a call runs (no other kernel
  *     holding compute units on another stream or from another context).  eh_create
  *     checks that the grids fit the empty device.  Every wait is bounded
@@ -342,7 +343,7 @@ eh_status eh_calibrate(eh_ctx* ctx, const float* H, const int32_t* pred, const i
 
 /*
  * Waits for `stream` and reports failures that only the device can see: the
- * persistent kernels (calls with at most 16 rows; eh_cascade and dssd_verify with 17
+ * persistent kernels (calls with at most 16 rows; eh_cascade and dssd_verify with up
  * to 256 rows) wait for other workgroups with a bounded spin, and a call that gave
  * up sets a flag in the context.
  * Returns EH_ERR_HIP if the flag is set (or if the synchronisation fails) and

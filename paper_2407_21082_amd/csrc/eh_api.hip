@@ -177,8 +177,11 @@ eh_status check_rows(eh_ctx* ctx, const void* h, int64_t row_stride, int n_rows)
 // Rows <= 16 go through the persistent decode kernel when the shape fits it.
 bool use_decode(const eh_ctx* c, int n_rows) { return c->decode_grid > 0 && n_rows <= 16; }
 // 17 .. 256 rows of a cascade or a verification go through the persistent rows kernel.
+// The persistent kernel for up to 256 rows; at most 16 rows go to the decode kernel where the
+// context has one (hidden sizes up to 2048), and here otherwise.
 bool use_rows(const eh_ctx* c, int64_t n_rows) {
-  return c->rows_grid > 0 && c->use_gemm && n_rows > 16 && n_rows <= kRowsMax && n_rows <= c->max_rows;
+  return c->rows_grid > 0 && c->use_gemm && (n_rows > 16 || c->decode_grid == 0) && n_rows >= 1 && n_rows <= kRowsMax &&
+         n_rows <= c->max_rows;
 }
 
 RowsParams rows_base(eh_ctx* c, int n_rows) {
@@ -321,7 +324,7 @@ eh_status eh_create(const eh_config* cfg, eh_ctx** out) {
     }
     if ((e = decode_prepare(c)) != hipSuccess) return bail(e, "decode_prepare");
     if ((e = rows_prepare(c)) != hipSuccess) return bail(e, "rows_prepare");
-    if (c->rows_grid > 0 && c->max_rows > 16) {
+    if (c->rows_grid > 0 && (c->max_rows > 16 || c->decode_grid == 0)) {
       // workspace of the persistent kernel for 17 .. 256 rows: one activation buffer per head (plus
       // the blocks a wave may read past the last live one), two sets of partial statistics
       const int rmax = std::min(c->R_pad_max, kRowsMax);

@@ -488,3 +488,65 @@ def test_calibrate_level_at_the_boundary(B):
                 want = O.calibrate_threshold(H.double().cpu().numpy(), t, e)
                 assert (float(tau[i]), int(cnt[i])) == want, (eps, n, correct, i)
     B.eh_destroy(ctx)
+
+
+# ------------------------------------------------------------------ few rows, hidden size above 2048
+@pytest.mark.parametrize("rows", [1, 9, 16])
+def test_few_rows_of_a_wide_model_run_the_persistent_cascade(B, rows):
+    """The single-launch kernel for at most 16 rows stops at hidden size 2048; beyond it (the 2.8B
+    shape of the batched configurations has 2560) a cascade or a verification of few rows is served
+    by the kernel for up to 256 rows, in one launch as well.  Parity as for any cascade; that it is
+    that kernel which ran shows in its bounded wait giving up when told to poll zero times."""
+    w = G.Workload("wide", d=2176, V=3000, n_heads=5, rows=rows, dtype="bf16", seed=40 + rows, kappa=0.6)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    n = w.n_heads
+    full = P.oracle_all_heads(heads, hid.h, True)
+    tau = G.tau_for_schedule(full[0], n) if rows > 1 else G.tau_linear(w)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=rows)
+    ex = torch.full((rows,), -7, dtype=torch.int32, device=DEV)
+    tok = torch.full((rows,), -7, dtype=torch.int32, device=DEV)
+    Hout = torch.zeros((n, rows), device=DEV)
+    nev = torch.zeros(1, dtype=torch.int64, device=DEV)
+    B.eh_cascade(ctx, hid.h, rows, ex, tok, Hout, nev)
+    torch.cuda.synchronize()
+    B.eh_check(ctx)
+    P.compare_cascade(f"wide{rows}", ex, tok, Hout, full[0], full[2], full[3], tau, [])
+    assert int(nev.item()) == int((ex.long() + 1).sum().item())
+    # verification of the same rows as one draft row of rows - 1 tokens (final head)
+    k = rows - 1
+    fin = n - 1
+    f_final = hid.h[fin].reshape(1, rows, w.d).contiguous()
+    target_o = full[2][fin]                                          # the oracle's argmax per position
+    draft = torch.tensor(target_o[:k].reshape(1, k), dtype=torch.int32, device=DEV)
+    if k >= 3:
+        draft[0, k // 2] = (int(target_o[k // 2]) + 1) % w.V          # first mismatch in the middle
+    acc = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    tgt = torch.full((rows,), -7, dtype=torch.int32, device=DEV)
+    B.dssd_verify(ctx, f_final, draft, None, acc, nxt, tgt)
+    torch.cuda.synchronize()
+    B.eh_check(ctx)
+    near = full[3][fin] < P.NEAR_TIE
+    assert all(int(tgt[i]) == int(target_o[i]) or near[i] for i in range(rows))
+    if not near.any():
+        want = k // 2 if k >= 3 else k
+        assert int(acc.item()) == want and int(nxt.item()) == int(target_o[want])
+    # the persistent kernel, not the launch-per-head path: only it can give up
+    B.eh_set_spin_limit(ctx, 0)
+    gave_up = 0
+    for _ in range(3):
+        B.eh_cascade(ctx, hid.h, rows, ex, tok, None, None)
+        try:
+            B.eh_check(ctx)
+        except B.EhError:
+            gave_up += 1
+    assert gave_up >= 1
+    B.eh_set_spin_limit(ctx, 1 << 22)
+    ex2 = torch.full((rows,), -7, dtype=torch.int32, device=DEV)
+    tok2 = torch.full((rows,), -7, dtype=torch.int32, device=DEV)
+    B.eh_cascade(ctx, hid.h, rows, ex2, tok2, None, None)
+    torch.cuda.synchronize()
+    B.eh_check(ctx)
+    P.compare_cascade(f"wide{rows}b", ex2, tok2, None, full[0], full[2], full[3], tau, [])
+    B.eh_destroy(ctx)
