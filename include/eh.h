@@ -257,7 +257,8 @@ eh_status dssd_verify(eh_ctx* ctx, const void* f_final, const int32_t* draft,
  *               the reason is EH_DRAFT_FALLBACK
  * n_evals_out   NULL or device int64, incremented by the (position, head)
  *               evaluations performed
- * Needs the single-row kernel (heads without a bias vector); EH_ERR_DTYPE otherwise.
+ * Needs one of the single-launch cascade kernels (heads without a bias vector; fp32
+ * heads up to d = 1024); EH_ERR_DTYPE otherwise.
  */
 enum { EH_DRAFT_LIMIT = 0, EH_DRAFT_EOS = 1, EH_DRAFT_FALLBACK = 2, EH_DRAFT_EXHAUSTED = 3 };
 eh_status dssd_draft(eh_ctx* ctx, const void* h_positions, int64_t pos_stride, int64_t layer_stride,

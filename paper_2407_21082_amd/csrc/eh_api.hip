@@ -717,8 +717,10 @@ eh_status dssd_draft(eh_ctx* ctx, const void* h_positions, int64_t pos_stride, i
   if (limit < 0 || n_positions < 0) return fail(ctx, EH_ERR_SHAPE, "limit and n_positions must be non-negative");
   if (!draft_len || (limit > 0 && (!draft || !exit_layers))) return fail(ctx, EH_ERR_NULL, "a required pointer is NULL");
   if (n_positions > 0 && limit > 0 && !h_positions) return fail(ctx, EH_ERR_NULL, "h_positions is NULL");
-  if (ctx->decode_grid <= 0)
-    return fail(ctx, EH_ERR_DTYPE, "drafting needs the single-row decode kernel (no bias vector, d within its limit)");
+  const bool by_rows = ctx->decode_grid <= 0 && use_rows(ctx, 1);  // hidden sizes above the decode kernel's
+  if (ctx->decode_grid <= 0 && !by_rows)
+    return fail(ctx, EH_ERR_DTYPE, "drafting needs a single-launch cascade kernel (bf16 or fp32 heads without a bias "
+                                   "vector; fp32 up to d = 1024)");
   if (ctx->n_heads < 2) return fail(ctx, EH_ERR_RANGE, "drafting needs at least one exit head besides the model's");
   const int esz = ctx->dtype == EH_BF16 ? 2 : 4;
   const int steps = n_positions < limit ? n_positions : limit;
@@ -734,7 +736,20 @@ eh_status dssd_draft(eh_ctx* ctx, const void* h_positions, int64_t pos_stride, i
   int* ex = ctx->active[0];          // the current position's exit layer and token
   int* tk = ctx->active[1];
   hipLaunchKernelGGL(draft_init_kernel, dim3(1), dim3(64), 0, s, state, limit, exit_layers);
-  for (int t = 0; t < steps; ++t) {
+  for (int t = 0; t < steps && by_rows; ++t) {
+    RowsParams p = rows_base(ctx, 1);
+    p.h = (const char*)h_positions + (int64_t)t * pos_stride * esz;
+    p.layer_stride = layer_stride;
+    p.row_stride = ctx->d;
+    p.l0 = 0; p.l1 = ctx->n_heads; p.mode = 0; p.argmax_only = 0;
+    p.live = state;  // 1 while drafting, 0 once it has stopped: both launches then return at once
+    p.exit_layer = ex; p.token = tk; p.H_out = nullptr;
+    p.n_evals = (unsigned long long*)n_evals_out;
+    EH_HIP(ctx, rows_launch(ctx, p, s));
+    hipLaunchKernelGGL(draft_step_kernel, dim3(1), dim3(1), 0, s, state, ex, tk, ctx->n_heads - 1, limit, eos_token,
+                       draft, exit_layers);
+  }
+  for (int t = 0; t < steps && !by_rows; ++t) {
     DecodeParams p = decode_base(ctx);
     p.h = (const char*)h_positions + (int64_t)t * pos_stride * esz;
     p.layer_stride = layer_stride;

@@ -1388,6 +1388,7 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel_rows(const
   EH_LDS char* lds = (EH_LDS char*)g32_smem;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (p.live && *(volatile const int*)p.live == 0) return;  // the same word for every workgroup: all or none
   if (p.mode == 1) {
     // A verification has no preset launch in front of it.  Its results start as "not done" (the
     // thread that writes them here is the one that writes the real ones later), and the last
@@ -1415,7 +1416,8 @@ __global__ __launch_bounds__(kG32Threads, 1) void gemm32_stats_kernel_rows(const
 
 // Presets of a cascade launch: the control block to zero, the outputs to "not decided".
 __global__ void rows_preset_kernel(int* __restrict__ ctl, int n_ctl, int* __restrict__ exit_layer, int* __restrict__ token,
-                                   int n_rows, float* __restrict__ H_out, int n_H) {
+                                   int n_rows, float* __restrict__ H_out, int n_H, const int* __restrict__ live) {
+  if (live && *live == 0) return;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n_ctl) ctl[i] = 0;
   if (i < n_rows) { exit_layer[i] = -1; token[i] = -1; }
@@ -1530,7 +1532,7 @@ hipError_t rows_launch(const eh_ctx* c, const RowsParams& p, hipStream_t s) {
     const int n_H = p.H_out ? p.n_heads * p.n_rows : 0;
     const int n = std::max(std::max(n_ctl, n_H), p.n_rows);
     hipLaunchKernelGGL(rows_preset_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p.ctl, n_ctl, p.exit_layer, p.token,
-                       p.n_rows, p.H_out, n_H);
+                       p.n_rows, p.H_out, n_H, p.live);
   }
   if (p.argmax_only)
     hipLaunchKernelGGL((gemm32_stats_kernel_rows<true>), dim3(c->rows_grid), dim3(kG32Threads), g32_lds_bytes(), s, p);

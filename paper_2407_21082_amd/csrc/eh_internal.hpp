@@ -121,6 +121,7 @@ struct RowsParams {
   int n_stream;                 // workgroups that stream weights; the rest of the grid serves
   int spin_limit;
   int* ctl;                     // control block, all zero at launch
+  const int* live;              // NULL, or a device word: the launch does nothing if it reads 0 (a draft that has stopped)
   int* ctl_next;                // verification: the block of the next launch, cleared by this one (else NULL)
   int n_ctl_next;
   frag_t* y;                    // [l1 - l0][y_stride]: one buffer per head of the launch
