@@ -943,3 +943,70 @@ def test_dssd_draft_decode_shape(B):
     print(f"draft windows checked {checked}, skipped for near-ties {skipped}")
     assert checked >= n_win - 2
     B.eh_destroy(ctx)
+
+
+@pytest.mark.parametrize("kind", ["uniform", "few_values", "wide_range", "rounded", "signed_and_infinite", "narrow"])
+def test_calibrate_random_sets_against_the_definition(B, small_ctx, kind):
+    """Many small seeded sets of every shape the key range can take (a few distinct values, one
+    binade, forty decades, negative and infinite 'entropies', which the interface does not
+    forbid), each against the oracle's literal quadratic definition, bit for bit."""
+    rng = np.random.default_rng({"uniform": 1, "few_values": 2, "wide_range": 3, "rounded": 4,
+                                 "signed_and_infinite": 5, "narrow": 6}[kind])
+    for trial in range(25):
+        M = int(rng.integers(1, 500))
+        if kind == "uniform":
+            H = rng.uniform(0, 8, M)
+        elif kind == "few_values":
+            H = rng.choice(rng.uniform(0, 8, int(rng.integers(1, 7))), M)
+        elif kind == "wide_range":
+            H = np.abs(rng.normal(0, 1, M)) * 10.0 ** rng.integers(-20, 20, M)
+        elif kind == "rounded":
+            H = np.round(rng.uniform(0, 4, M), 1)
+        elif kind == "signed_and_infinite":
+            H = rng.normal(0, 3, M)
+            H[rng.random(M) < 0.05] = np.inf
+            H[rng.random(M) < 0.05] = -np.inf
+            H[rng.random(M) < 0.05] = 0.0
+            H[rng.random(M) < 0.05] = -0.0
+        else:
+            H = 3.0 + rng.integers(0, 300, M) * 2.0 ** -21         # a few hundred neighbouring floats
+        H = H.astype(np.float32)
+        if trial % 5 == 0:
+            H[rng.integers(0, M)] = np.nan
+        finite = np.where(np.isfinite(H), H, 0.0)
+        p = rng.uniform(0.2, 0.95)
+        ok = rng.random(M) < np.clip(p + 0.3 * (finite < np.median(finite)), 0, 1)
+        ref = np.ones(M, np.int32)
+        pred = np.where(ok, 1, 2).astype(np.int32)
+        eps = [0.0, 0.5, 0.7, 0.9, 1.0, float(rng.uniform(0, 1)), float(rng.uniform(0, 1))]
+        tau, n = _calibrate(B, small_ctx, torch.tensor(H, device=DEV), torch.tensor(pred, device=DEV),
+                            torch.tensor(ref, device=DEV), eps)
+        Hc = H.astype(np.float64)
+        for i, e in enumerate(eps):
+            want_tau, want_n = O.calibrate_threshold(Hc, ok, e)
+            same = (tau[i] == np.float32(want_tau)) or (np.isneginf(tau[i]) and np.isneginf(want_tau))
+            assert same and int(n[i]) == want_n, (kind, trial, M, e, tau[i], want_tau, n[i], want_n)
+
+
+def test_calibrate_data_that_cannot_be_pruned_is_sorted(B, small_ctx):
+    """Distinct entropies with predictions alternately wrong and right in order of entropy: the
+    proportion among the c most confident tokens is 1/2 for even c and just under it for odd c.
+    At a level a hair above 1/2 no threshold qualifies, but no bin of any level can be ruled
+    out from its counts either (its bound lies above the level), so the tables of kept bins
+    overflow and the call must notice and sort; at 1/2 itself the very top qualifies and the
+    counting answers at once.  Both answers are checked, and which way each call went."""
+    M = 1 << 16
+    H = (torch.arange(M, device=DEV, dtype=torch.float32) * 1e-4 + 0.25)[torch.randperm(
+        M, generator=torch.Generator(device="cpu").manual_seed(5)).to(DEV)].contiguous()
+    rank = torch.argsort(torch.argsort(H))                              # position in ascending entropy
+    ref = torch.zeros(M, dtype=torch.int32, device=DEV)
+    pred = (1 - (rank % 2)).to(torch.int32)                             # even rank: wrong (1 != 0), odd: right
+    Hc = H.cpu().numpy().astype(np.float64)
+    t = O.correctness(pred.cpu().numpy(), ref.cpu().numpy())
+    for eps, sorts in (([0.5], 0), ([0.5000001], 1), ([0.5, 0.5000001, 0.3], 1)):
+        before = B.eh_probe_calibrate_sorted(small_ctx)
+        tau, n = _calibrate(B, small_ctx, H, pred, ref, eps)
+        assert B.eh_probe_calibrate_sorted(small_ctx) - before == sorts, eps
+        for i, (want_tau, want_n) in enumerate(_calibrate_by_counting(Hc, t, eps)):
+            assert tau[i] == want_tau and n[i] == want_n, (eps[i], tau[i], want_tau, n[i], want_n)
+    assert np.isneginf(_calibrate(B, small_ctx, H, pred, ref, [0.5000001])[0][0])
