@@ -550,3 +550,36 @@ def test_few_rows_of_a_wide_model_run_the_persistent_cascade(B, rows):
     B.eh_check(ctx)
     P.compare_cascade(f"wide{rows}b", ex2, tok2, None, full[0], full[2], full[3], tau, [])
     B.eh_destroy(ctx)
+
+
+# ------------------------------------------------------------------ every block layout of the rows kernel
+@pytest.mark.parametrize("rows", [17, 33, 97, 129, 161, 193, 225, 256])
+def test_cascade_across_block_layouts(B, rows):
+    """1 to 8 blocks of 32 rows on the four waves of the kernel for 17 .. 256 rows (no block, one
+    or two per wave), shrinking from head to head as rows leave on the 10 / 40 / 70 % schedule, so
+    that the layout changes inside one launch; the oracle on every row, and the same launch
+    twice for a bitwise repeat (the list of live rows is built through atomics)."""
+    w = G.Workload("blocks", d=160, V=2500, n_heads=7, rows=rows, dtype="bf16", seed=900 + rows, kappa=0.6)
+    heads = G.make_heads(w, DEV)
+    hid = G.make_hidden(w, heads, DEV)
+    n = w.n_heads
+    full = P.oracle_all_heads(heads, hid.h, True)
+    tau = G.tau_for_schedule(full[0], n)
+    ctx = B.eh_create(heads.W, heads.gamma, heads.beta, tau, max_rows=rows)
+    outs = []
+    for _ in range(2):
+        ex = torch.full((rows,), -7, dtype=torch.int32, device=DEV)
+        tok = torch.full((rows,), -7, dtype=torch.int32, device=DEV)
+        Hout = torch.zeros((n, rows), device=DEV)
+        nev = torch.zeros(1, dtype=torch.int64, device=DEV)
+        B.eh_cascade(ctx, hid.h, rows, ex, tok, Hout, nev)
+        torch.cuda.synchronize()
+        B.eh_check(ctx)
+        outs.append((ex, tok, Hout, nev))
+    ex, tok, Hout, nev = outs[0]
+    P.compare_cascade(f"blocks{rows}", ex, tok, Hout, full[0], full[2], full[3], tau, [])
+    assert int(nev.item()) == int((ex.long() + 1).sum().item())
+    assert len(set(ex.tolist())) >= 4
+    assert torch.equal(ex, outs[1][0]) and torch.equal(tok, outs[1][1])
+    assert torch.equal(Hout.view(torch.int32), outs[1][2].view(torch.int32))
+    B.eh_destroy(ctx)

@@ -598,10 +598,12 @@ def test_eval_heads_metrics_tie_at_the_top_and_refusals(B):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("Bsz,k", [(5, 4), (3, 2), (7, 9)])
+@pytest.mark.parametrize("Bsz,k", [(5, 4), (3, 2), (7, 9), (9, 16), (4, 49), (8, 31), (2, 127), (40, 5)])
 def test_dssd_verify_small(B, dtype, Bsz, k):
     """Verification on small shapes: with and without draft lengths, with and without the
-    target output, through the decode kernel (at most 16 positions) and the batched one."""
+    target output, through the decode kernel (at most 16 positions), the persistent kernel for up
+    to 256 positions (1 to 8 blocks of 32; a draft longer than one wave's 64 positions; more draft
+    rows than a wave) and the batched one (fp32)."""
     w = G.Workload("verify", d=128, V=900, n_heads=2, rows=Bsz * (k + 1), dtype=dtype, seed=Bsz * 10 + k)
     heads = G.make_heads(w, DEV)
     gen = torch.Generator(device="cpu")
