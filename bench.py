@@ -384,19 +384,26 @@ def bench_losses(args, torch, B, G, dev):
 
 def timed(torch, step, steps, warmup):
     """warmup untimed steps, then `steps` timed ones between HIP events on the launch stream
-    (and the host clock around the same region).  Returns (host seconds, event seconds)."""
+    (and the host clock around the same region).  Returns (host seconds, event seconds); the
+    median, minimum and maximum time of a step, from an event behind every step, are left in
+    timed.step_ms."""
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(steps):
+    evs[0].record()
+    for i in range(steps):
         step()
-    ev1.record()
+        evs[i + 1].record()
     torch.cuda.synchronize()
-    return time.perf_counter() - t0, ev0.elapsed_time(ev1) * 1e-3
+    host_s = time.perf_counter() - t0
+    per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(steps))
+    timed.step_ms = {"median": per[len(per) // 2], "min": per[0], "max": per[-1]}
+    return host_s, evs[0].elapsed_time(evs[-1]) * 1e-3
+
+
+timed.step_ms = None
 
 
 def oracle_rate(run_some, seconds):
@@ -460,7 +467,7 @@ def run_c1(args, torch, B, G, dev, steps, warmup, cpu_leg, ceiling):
                        f"{n_dec} decode steps per bench step, exit at first H<tau",
            "decode_steps": n_dec, "mean_evals_per_decode_step": evals / launches,
            "mean_exit_layer": float(ex.float().mean().item())}
-    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "step_ms": timed.step_ms, "roofline": roof, "config": cfg, "dtype": w.dtype,
            "cpu_baseline": None}
     if ceiling:
         res["read_ceiling"] = read_ceiling(torch, B, ctx, w, dev)
@@ -541,7 +548,7 @@ def run_c2(args, torch, B, G, dev, steps, warmup, cpu_leg):
             "flops_per_launch": flops_per_launch, "launches": launches}
     cfg = {"workload": "c2_calib: d=2048 V=50304 24 heads x 512 tokens bf16, all heads on all tokens"
                        + (", with max-probability and top-2 difference" if args.metrics else "")}
-    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "step_ms": timed.step_ms, "roofline": roof, "config": cfg, "dtype": w.dtype,
            "cpu_baseline": None, "us_per_head": avg_s * 1e6}
     if cpu_leg:
         res["cpu_baseline"] = cpu_head_evals(args, G, heads, ((l, hid.h[l][:128]) for l in range(w.n_heads)),
@@ -598,7 +605,7 @@ def run_c3(args, torch, B, G, dev, steps, warmup, cpu_leg, keep=None):
                        "compaction between heads",
            "mean_evals_per_cascade": evals / steps,
            "exited_by_layer_8_16_24": [float((exl < l).mean()) for l in (8, 16, 24)]}
-    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "step_ms": timed.step_ms, "roofline": roof, "config": cfg, "dtype": w.dtype,
            "cpu_baseline": None, "us_per_head": avg_s * 1e6}
     if cpu_leg:
         # head by head on the rows this run's cascade kept alive up to that head
@@ -659,7 +666,7 @@ def run_c4(args, torch, B, G, dev, steps, warmup, cpu_leg, heads=None):
     B.dssd_tally(ctxs[0], None, acc, Bsz, k, None, counters)
     cnt = counters.tolist()
     cfg.update(drafted=cnt[1], accepted=cnt[2], wasted=cnt[3], acceptance_rate=cnt[2] / max(cnt[1], 1))
-    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "roofline": roof, "config": cfg, "dtype": w.dtype,
+    res = {"value": evals / dt, "ms_per_step": dt / steps * 1e3, "step_ms": timed.step_ms, "roofline": roof, "config": cfg, "dtype": w.dtype,
            "cpu_baseline": None, "us_per_head": avg_s * 1e6}
     if cpu_leg:
         from oracle import eh_oracle as O
@@ -781,7 +788,7 @@ def main():
 
         def brief(r):
             return {"value": r["value"], "unit": "evals/s", "us_per_head": r["us_per_head"], "steps": bs, "warmup": bw,
-                    "workload": r["config"]["workload"], "roofline": r["roofline"]}
+                    "step_ms": r.get("step_ms"), "workload": r["config"]["workload"], "roofline": r["roofline"]}
 
         batched["c2_calib"] = brief(run_c2(args, torch, B, G, dev, bs, bw, False))
         torch.cuda.empty_cache()
@@ -802,6 +809,7 @@ def main():
 
     line = {"metric": "exit_head_evals_per_sec", "value": res["value"], "unit": "evals/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+            "step_ms": res.get("step_ms"),
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": res["dtype"],
             "data": "synthetic", "config": res["config"], "roofline": res["roofline"], "cpu_baseline": res["cpu_baseline"]}
     line.update(extra)
