@@ -30,6 +30,11 @@
  *     checks that the grids fit the empty device.  Every wait is bounded
  *     (eh_set_spin_limit); a call that gives up sets a flag that eh_check reports
  *     and clears, rows it did not finish read -1 / NaN, and the context stays usable.
+ *     Such a launch also carries a tag (and, for dssd_verify, a choice of control
+ *     block) that the host advances with every call, so these calls must be made
+ *     anew each time: recording one into a HIP graph and replaying the graph is not
+ *     supported.  eh_eval, eh_eval_heads, eh_eval_heads_metrics and eh_exit_decide
+ *     with more than 16 rows, and eh_eval_noalloc with any number, carry no such state.
  */
 #ifndef EH_H_
 #define EH_H_
