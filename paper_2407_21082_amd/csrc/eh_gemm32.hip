@@ -227,11 +227,17 @@ __host__ __device__ constexpr int dma_per_wave(int mt) { return (2 * mt + kG32Wa
 // activations followed by the same NB/2 blocks of the model's (yq2), and a tile only meets
 // the blocks of its own side: accumulator [m][j] and [m + MT/2][j] then hold the two logits
 // of the same (vocabulary row, token) in the same register of the same lane.
-template <int MT, int NB, bool ARGMAX_ONLY, bool TOP2, bool DUAL = false, typename ST = Stats>
+struct NothingBetween {
+  __device__ __forceinline__ void operator()() const {}
+};
+// `between` runs when the k loop is over and nobody reads the ring any more, before the
+// statistics of the pass are worked out: the place to ask for the next pass's first weights, so
+// that the memory system has something to do while this wave computes.
+template <int MT, int NB, bool ARGMAX_ONLY, bool TOP2, bool DUAL = false, typename ST = Stats, typename BT = NothingBetween>
 __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag_t* __restrict__ yq,
                                        int T16, int t16_end, int KS, int row_hi, int lane, int wave,
                                        EH_LDS char* lds, ST (&st)[DUAL ? NB / 2 : NB], long long wdelta = 0,
-                                       const frag_t* __restrict__ yq2 = nullptr) {
+                                       const frag_t* __restrict__ yq2 = nullptr, BT between = BT()) {
   static_assert(!DUAL || (MT % 2 == 0 && NB % 2 == 0), "two equal sides");
   constexpr int NA = DUAL ? NB / 2 : NB;  // accumulator tiles per weight tile
   constexpr int MH = MT / 2, NH = NB / 2;
@@ -441,6 +447,7 @@ __device__ __forceinline__ void pass32(const frag_t* __restrict__ Wf, const frag
       for (int j = 0; j < kDepth; ++j) asm volatile("" ::"v"(b[j][n][h]));
 #pragma unroll
   for (int m = 0; m < MT; ++m) asm volatile("" ::"v"(a[m][0]), "v"(a[m][1]));
+  between();
 
   // accumulator register 4g+i of lane l: vocabulary row 32*tile + 8g + 4*(l/32) + i, token l%32
   const int half = lane >> 5;
@@ -822,9 +829,9 @@ struct RowMask {
 // behind the prologue, one per k-step), but issues nothing else.  Its loads are the DMA pieces
 // only, in pass32's order: at the wait that opens step ks the pieces of steps ks+2 .. ks+D may
 // still be in flight.
-template <int MT>
+template <int MT, typename BT = NothingBetween>
 __device__ __forceinline__ void pass32_idle(const frag_t* __restrict__ Wf, int T16, int t16_end, int KS, int lane,
-                                            int wave, EH_LDS char* lds) {
+                                            int wave, EH_LDS char* lds, BT between = BT()) {
   constexpr int kDma = dma_per_wave(MT);
   constexpr int NF = 2 * MT;
   const int lastk = KS - 1;
@@ -858,22 +865,30 @@ __device__ __forceinline__ void pass32_idle(const frag_t* __restrict__ Wf, int T
     dma(ks + kDepth + 1);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  between();
 }
 
-// The weights of the first kDepth+1 k-steps of a pass, brought into the ring ahead of time by
-// this wave's DMA share (the pass will fetch them again: what this buys is that they then come
-// from the L2 and not from HBM).  Called between passes, when nobody reads the ring; the loads are
-// waited for by the vmcnt(0) that opens the next pass at the latest.
+// The weights of the first kDepth + 1 k-steps of a pass, asked for ahead of time by this wave's DMA
+// share (the pass will fetch them again: what this buys is that they then come from the L2 and
+// not from HBM, and that the memory system has work while the waves compute).  They land in ring
+// slots, which nobody uses for them; the one slot that another wave of the workgroup may still
+// be reading when this is called right behind a k loop -- the operands of that loop's last step,
+// slot (KS - 1) mod 8 -- is left alone.  Waited for by the vmcnt(0) that opens the next pass at
+// the latest.
 template <int MT>
 __device__ __forceinline__ void ring_prefetch(const frag_t* __restrict__ Wf, int T16, int t16_end, int KS, int lane,
                                               int wave, EH_LDS char* lds) {
   constexpr int kDma = dma_per_wave(MT);
   constexpr int NF = 2 * MT;
+  constexpr int kAhead = kDepth + 1;  // k-steps asked for (seven were slower than four)
+  static_assert(kAhead <= kSlots, "one slot per k-step");
   const int lastk = KS - 1;
+  const int busy = lastk & (kSlots - 1);
   const uint32_t lane16 = (uint32_t)lane << 4;
   const EH_GLOBAL char* wbase = uniform_ptr(Wf);
 #pragma unroll
-  for (int ks = 0; ks <= kDepth; ++ks) {
+  for (int ks = 0; ks < kAhead; ++ks) {
+    if (ks == busy) continue;  // uniform
     const int k = min(ks, lastk);
 #pragma unroll
     for (int i = 0; i < kDma; ++i) {
@@ -1029,11 +1044,18 @@ __device__ __forceinline__ bool rows_stream(const RowsParams& p, const RowsCtl& 
       const int left = (T1 - t + 1) >> 1;
       const int passes = (left + kMaxMT - 1) / kMaxMT;
       const int mt = (left + passes - 1) / passes;
+      // behind the head's last k loop, while its statistics are worked out and handed on: the
+      // start of the next head's weights is asked for (towards the L2; the next pass fetches it
+      // again from there), so that this workgroup's share of the memory system does not idle
+      const bool hand_on = t + 2 * mt >= T1 && j + 1 < nh;
+      auto btw = [&]() {
+        if (hand_on) warm(p.Wf[l + 1]);
+      };
 #define EH_ROWS_PASS(MT_)                                                                                     \
-  if (nb_live <= 0) pass32_idle<MT_>(Wf, t, T1, p.KS, lane, wave, lds);                                          \
-  else if (nb_live == 1) pass32<MT_, 1, ARGMAX_ONLY, false>(Wf, ybase, t, T1, p.KS, row_hi, lane, wave, lds,          \
-                                                        reinterpret_cast<Stats(&)[1]>(st[0]));                   \
-  else pass32<MT_, 2, ARGMAX_ONLY, false>(Wf, ybase, t, T1, p.KS, row_hi, lane, wave, lds, st)
+  if (nb_live <= 0) pass32_idle<MT_>(Wf, t, T1, p.KS, lane, wave, lds, btw);                                     \
+  else if (nb_live == 1) pass32<MT_, 1, ARGMAX_ONLY, false, false, Stats>(Wf, ybase, t, T1, p.KS, row_hi, lane, wave, lds, \
+                                                        reinterpret_cast<Stats(&)[1]>(st[0]), 0, nullptr, btw);  \
+  else pass32<MT_, 2, ARGMAX_ONLY, false, false, Stats>(Wf, ybase, t, T1, p.KS, row_hi, lane, wave, lds, st, 0, nullptr, btw)
       switch (mt) {
         case 7: EH_ROWS_PASS(7); break;
         case 6: EH_ROWS_PASS(6); break;
@@ -1057,10 +1079,9 @@ __device__ __forceinline__ bool rows_stream(const RowsParams& p, const RowsCtl& 
       }
     }
     if (j + 1 < nh) {
-      // while those stores travel: warm the L2 with the start of the next head's weights, and look
-      // whether the next head's activations are there (they have been for a while, as a rule).
-      // Heads from the third on carry their column count in the upper bits of the counter.
-      warm(p.Wf[l + 1]);
+      // while those stores travel: look whether the next head's activations are there (they have
+      // been for a while, as a rule).  Heads from the third on carry their column count in the
+      // upper bits of the counter.
       if (wave == 0) {
         const int v = rows_wait(p, c, c.ready(j + 1), nsw, lane, 0xff);
         if (lane == 0) *flag = v;
